@@ -1,0 +1,133 @@
+"""Python face of the C oracle (oracle/rmsnorm_linear_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's CPU-baseline leg, never by the HIP package.  Everything returned
+is float64 and is never rounded to the 16-bit storage type.
+
+Arrays use the storage conventions of the input generators: numpy float16
+for "f16", numpy float32 for "f32", numpy uint16 (upper half of the float32
+bit pattern) for "bf16".
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_DT = {"f16": 0, "bf16": 1, "f32": 2}
+_NP = {"f16": np.float16, "bf16": np.uint16, "f32": np.float32}
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        lib = ctypes.CDLL(path)
+        lib.oracle_decode_f16.restype = ctypes.c_double
+        lib.oracle_decode_f16.argtypes = [ctypes.c_uint16]
+        lib.oracle_decode_bf16.restype = ctypes.c_double
+        lib.oracle_decode_bf16.argtypes = [ctypes.c_uint16]
+        lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_decode.restype = None
+        lib.oracle_decode.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p]
+        lib.oracle_rmsnorm_f64.restype = None
+        lib.oracle_rmsnorm_f64.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double,
+                                           ctypes.c_long, ctypes.c_long, ctypes.c_void_p]
+        lib.oracle_matmul_f64.restype = None
+        lib.oracle_matmul_f64.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_long,
+                                          ctypes.c_long, ctypes.c_long, ctypes.c_void_p]
+        lib.oracle_rmsnorm_linear.restype = ctypes.c_int
+        lib.oracle_rmsnorm_linear.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                              ctypes.c_int, ctypes.c_double, ctypes.c_long,
+                                              ctypes.c_long, ctypes.c_long, ctypes.c_void_p,
+                                              ctypes.c_long, ctypes.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    """Threads the oracle's OpenMP loops will use."""
+    return int(_load().oracle_num_threads())
+
+
+def _storage(a, dtype):
+    a = np.ascontiguousarray(a)
+    if a.dtype != _NP[dtype]:
+        raise TypeError(f"{dtype} arrays must be numpy {_NP[dtype].__name__}, got {a.dtype}")
+    return a
+
+
+def decode(a, dtype: str) -> np.ndarray:
+    """Widen a storage array to float64 with the oracle's own decoders."""
+    a = _storage(a, dtype)
+    out = np.empty(a.shape, dtype=np.float64)
+    _load().oracle_decode(a.ctypes.data, _DT[dtype], a.size, out.ctypes.data)
+    return out
+
+
+def decode_f16_scalar(bits: int) -> float:
+    return float(_load().oracle_decode_f16(int(bits) & 0xFFFF))
+
+
+def decode_bf16_scalar(bits: int) -> float:
+    return float(_load().oracle_decode_bf16(int(bits) & 0xFFFF))
+
+
+def rmsnorm_f64(x, g, eps: float) -> np.ndarray:
+    """Eq. 1 on float64 arrays: x [M,K], g [K] -> [M,K]."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    g = np.ascontiguousarray(g, dtype=np.float64)
+    M, K = x.shape
+    assert g.shape == (K,)
+    out = np.empty((M, K), dtype=np.float64)
+    _load().oracle_rmsnorm_f64(x.ctypes.data, g.ctypes.data, float(eps), M, K, out.ctypes.data)
+    return out
+
+
+def matmul_f64(a, w) -> np.ndarray:
+    """Plain float64 product: a [M,K] @ w [K,N]."""
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    M, K = a.shape
+    K2, N = w.shape
+    assert K == K2
+    z = np.empty((M, N), dtype=np.float64)
+    _load().oracle_matmul_f64(a.ctypes.data, w.ctypes.data, M, K, N, z.ctypes.data)
+    return z
+
+
+def rmsnorm_linear(X, g, W, dtype: str, eps: float, rows=None) -> np.ndarray:
+    """The whole block on storage-typed inputs; returns float64 [len(rows), N].
+
+    `eps` is taken as given (pass the float32-rounded value the GPU receives).
+    `rows` defaults to every row of X.
+    """
+    X = _storage(X, dtype)
+    g = _storage(g, dtype)
+    W = _storage(W, dtype)
+    M, K = X.shape
+    K2, N = W.shape
+    if K2 != K or g.shape != (K,):
+        raise ValueError("shape mismatch")
+    rows = np.arange(M, dtype=np.int64) if rows is None else np.ascontiguousarray(rows, dtype=np.int64)
+    Z = np.empty((len(rows), N), dtype=np.float64)
+    rc = _load().oracle_rmsnorm_linear(X.ctypes.data, g.ctypes.data, W.ctypes.data, _DT[dtype],
+                                       float(eps), M, K, N, rows.ctypes.data, len(rows),
+                                       Z.ctypes.data)
+    if rc != 0:
+        raise RuntimeError("oracle_rmsnorm_linear rejected its arguments")
+    return Z
+
+
+def rmsnorm(X, g, dtype: str, eps: float) -> np.ndarray:
+    """Eq. 1 on storage-typed inputs; float64 [M,K] (unfused A/B leg)."""
+    return rmsnorm_f64(decode(X, dtype), decode(g, dtype), eps)
+
+
+def matmul(A, W, dtype: str) -> np.ndarray:
+    """Plain product on storage-typed inputs; float64 [M,N] (unfused A/B leg)."""
+    return matmul_f64(decode(A, dtype), decode(W, dtype))
