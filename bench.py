@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused RMSNorm + MatMul hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode] [--variant auto]
+
+A step is one rmsnorm_linear call (stage W and X, X (.) g, sum of squares, contraction, split-K
+reduce, row scale, store) on one seeded synthetic batch.  The default workload is the decode
+projection (X 1x4096, W 4096x4096, bf16), the HBM-bound configuration the headline metric is quoted
+on; --workload selects another of the five configurations.  Inputs are resident in HBM before the
+timed region.  So that a small W is not simply served from the 256 MB Infinity Cache, steps rotate
+through enough distinct copies of (X, g, W, Y) to exceed 512 MiB; the same-buffer ("warm") rate is
+reported beside it.  The K timed steps are enqueued as one HIP graph on the current stream and are
+bracketed by HIP events on that stream, so elapsed / K approaches the kernel's own duration.
+
+Prints ONE JSON line.  `roofline` prices the dominant kernel against the published MI355X peak;
+`cpu_baseline` is the fp64 CPU oracle timed on this machine's host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = 2500.0        # MI355X dense bf16/fp16 matrix, published (2.5 PFLOP/s)
+ROTATE_BYTES = 512 << 20
+
+
+def _time_region(fn_enqueue, torch):
+    """Events on the current stream around fn_enqueue(); returns (event ms, wall ms)."""
+    start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    start.record()
+    fn_enqueue()
+    end.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3
+    return start.elapsed_time(end), wall
+
+
+def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=True):
+    import workloads
+    from tests.util import compare, to_device, to_host_f64
+
+    w = workloads.config(name)
+    tdt = {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}[w.dtype]
+    abytes = w.algorithmic_bytes
+    copies = max(1, min(steps, -(-ROTATE_BYTES // abytes)))
+    if name == "prefill":
+        copies = 2
+    X0, g0, W0 = to_device(w.X, w.dtype), to_device(w.g, w.dtype), to_device(w.W, w.dtype)
+    Xs, gs, Ws, Ys = [X0], [g0], [W0], [torch.empty((w.M, w.N), dtype=tdt, device="cuda")]
+    for _ in range(copies - 1):
+        Xs.append(X0.clone()); gs.append(g0.clone()); Ws.append(W0.clone()); Ys.append(torch.empty_like(Ys[0]))
+
+    rl.rl_set_variant(variant)
+
+    def step(i):
+        j = i % copies
+        rl.rmsnorm_linear(Xs[j], gs[j], Ws[j], w.eps, Ys[j])
+
+    for i in range(max(warmup, 1)):
+        step(i)
+    torch.cuda.synchronize()
+    used = rl.rl_last_variant()
+
+    def make_runner(step_fn):
+        if use_graph:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for i in range(steps):
+                    step_fn(i)
+            graph.replay()                       # one untimed replay
+            torch.cuda.synchronize()
+            return graph.replay
+        return lambda: [step_fn(i) for i in range(steps)]
+
+    cold = make_runner(step)
+    ev_ms, wall_ms = min((_time_region(cold, torch) for _ in range(3)), key=lambda t: t[0])
+    warm = make_runner(lambda i: rl.rmsnorm_linear(Xs[0], gs[0], Ws[0], w.eps, Ys[0]))
+    warm_ms, _ = min((_time_region(warm, torch) for _ in range(3)), key=lambda t: t[0])
+
+    # the unfused pair from the same library, same rotation, for the fusion gain on this hardware
+    Xn = [torch.empty_like(x) for x in Xs]
+
+    def pair(i):
+        j = i % copies
+        rl.rmsnorm(Xs[j], gs[j], w.eps, Xn[j])
+        rl.matmul(Xn[j], Ws[j], Ys[j])
+
+    pair(0)
+    torch.cuda.synchronize()
+    pair_ms, _ = min((_time_region(make_runner(pair), torch) for _ in range(3)), key=lambda t: t[0])
+
+    parity = None
+    if check:
+        import oracle
+        step(0)
+        torch.cuda.synchronize()
+        rows = torch.from_numpy(w.check_rows).cuda()
+        Y = to_host_f64(Ys[0][rows], w.dtype)
+        Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps, rows=w.check_rows)
+        parity, _ = compare(Y, Z, w.dtype, name)
+    rl.rl_set_variant("auto")
+
+    per_step_ms = ev_ms / steps
+    mem_bound = w.M <= 64
+    res = {
+        "workload": name, "M": w.M, "K": w.K, "N": w.N, "dtype": w.dtype, "variant": used,
+        "copies_rotated": copies, "us_per_step": per_step_ms * 1e3,
+        "us_per_step_warm": warm_ms / steps * 1e3, "us_per_step_unfused_pair": pair_ms / steps * 1e3,
+        "wall_us_per_step": wall_ms / steps * 1e3,
+        "TBps": abytes / (per_step_ms * 1e-3) / 1e12, "TBps_warm": abytes / (warm_ms / steps * 1e-3) / 1e12,
+        "TFLOPs": w.flops / (per_step_ms * 1e-3) / 1e12,
+        "algorithmic_bytes": abytes, "flops": w.flops,
+        "max_err_over_rmsY": parity,
+    }
+    if mem_bound:
+        res["roofline_frac"] = res["TBps"] * 1e3 / HBM_PEAK_GBS
+    else:
+        res["roofline_frac"] = res["TFLOPs"] / MFMA_PEAK_TFLOPS
+    return res, w
+
+
+def cpu_baseline(w, mem_bound, budget_s=12.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
+    import oracle
+    rows = w.check_rows if w.M > 64 else np.arange(w.M)
+    reps, t_total = 0, 0.0
+    t_start = time.perf_counter()
+    while True:
+        t0 = time.perf_counter()
+        oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps, rows=rows)
+        t_total += time.perf_counter() - t0
+        reps += 1
+        if time.perf_counter() - t_start > budget_s or reps >= 200:
+            break
+    sec = t_total / reps
+    frac = len(rows) / w.M
+    if mem_bound:
+        value, unit = w.algorithmic_bytes / sec / 1e12, "TB/s"
+    else:
+        value, unit = 2.0 * len(rows) * w.K * w.N / sec / 1e12, "TFLOP/s"
+    return {"value": value, "unit": unit, "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{reps} run(s) of the fp64 oracle on {len(rows)} of {w.M} rows "
+                      f"({frac:.3g} of the workload), {sec:.3f} s each",
+            "seconds_per_run": sec}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="decode")
+    ap.add_argument("--variant", default="auto")
+    ap.add_argument("--no-graph", action="store_true", help="enqueue the timed steps one by one")
+    ap.add_argument("--others", action="store_true", help="also time the other four configurations")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (sharding is design-only, see DESIGN.md)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    import paper_2405_05751_amd as rl
+    rl.lib()                                      # fail loudly if the HIP library is not built
+
+    name = args.workload
+    steps = args.steps if args.steps is not None else (20 if name == "prefill" else 200)
+    res, w = run_workload(rl, torch, name, steps, args.warmup, args.variant, use_graph=not args.no_graph)
+    mem_bound = w.M <= 64
+    if mem_bound:
+        metric, unit, value = "fused RMSNorm+MatMul TB/s", "TB/s", res["TBps"]
+        roof = {"bound": "hbm", "achieved": res["TBps"] * 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        metric, unit, value = "fused RMSNorm+MatMul TFLOP/s", "TFLOP/s", res["TFLOPs"]
+        roof = {"bound": "mfma", "achieved": res["TFLOPs"], "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = res["variant"]
+    roof["us_per_launch"] = res["us_per_step"]
+
+    out = {
+        "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": res["us_per_step"] / 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{name}: X {w.M}x{w.K}, W {w.K}x{w.N}, {w.dtype}", "variant": res["variant"],
+                   "copies_rotated": res["copies_rotated"], "graph": not args.no_graph},
+        "roofline": roof,
+        "detail": res,
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w, mem_bound)
+    if args.others:
+        import workloads
+        others = []
+        for other in workloads.CONFIG_NAMES:
+            if other == name:
+                continue
+            r, _ = run_workload(rl, torch, other, 20 if other == "prefill" else 200, args.warmup, args.variant,
+                                use_graph=not args.no_graph)
+            others.append(r)
+        out["other_workloads"] = others
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

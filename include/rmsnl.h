@@ -1,0 +1,127 @@
+/*
+ * rmsnl - RMSNorm-then-linear for AMD MI355X (gfx950), C ABI.
+ *
+ * All pointers named X, g, W, Y, Xn, A are DEVICE pointers (HIP global memory on the
+ * current device) owned by the caller; the library reads or writes them on the given
+ * stream and never frees or keeps them.  `stream` is a hipStream_t passed as void*
+ * (NULL = the default stream).  Every entry point only enqueues work and returns; it
+ * performs no host synchronisation.  Matrices are dense and row-major:
+ *
+ *     X [M][K]   activations        g [K]      gain
+ *     W [K][N]   weight, N fastest  Y [M][N]   output
+ *
+ * Element type is selected by rl_dtype and is the same for all arrays of a call:
+ * 16-bit types are accumulated in fp32 and rounded once (nearest-even) when stored.
+ * Y must not overlap X, g or W.  Pointers must be aligned to 16 bytes.
+ *
+ * Errors: every function returns an rl_status; nothing throws or aborts.  Argument
+ * checks run before the first HIP call.  rl_last_error() returns a thread-local
+ * message for the most recent non-OK status on the calling thread.
+ */
+#ifndef RMSNL_H
+#define RMSNL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+#pragma GCC visibility push(default)
+
+typedef enum {
+    RL_OK = 0,
+    RL_ERR_INVALID_ARG = 1,   /* null / misaligned pointer, size < 1 or >= 2^31, bad enum, eps < 0 or not finite */
+    RL_ERR_UNSUPPORTED = 2,   /* a forced variant cannot run this shape or type */
+    RL_ERR_HIP = 3,           /* a HIP runtime call failed; text in rl_last_error() */
+    RL_ERR_WORKSPACE = 4      /* caller-provided workspace too small */
+} rl_status;
+
+typedef enum { RL_F16 = 0, RL_BF16 = 1, RL_F32 = 2 } rl_dtype;
+
+typedef enum {
+    RL_AUTO = 0,          /* pick by shape */
+    RL_GEMV_SPLITK = 1,   /* M <= 16, no matrix cores, K split over workgroups */
+    RL_MFMA_SKINNY = 2,   /* M <= 64, matrix cores, K split over the waves of a workgroup */
+    RL_MFMA_TILE = 3,     /* large M: 256x256 output tiles on matrix cores */
+    RL_NAIVE = 4          /* any shape and type, fp32 arithmetic, slow */
+} rl_variant;
+
+/*
+ * Fused RMSNorm + MatMul in one kernel (case-study section: Eq. 1 followed by the
+ * MatMul of Fig. 2a, computed in the reordered form of Fig. 2b):
+ *
+ *     A_i  = sum_k X[i][k]^2                      (accumulated in the same K loop as B)
+ *     B_in = sum_k (X[i][k] * g[k]) * W[k][n]
+ *     Y_in = B_in / sqrt(A_i / K + eps)
+ *
+ * eps is added to the mean square under the root (eps = 0 gives Eq. 1 exactly).
+ * An all-zero row with eps = 0 yields NaN, as the definition does.
+ * May use the library workspace (see rl_set_workspace): calls that overlap in time on
+ * different streams of one device must not both use the split-K variant.
+ */
+rl_status rmsnorm_linear(const void* X, const void* g, const void* W, float eps, void* Y,
+                         int64_t M, int64_t K, int64_t N, rl_dtype dt, void* stream);
+
+/*
+ * Unfused pair, for A/B comparison with the fused call (the two-kernel baseline of
+ * Fig. 2a: the normalised intermediate goes through device memory).
+ *
+ * rmsnorm: Xn[i][k] = X[i][k] * g[k] / sqrt(mean_k X[i][k]^2 + eps), Eq. 1, rounded to dt.
+ * matmul:  Y = A . W with A [M][K], same variants and layout rules as rmsnorm_linear.
+ */
+rl_status rmsnorm(const void* X, const void* g, float eps, void* Xn,
+                  int64_t M, int64_t K, rl_dtype dt, void* stream);
+rl_status matmul(const void* A, const void* W, void* Y,
+                 int64_t M, int64_t K, int64_t N, rl_dtype dt, void* stream);
+
+/*
+ * Variant control (process-wide).  RL_AUTO is the default; the environment variable
+ * RL_VARIANT (auto|gemv|skinny|tile|naive) sets the initial value.  A forced variant that
+ * cannot run a shape makes the call return RL_ERR_UNSUPPORTED instead of falling back.
+ * rl_last_variant() reports what the most recent successful call on this thread ran.
+ */
+rl_status rl_set_variant(rl_variant v);
+rl_variant rl_get_variant(void);
+rl_variant rl_last_variant(void);
+
+/*
+ * Launch-shape overrides for tuning sweeps (process-wide, 0 = automatic):
+ *   n_tile  columns of W per workgroup, k_split  number of K slabs (split-K factor).
+ * Values a variant cannot honour give RL_ERR_UNSUPPORTED at the next call.
+ */
+rl_status rl_set_tuning(int n_tile, int k_split);
+
+/*
+ * Split-K workspace (fp32 partial sums + arrival counters).  By default the library
+ * allocates rl_workspace_default_bytes() once per device on first need and keeps it until
+ * the process ends.  rl_set_workspace lends a caller-owned DEVICE buffer instead (for the
+ * current device; bytes must be >= rl_workspace_bytes() of every later call; the first
+ * 64 KiB must be zero when lent); NULL returns to the library's own buffer.
+ * rl_workspace_bytes gives the bytes a call of that shape needs (0 if none).
+ */
+rl_status rl_set_workspace(void* dev_ptr, size_t bytes);
+size_t rl_workspace_bytes(int64_t M, int64_t K, int64_t N, rl_dtype dt);
+size_t rl_workspace_default_bytes(void);
+
+/*
+ * Measurement helpers (not on the hot path): a plain device-to-device copy kernel of
+ * `bytes` bytes (multiple of 16) used to calibrate memory counters and to measure the
+ * achievable streaming rate, and a register-only matrix-core loop of `iters` iterations
+ * per wave that reports the achievable MFMA rate (writes one float per lane to `sink`,
+ * which must hold rl_probe_mfma_sink_floats() floats).
+ */
+rl_status rl_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
+rl_status rl_probe_read(const void* src, size_t bytes, void* sink, void* stream);
+rl_status rl_probe_mfma(void* sink, int iters, rl_dtype dt, void* stream);
+size_t rl_probe_mfma_sink_floats(void);
+double rl_probe_mfma_flops(int iters);
+
+const char* rl_last_error(void);
+const char* rl_version(void);
+
+#pragma GCC visibility pop
+#ifdef __cplusplus
+}
+#endif
+#endif /* RMSNL_H */

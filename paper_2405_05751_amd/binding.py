@@ -1,0 +1,190 @@
+"""ctypes binding of librmsnl.so: argument marshalling only.
+
+Every function has the name and meaning of its C entry point in include/rmsnl.h.
+Tensors are torch CUDA(HIP) tensors used purely as device buffers; the stream is
+torch's current stream unless one is given.  There is no CPU fallback: if the
+shared library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librmsnl.so")
+
+RL_OK, RL_ERR_INVALID_ARG, RL_ERR_UNSUPPORTED, RL_ERR_HIP, RL_ERR_WORKSPACE = range(5)
+RL_F16, RL_BF16, RL_F32 = range(3)
+RL_AUTO, RL_GEMV_SPLITK, RL_MFMA_SKINNY, RL_MFMA_TILE, RL_NAIVE = range(5)
+VARIANTS = {"auto": RL_AUTO, "gemv": RL_GEMV_SPLITK, "skinny": RL_MFMA_SKINNY,
+            "tile": RL_MFMA_TILE, "naive": RL_NAIVE}
+VARIANT_NAMES = {v: k for k, v in VARIANTS.items()}
+_DTYPES = {torch.float16: RL_F16, torch.bfloat16: RL_BF16, torch.float32: RL_F32}
+
+EXPORTS = {
+    # name: (restype, argtypes)
+    "rmsnorm_linear": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
+                                      ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                      ctypes.c_int, ctypes.c_void_p]),
+    "rmsnorm": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
+                               ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]),
+    "matmul": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                              ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]),
+    "rl_set_variant": (ctypes.c_int, [ctypes.c_int]),
+    "rl_get_variant": (ctypes.c_int, []),
+    "rl_last_variant": (ctypes.c_int, []),
+    "rl_set_tuning": (ctypes.c_int, [ctypes.c_int, ctypes.c_int]),
+    "rl_set_workspace": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t]),
+    "rl_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]),
+    "rl_workspace_default_bytes": (ctypes.c_size_t, []),
+    "rl_probe_copy": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "rl_probe_read": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]),
+    "rl_probe_mfma": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]),
+    "rl_probe_mfma_sink_floats": (ctypes.c_size_t, []),
+    "rl_probe_mfma_flops": (ctypes.c_double, [ctypes.c_int]),
+    "rl_last_error": (ctypes.c_char_p, []),
+    "rl_version": (ctypes.c_char_p, []),
+}
+
+
+class RmsnlError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"rmsnl status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python __graft_entry__.py` (or "
+                              "paper_2405_05751_amd/build.py) to compile the HIP library")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != RL_OK:
+        raise RmsnlError(status, lib().rl_last_error().decode())
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev(t: torch.Tensor, name: str) -> int:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def rmsnorm_linear(X: torch.Tensor, g: torch.Tensor, W: torch.Tensor, eps: float,
+                   Y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    M, K = X.shape
+    K2, N = W.shape
+    if K2 != K or g.shape != (K,) or X.dtype != W.dtype or X.dtype != g.dtype:
+        raise ValueError("shape or dtype mismatch")
+    if Y is None:
+        Y = torch.empty((M, N), dtype=X.dtype, device=X.device)
+    elif Y.shape != (M, N) or Y.dtype != X.dtype:
+        raise ValueError("Y has the wrong shape or dtype")
+    _check(lib().rmsnorm_linear(_dev(X, "X"), _dev(g, "g"), _dev(W, "W"), float(eps), _dev(Y, "Y"),
+                                M, K, N, _DTYPES[X.dtype], _stream(stream)))
+    return Y
+
+
+def rmsnorm(X: torch.Tensor, g: torch.Tensor, eps: float, Xn: Optional[torch.Tensor] = None,
+            stream=None) -> torch.Tensor:
+    M, K = X.shape
+    if g.shape != (K,) or g.dtype != X.dtype:
+        raise ValueError("shape or dtype mismatch")
+    if Xn is None:
+        Xn = torch.empty_like(X)
+    _check(lib().rmsnorm(_dev(X, "X"), _dev(g, "g"), float(eps), _dev(Xn, "Xn"), M, K,
+                         _DTYPES[X.dtype], _stream(stream)))
+    return Xn
+
+
+def matmul(A: torch.Tensor, W: torch.Tensor, Y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    M, K = A.shape
+    K2, N = W.shape
+    if K2 != K or A.dtype != W.dtype:
+        raise ValueError("shape or dtype mismatch")
+    if Y is None:
+        Y = torch.empty((M, N), dtype=A.dtype, device=A.device)
+    _check(lib().matmul(_dev(A, "A"), _dev(W, "W"), _dev(Y, "Y"), M, K, N, _DTYPES[A.dtype],
+                        _stream(stream)))
+    return Y
+
+
+def rl_set_variant(v) -> None:
+    _check(lib().rl_set_variant(VARIANTS[v] if isinstance(v, str) else int(v)))
+
+
+def rl_get_variant() -> str:
+    return VARIANT_NAMES[lib().rl_get_variant()]
+
+
+def rl_last_variant() -> str:
+    return VARIANT_NAMES[lib().rl_last_variant()]
+
+
+def rl_set_tuning(n_tile: int = 0, k_split: int = 0) -> None:
+    _check(lib().rl_set_tuning(int(n_tile), int(k_split)))
+
+
+def rl_set_workspace(buf: Optional[torch.Tensor]) -> None:
+    if buf is None:
+        _check(lib().rl_set_workspace(None, 0))
+    else:
+        _check(lib().rl_set_workspace(_dev(buf, "workspace"), buf.numel() * buf.element_size()))
+
+
+def rl_workspace_bytes(M: int, K: int, N: int, dtype: torch.dtype) -> int:
+    return int(lib().rl_workspace_bytes(M, K, N, _DTYPES[dtype]))
+
+
+def rl_workspace_default_bytes() -> int:
+    return int(lib().rl_workspace_default_bytes())
+
+
+def rl_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(lib().rl_probe_copy(_dev(dst, "dst"), _dev(src, "src"), nbytes, _stream(stream)))
+
+
+def rl_probe_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(lib().rl_probe_read(_dev(src, "src"), nbytes, _dev(sink, "sink"), _stream(stream)))
+
+
+def rl_probe_mfma(sink: torch.Tensor, iters: int, dtype: torch.dtype = torch.bfloat16, stream=None) -> float:
+    """Enqueue the matrix-core loop; returns the flops one launch performs."""
+    if sink.numel() < lib().rl_probe_mfma_sink_floats() or sink.dtype != torch.float32:
+        raise ValueError("sink too small")
+    _check(lib().rl_probe_mfma(_dev(sink, "sink"), int(iters), _DTYPES[dtype], _stream(stream)))
+    return float(lib().rl_probe_mfma_flops(int(iters)))
+
+
+def rl_last_error() -> str:
+    return lib().rl_last_error().decode()
+
+
+def rl_version() -> str:
+    return lib().rl_version().decode()

@@ -1,0 +1,290 @@
+// C ABI of the rmsnl library: argument checks, variant choice, workspace, launch.
+#include "../../include/rmsnl.h"
+#include "common.hpp"
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+
+using namespace rmsnl;
+
+namespace {
+
+constexpr size_t kDefaultWorkspace = size_t(64) << 20;   // partials + counters, per device
+constexpr int kMaxDevices = 16;
+
+thread_local char tl_error[512] = "";
+thread_local rl_variant tl_last_variant = RL_AUTO;
+
+std::mutex g_mu;
+bool g_env_read = false;
+rl_variant g_variant = RL_AUTO;
+int g_n_tile = 0, g_k_split = 0;
+struct Workspace { void* ptr; size_t bytes; bool owned; };
+Workspace g_ws[kMaxDevices] = {};
+Workspace g_lent[kMaxDevices] = {};
+
+rl_status fail(rl_status st, const char* fmt, const char* a = "", const char* b = "")
+{
+    snprintf(tl_error, sizeof tl_error, fmt, a, b);
+    return st;
+}
+
+void read_env_locked()
+{
+    if (g_env_read) return;
+    g_env_read = true;
+    const char* e = getenv("RL_VARIANT");
+    if (!e) return;
+    if (!strcmp(e, "gemv")) g_variant = RL_GEMV_SPLITK;
+    else if (!strcmp(e, "skinny")) g_variant = RL_MFMA_SKINNY;
+    else if (!strcmp(e, "tile")) g_variant = RL_MFMA_TILE;
+    else if (!strcmp(e, "naive")) g_variant = RL_NAIVE;
+    else g_variant = RL_AUTO;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+rl_status check_dims(int64_t M, int64_t K, int64_t N, rl_dtype dt)
+{
+    if (dt != RL_F16 && dt != RL_BF16 && dt != RL_F32) return fail(RL_ERR_INVALID_ARG, "unknown dtype");
+    const int64_t lim = int64_t(1) << 31;
+    if (M < 1 || K < 1 || N < 1 || M >= lim || K >= lim || N >= lim)
+        return fail(RL_ERR_INVALID_ARG, "M, K, N must be in [1, 2^31)");
+    return RL_OK;
+}
+
+// workspace for the current device: the lent buffer if there is one, else the library's own
+rl_status get_workspace(size_t need, Workspace* out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(RL_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(RL_ERR_UNSUPPORTED, "device index out of range");
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (g_lent[dev].ptr) {
+        if (g_lent[dev].bytes < need + kHeadBytes) return fail(RL_ERR_WORKSPACE, "lent workspace too small");
+        *out = g_lent[dev];
+        return RL_OK;
+    }
+    if (!g_ws[dev].ptr) {
+        void* p = nullptr;
+        e = hipMalloc(&p, kDefaultWorkspace);
+        if (e != hipSuccess) return fail(RL_ERR_HIP, "hipMalloc(workspace): %s", hipGetErrorString(e));
+        e = hipMemset(p, 0, kCounterBytes);              // synchronous, once per device
+        if (e != hipSuccess) { (void)hipFree(p); return fail(RL_ERR_HIP, "hipMemset(workspace): %s", hipGetErrorString(e)); }
+        g_ws[dev] = Workspace{p, kDefaultWorkspace, true};
+    }
+    if (g_ws[dev].bytes < need + kHeadBytes)
+        return fail(RL_ERR_WORKSPACE, "shape needs more split-K workspace than the library holds; lend one with rl_set_workspace");
+    *out = g_ws[dev];
+    return RL_OK;
+}
+
+// layout: [arrival counters | partial sums of squares | partial B]
+void carve(const Workspace& ws, Problem& p)
+{
+    char* base = static_cast<char*>(ws.ptr);
+    p.ws_counter = reinterpret_cast<unsigned*>(base);
+    p.ws_sumsq = reinterpret_cast<float*>(base + kCounterBytes);
+    p.ws_partial = reinterpret_cast<float*>(base + kHeadBytes);
+}
+
+rl_variant choose_auto(const Problem& p)
+{
+    if (p.dt == F32) return RL_NAIVE;
+    if (p.N % 8 != 0 || p.K % 8 != 0) return RL_NAIVE;
+    if (p.M <= 4) return RL_GEMV_SPLITK;
+    if (p.M <= 64) return RL_MFMA_SKINNY;
+    return RL_MFMA_TILE;
+}
+
+rl_status run(Problem& p, void* stream)
+{
+    rl_variant forced;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        read_env_locked();
+        forced = g_variant;
+        p.n_tile = g_n_tile;
+        p.k_split = g_k_split;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    rl_variant order[4];
+    int n_order = 0;
+    if (forced != RL_AUTO) {
+        order[n_order++] = forced;
+    } else {
+        p.n_tile = 0;                      // tuning overrides apply to a forced variant only
+        p.k_split = 0;
+        rl_variant first = choose_auto(p);
+        order[n_order++] = first;
+        if (first == RL_MFMA_TILE) order[n_order++] = RL_MFMA_SKINNY;
+        if (first != RL_NAIVE) order[n_order++] = RL_NAIVE;
+    }
+    const char* why = "variant cannot run this shape";
+    for (int i = 0; i < n_order; ++i) {
+        rl_variant v = order[i];
+        hipError_t e = hipErrorInvalidValue;
+        why = "variant cannot run this shape";
+        size_t need = 0;
+        if (v == RL_GEMV_SPLITK) need = gemv_workspace_bytes(p);
+        else if (v == RL_MFMA_SKINNY) need = skinny_workspace_bytes(p);
+        p.ws_partial = nullptr; p.ws_sumsq = nullptr; p.ws_counter = nullptr;
+        if (need) {
+            Workspace ws;
+            rl_status st = get_workspace(need, &ws);
+            if (st != RL_OK) return st;
+            carve(ws, p);
+        }
+        switch (v) {
+        case RL_GEMV_SPLITK: e = launch_gemv(p, s, &why); break;
+        case RL_MFMA_SKINNY: e = launch_skinny(p, s, &why); break;
+        case RL_MFMA_TILE:   e = launch_tile(p, s, &why); break;
+        case RL_NAIVE:       e = launch_naive(p, s, &why); break;
+        default: return fail(RL_ERR_INVALID_ARG, "unknown variant");
+        }
+        if (e == hipSuccess) { tl_last_variant = v; return RL_OK; }
+        if (e != hipErrorInvalidValue) return fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+        (void)hipGetLastError();
+    }
+    return fail(RL_ERR_UNSUPPORTED, "%s", why);
+}
+
+}  // namespace
+
+extern "C" {
+
+rl_status rmsnorm_linear(const void* X, const void* g, const void* W, float eps, void* Y,
+                         int64_t M, int64_t K, int64_t N, rl_dtype dt, void* stream)
+{
+    if (!X || !g || !W || !Y) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (rl_status st = check_dims(M, K, N, dt)) return st;
+    if (!std::isfinite(eps) || eps < 0.f) return fail(RL_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    if (!aligned16(X) || !aligned16(g) || !aligned16(W) || !aligned16(Y))
+        return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    Problem p{};
+    p.X = X; p.g = g; p.W = W; p.Y = Y;
+    p.M = int(M); p.K = int(K); p.N = int(N);
+    p.eps = eps; p.fused = 1; p.dt = DType(dt);
+    return run(p, stream);
+}
+
+rl_status matmul(const void* A, const void* W, void* Y, int64_t M, int64_t K, int64_t N, rl_dtype dt,
+                 void* stream)
+{
+    if (!A || !W || !Y) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (rl_status st = check_dims(M, K, N, dt)) return st;
+    if (!aligned16(A) || !aligned16(W) || !aligned16(Y))
+        return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    Problem p{};
+    p.X = A; p.g = nullptr; p.W = W; p.Y = Y;
+    p.M = int(M); p.K = int(K); p.N = int(N);
+    p.eps = 0.f; p.fused = 0; p.dt = DType(dt);
+    return run(p, stream);
+}
+
+rl_status rmsnorm(const void* X, const void* g, float eps, void* Xn, int64_t M, int64_t K, rl_dtype dt,
+                  void* stream)
+{
+    if (!X || !g || !Xn) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (rl_status st = check_dims(M, K, 1, dt)) return st;
+    if (!std::isfinite(eps) || eps < 0.f) return fail(RL_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    if (!aligned16(X) || !aligned16(g) || !aligned16(Xn))
+        return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    hipError_t e = launch_rmsnorm(X, g, eps, Xn, int(M), int(K), DType(dt), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+    return RL_OK;
+}
+
+rl_status rl_set_variant(rl_variant v)
+{
+    if (v < RL_AUTO || v > RL_NAIVE) return fail(RL_ERR_INVALID_ARG, "unknown variant");
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_env_read = true;
+    g_variant = v;
+    return RL_OK;
+}
+
+rl_variant rl_get_variant(void)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    read_env_locked();
+    return g_variant;
+}
+
+rl_variant rl_last_variant(void) { return tl_last_variant; }
+
+rl_status rl_set_tuning(int n_tile, int k_split)
+{
+    if (n_tile < 0 || k_split < 0) return fail(RL_ERR_INVALID_ARG, "tuning values must be >= 0");
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_n_tile = n_tile;
+    g_k_split = k_split;
+    return RL_OK;
+}
+
+rl_status rl_set_workspace(void* dev_ptr, size_t bytes)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(RL_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(RL_ERR_UNSUPPORTED, "device index out of range");
+    if (dev_ptr && (!aligned16(dev_ptr) || bytes <= kHeadBytes))
+        return fail(RL_ERR_INVALID_ARG, "workspace must be 16-byte aligned and larger than 320 KiB");
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_lent[dev] = Workspace{dev_ptr, dev_ptr ? bytes : 0, false};
+    return RL_OK;
+}
+
+size_t rl_workspace_bytes(int64_t M, int64_t K, int64_t N, rl_dtype dt)
+{
+    if (check_dims(M, K, N, dt) != RL_OK) return 0;
+    Problem p{};
+    p.M = int(M); p.K = int(K); p.N = int(N); p.dt = DType(dt); p.fused = 1;
+    rl_variant v;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        read_env_locked();
+        v = g_variant;
+        if (v != RL_AUTO) { p.n_tile = g_n_tile; p.k_split = g_k_split; }
+    }
+    if (v == RL_AUTO) v = choose_auto(p);
+    size_t need = 0;
+    if (v == RL_GEMV_SPLITK) need = gemv_workspace_bytes(p);
+    else if (v == RL_MFMA_SKINNY) need = skinny_workspace_bytes(p);
+    return need ? need + kHeadBytes : 0;
+}
+
+size_t rl_workspace_default_bytes(void) { return kDefaultWorkspace; }
+
+rl_status rl_probe_copy(void* dst, const void* src, size_t bytes, void* stream)
+{
+    if (!dst || !src || bytes == 0 || bytes % 16 || !aligned16(dst) || !aligned16(src))
+        return fail(RL_ERR_INVALID_ARG, "probe copy needs 16-byte aligned pointers and size");
+    hipError_t e = launch_probe_copy(dst, src, bytes, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RL_OK : fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+}
+
+rl_status rl_probe_read(const void* src, size_t bytes, void* sink, void* stream)
+{
+    if (!sink || !src || bytes == 0 || bytes % 16 || !aligned16(src))
+        return fail(RL_ERR_INVALID_ARG, "probe read needs 16-byte aligned pointer and size");
+    hipError_t e = launch_probe_read(src, bytes, sink, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RL_OK : fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+}
+
+rl_status rl_probe_mfma(void* sink, int iters, rl_dtype dt, void* stream)
+{
+    if (!sink || iters < 1 || (dt != RL_F16 && dt != RL_BF16))
+        return fail(RL_ERR_INVALID_ARG, "probe mfma needs a sink, iters >= 1 and a 16-bit type");
+    hipError_t e = launch_probe_mfma(sink, iters, DType(dt), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RL_OK : fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+}
+
+const char* rl_last_error(void) { return tl_error; }
+const char* rl_version(void) { return "rmsnl 0.1 (gfx950)"; }
+
+}  // extern "C"

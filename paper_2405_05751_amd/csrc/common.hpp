@@ -1,0 +1,126 @@
+// Shared declarations of the rmsnl HIP sources (gfx950 only).
+//
+// Notation follows the paper's case study: X [M][K] activations, g [K] gain, W [K][N]
+// weight, A_i = sum_k X_ik^2, B_in = sum_k X_ik g_k W_kn, Y_in = B_in / sqrt(A_i/K + eps).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rmsnl {
+
+enum DType : int { F16 = 0, BF16 = 1, F32 = 2 };
+
+// One call, as the launchers see it.  Pointers are device pointers.
+struct Problem {
+    const void* X;        // [M][K]; for the plain matmul this is the left operand
+    const void* g;        // [K]; unused when fused == 0
+    const void* W;        // [K][N]
+    void* Y;              // [M][N]
+    int M, K, N;
+    float eps;
+    int fused;            // 1: RMSNorm prologue + row scaling, 0: plain product
+    DType dt;
+    // split-K workspace (may be null when the chosen launch needs none)
+    float* ws_partial;    // [S][M][N] partial B
+    float* ws_sumsq;      // [S][Mpad] partial A
+    unsigned* ws_counter; // one arrival counter per N tile, zero between calls
+    // launch-shape overrides, 0 = automatic
+    int n_tile;
+    int k_split;
+};
+
+// Launchers: return hipSuccess/err of the launch; `why` (optional) gets a static string when
+// the variant cannot run the shape (then nothing was launched and the return is hipErrorInvalidValue).
+hipError_t launch_naive(const Problem& p, hipStream_t s, const char** why);
+hipError_t launch_rmsnorm(const void* X, const void* g, float eps, void* Xn, int M, int K, DType dt,
+                          hipStream_t s);
+hipError_t launch_gemv(const Problem& p, hipStream_t s, const char** why);
+hipError_t launch_skinny(const Problem& p, hipStream_t s, const char** why);
+hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why);
+// bytes of partial-B workspace the launch of this problem would use (0 = no split)
+size_t gemv_workspace_bytes(const Problem& p);
+size_t skinny_workspace_bytes(const Problem& p);
+
+hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t s);
+hipError_t launch_probe_mfma(void* sink, int iters, DType dt, hipStream_t s);
+
+// workspace head: arrival counters, then the per-slab partial sums of squares; partial B follows
+constexpr size_t kCounterBytes = 64 * 1024;
+constexpr size_t kSumsqBytes = 256 * 1024;
+constexpr size_t kHeadBytes = kCounterBytes + kSumsqBytes;
+constexpr int kMaxCounters = int(kCounterBytes / sizeof(unsigned));
+constexpr int kMaxSumsqFloats = int(kSumsqBytes / sizeof(float));
+
+// ------------------------------------------------------------------ device helpers
+#if defined(__HIPCC__)
+
+typedef uint16_t u16;
+typedef __attribute__((ext_vector_type(2))) float float2_t;
+typedef __attribute__((ext_vector_type(4))) float float4_t;
+typedef __attribute__((ext_vector_type(16))) float float16_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t uint4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t uint2_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+
+struct Bf16 {};   // tag types for the 16-bit storage formats
+struct Fp16 {};
+
+template <typename T> struct Elem;
+
+template <> struct Elem<Bf16> {
+    typedef u16 store_t;
+    static __device__ __forceinline__ float to_f32(u16 b) { return __uint_as_float(uint32_t(b) << 16); }
+    // low / high half of a packed pair
+    static __device__ __forceinline__ float lo(uint32_t p) { return __uint_as_float(p << 16); }
+    static __device__ __forceinline__ float hi(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
+    static __device__ __forceinline__ u16 from_f32(float f) {
+        __bf16 h = (__bf16)f;                        // v_cvt_pk_bf16_f32, nearest-even
+        return __builtin_bit_cast(u16, h);
+    }
+    static __device__ __forceinline__ uint32_t pack(float a, float b) {
+        float2_t v = {a, b};
+        bf16x2_t h = __builtin_convertvector(v, bf16x2_t);
+        return __builtin_bit_cast(uint32_t, h);
+    }
+};
+
+template <> struct Elem<Fp16> {
+    typedef u16 store_t;
+    static __device__ __forceinline__ float to_f32(u16 b) { return (float)__builtin_bit_cast(_Float16, b); }
+    static __device__ __forceinline__ float lo(uint32_t p) { return to_f32(u16(p & 0xffffu)); }
+    static __device__ __forceinline__ float hi(uint32_t p) { return to_f32(u16(p >> 16)); }
+    static __device__ __forceinline__ u16 from_f32(float f) {
+        _Float16 h = (_Float16)f;                    // v_cvt_f16_f32, nearest-even
+        return __builtin_bit_cast(u16, h);
+    }
+    static __device__ __forceinline__ uint32_t pack(float a, float b) {
+        return uint32_t(from_f32(a)) | (uint32_t(from_f32(b)) << 16);
+    }
+};
+
+template <> struct Elem<float> {
+    typedef float store_t;
+    static __device__ __forceinline__ float to_f32(float f) { return f; }
+    static __device__ __forceinline__ float from_f32(float f) { return f; }
+};
+
+// rinv = 1 / sqrt(A / K + eps), correctly rounded division and root (not the fast approximations)
+__device__ __forceinline__ float row_scale(float sumsq, float inv_K, float eps) {
+    return 1.0f / __fsqrt_rn(__fmaf_rn(sumsq, inv_K, eps));
+}
+
+// sum over the 64 lanes of a wave, result in every lane
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+#endif  // __HIPCC__
+
+}  // namespace rmsnl

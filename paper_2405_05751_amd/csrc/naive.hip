@@ -1,0 +1,270 @@
+// Reference-grade kernels of the library: the any-shape fp32-arithmetic fallback for the fused
+// block, the stand-alone RMSNorm of the unfused A/B pair, and the measurement probes.
+#include "../../include/rmsnl.h"
+#include "common.hpp"
+
+namespace rmsnl {
+
+// ---------------------------------------------------------------------------------------------
+// Fallback: one workgroup = one row i and 64 consecutive columns; the K range is dealt to the four
+// waves (k = wave, wave+4, ...), so every thread carries two running sums -- A_i and B_in, the two
+// accumulators of the fused kernel -- and the four partials meet in LDS.  Works for every M, K, N.
+// ---------------------------------------------------------------------------------------------
+template <typename T, bool FUSED>
+__global__ __launch_bounds__(256) void naive_kernel(const typename Elem<T>::store_t* __restrict__ X,
+                                                    const typename Elem<T>::store_t* __restrict__ g,
+                                                    const typename Elem<T>::store_t* __restrict__ W,
+                                                    typename Elem<T>::store_t* __restrict__ Y,
+                                                    int M, int K, int N, float eps, float inv_K)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int i = blockIdx.y;
+    const int n = blockIdx.x * 64 + lane;
+    const bool live = n < N;
+    const size_t xrow = size_t(i) * K;
+
+    float B = 0.f, A = 0.f;
+    for (int k = wave; k < K; k += 4) {
+        float x = Elem<T>::to_f32(X[xrow + k]);
+        float xg = x;
+        if (FUSED) {
+            A = __fmaf_rn(x, x, A);
+            xg = x * Elem<T>::to_f32(g[k]);
+        }
+        float w = live ? Elem<T>::to_f32(W[size_t(k) * N + n]) : 0.f;
+        B = __fmaf_rn(xg, w, B);
+    }
+    __shared__ float sB[4][64];
+    __shared__ float sA[4];
+    sB[wave][lane] = B;
+    if (lane == 0) sA[wave] = A;
+    __syncthreads();
+    if (wave == 0 && live) {
+        float b = (sB[0][lane] + sB[1][lane]) + (sB[2][lane] + sB[3][lane]);
+        if (FUSED) {
+            float a = (sA[0] + sA[1]) + (sA[2] + sA[3]);
+            b *= row_scale(a, inv_K, eps);
+        }
+        Y[size_t(i) * N + n] = Elem<T>::from_f32(b);
+    }
+}
+
+template <typename T>
+static hipError_t launch_naive_t(const Problem& p, hipStream_t s)
+{
+    typedef typename Elem<T>::store_t S;
+    dim3 grid((p.N + 63) / 64, p.M);
+    if (p.fused)
+        naive_kernel<T, true><<<grid, 256, 0, s>>>((const S*)p.X, (const S*)p.g, (const S*)p.W, (S*)p.Y,
+                                                   p.M, p.K, p.N, p.eps, 1.0f / float(p.K));
+    else
+        naive_kernel<T, false><<<grid, 256, 0, s>>>((const S*)p.X, nullptr, (const S*)p.W, (S*)p.Y,
+                                                    p.M, p.K, p.N, 0.f, 0.f);
+    return hipGetLastError();
+}
+
+hipError_t launch_naive(const Problem& p, hipStream_t s, const char** why)
+{
+    if (p.M > 65535) {          // grid.y limit
+        if (why) *why = "naive variant supports M <= 65535";
+        return hipErrorInvalidValue;
+    }
+    switch (p.dt) {
+    case F16:  return launch_naive_t<Fp16>(p, s);
+    case BF16: return launch_naive_t<Bf16>(p, s);
+    default:   return launch_naive_t<float>(p, s);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Stand-alone RMSNorm (Eq. 1): one workgroup per row; first pass sums the squares, second pass
+// re-reads the row (it is still in cache) and writes x * g * rinv rounded to the storage type.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const typename Elem<T>::store_t* __restrict__ X,
+                                                      const typename Elem<T>::store_t* __restrict__ g,
+                                                      typename Elem<T>::store_t* __restrict__ Xn,
+                                                      int K, float eps, float inv_K)
+{
+    const size_t row = size_t(blockIdx.x) * K;
+    float a = 0.f;
+    for (int k = threadIdx.x; k < K; k += 256) {
+        float x = Elem<T>::to_f32(X[row + k]);
+        a = __fmaf_rn(x, x, a);
+    }
+    a = wave_sum(a);
+    __shared__ float sA[4];
+    if ((threadIdx.x & 63) == 0) sA[threadIdx.x >> 6] = a;
+    __syncthreads();
+    const float rinv = row_scale((sA[0] + sA[1]) + (sA[2] + sA[3]), inv_K, eps);
+    for (int k = threadIdx.x; k < K; k += 256) {
+        float x = Elem<T>::to_f32(X[row + k]);
+        Xn[row + k] = Elem<T>::from_f32(x * Elem<T>::to_f32(g[k]) * rinv);
+    }
+}
+
+// 16-bit rows with K % 8 == 0: 16-byte loads and stores, the row stays in registers when it fits
+template <typename T, int PER_THREAD>
+__global__ __launch_bounds__(256) void rmsnorm_vec_kernel(const uint4_t* __restrict__ X,
+                                                          const uint4_t* __restrict__ g,
+                                                          uint4_t* __restrict__ Xn,
+                                                          int K8, float eps, float inv_K)
+{
+    const size_t row = size_t(blockIdx.x) * K8;
+    uint4_t x[PER_THREAD];
+    float a = 0.f;
+#pragma unroll
+    for (int j = 0; j < PER_THREAD; ++j) {
+        int c = threadIdx.x + j * 256;
+        x[j] = c < K8 ? X[row + c] : uint4_t{0, 0, 0, 0};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float lo = Elem<T>::lo(x[j][e]), hi = Elem<T>::hi(x[j][e]);
+            a = __fmaf_rn(lo, lo, a);
+            a = __fmaf_rn(hi, hi, a);
+        }
+    }
+    a = wave_sum(a);
+    __shared__ float sA[4];
+    if ((threadIdx.x & 63) == 0) sA[threadIdx.x >> 6] = a;
+    __syncthreads();
+    const float rinv = row_scale((sA[0] + sA[1]) + (sA[2] + sA[3]), inv_K, eps);
+#pragma unroll
+    for (int j = 0; j < PER_THREAD; ++j) {
+        int c = threadIdx.x + j * 256;
+        if (c < K8) {
+            uint4_t gg = g[c], o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                o[e] = Elem<T>::pack(Elem<T>::lo(x[j][e]) * Elem<T>::lo(gg[e]) * rinv,
+                                     Elem<T>::hi(x[j][e]) * Elem<T>::hi(gg[e]) * rinv);
+            Xn[row + c] = o;
+        }
+    }
+}
+
+template <typename T>
+static hipError_t launch_rmsnorm_t(const void* X, const void* g, float eps, void* Xn, int M, int K,
+                                   hipStream_t s)
+{
+    typedef typename Elem<T>::store_t S;
+    const float inv_K = 1.0f / float(K);
+    if constexpr (sizeof(S) == 2) {
+        if (K % 8 == 0 && K <= 8 * 256 * 8) {
+            const int K8 = K / 8;
+            const int per = (K8 + 255) / 256;
+            const uint4_t* x = (const uint4_t*)X;
+            const uint4_t* gg = (const uint4_t*)g;
+            uint4_t* o = (uint4_t*)Xn;
+            if (per <= 1)      rmsnorm_vec_kernel<T, 1><<<M, 256, 0, s>>>(x, gg, o, K8, eps, inv_K);
+            else if (per <= 2) rmsnorm_vec_kernel<T, 2><<<M, 256, 0, s>>>(x, gg, o, K8, eps, inv_K);
+            else if (per <= 4) rmsnorm_vec_kernel<T, 4><<<M, 256, 0, s>>>(x, gg, o, K8, eps, inv_K);
+            else               rmsnorm_vec_kernel<T, 8><<<M, 256, 0, s>>>(x, gg, o, K8, eps, inv_K);
+            return hipGetLastError();
+        }
+    }
+    rmsnorm_kernel<T><<<M, 256, 0, s>>>((const S*)X, (const S*)g, (S*)Xn, K, eps, inv_K);
+    return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm(const void* X, const void* g, float eps, void* Xn, int M, int K, DType dt,
+                          hipStream_t s)
+{
+    switch (dt) {
+    case F16:  return launch_rmsnorm_t<Fp16>(X, g, eps, Xn, M, K, s);
+    case BF16: return launch_rmsnorm_t<Bf16>(X, g, eps, Xn, M, K, s);
+    default:   return launch_rmsnorm_t<float>(X, g, eps, Xn, M, K, s);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Probes
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void probe_copy_kernel(uint4_t* __restrict__ dst,
+                                                         const uint4_t* __restrict__ src, size_t n16)
+{
+    size_t i = size_t(blockIdx.x) * 256 * 8 + threadIdx.x;
+    uint4_t v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = (i + j * 256 < n16) ? src[i + j * 256] : uint4_t{0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        if (i + j * 256 < n16) dst[i + j * 256] = v[j];
+}
+
+__global__ __launch_bounds__(256) void probe_read_kernel(const uint4_t* __restrict__ src, size_t n16,
+                                                         uint32_t* __restrict__ sink)
+{
+    size_t i = size_t(blockIdx.x) * 256 * 16 + threadIdx.x;
+    uint4_t v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) v[j] = (i + j * 256 < n16) ? src[i + j * 256] : uint4_t{0, 0, 0, 0};
+    uint32_t acc = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc ^= v[j][0] ^ v[j][1] ^ v[j][2] ^ v[j][3];
+    if (acc == 0x9e3779b9u) sink[0] = acc;       // practically never taken; keeps the loads alive
+}
+
+hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t s)
+{
+    size_t n16 = bytes / 16;
+    unsigned blocks = unsigned((n16 + 2047) / 2048);
+    probe_copy_kernel<<<blocks, 256, 0, s>>>((uint4_t*)dst, (const uint4_t*)src, n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t s)
+{
+    size_t n16 = bytes / 16;
+    unsigned blocks = unsigned((n16 + 4095) / 4096);
+    probe_read_kernel<<<blocks, 256, 0, s>>>((const uint4_t*)src, n16, (uint32_t*)sink);
+    return hipGetLastError();
+}
+
+// register-only MFMA loop: 4 independent 32x32x16 accumulators per wave, 4 waves per workgroup,
+// 4 workgroups per CU's worth of grid; flops = grid * 4 waves * iters * 4 * 32*32*16*2
+constexpr int kProbeBlocks = 1024;
+template <typename V>
+__device__ __forceinline__ float16_t mfma32(V a, V b, float16_t c);
+template <> __device__ __forceinline__ float16_t mfma32<bf16x8_t>(bf16x8_t a, bf16x8_t b, float16_t c)
+{ return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+template <> __device__ __forceinline__ float16_t mfma32<f16x8_t>(f16x8_t a, f16x8_t b, float16_t c)
+{ return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+
+template <typename V>
+__global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ sink, int iters)
+{
+    typedef __attribute__((ext_vector_type(8))) float float8_t;
+    float8_t af, bf;
+    for (int e = 0; e < 8; ++e) {
+        af[e] = float((threadIdx.x + e) & 7) * 0.125f;
+        bf[e] = float((threadIdx.x * 3 + e) & 7) * 0.0625f;
+    }
+    V a = __builtin_convertvector(af, V), b = __builtin_convertvector(bf, V);
+    float16_t c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+    for (int it = 0; it < iters; ++it) {
+        c0 = mfma32<V>(a, b, c0);
+        c1 = mfma32<V>(a, b, c1);
+        c2 = mfma32<V>(a, b, c2);
+        c3 = mfma32<V>(a, b, c3);
+    }
+    float r = 0.f;
+    for (int e = 0; e < 16; ++e) r += c0[e] + c1[e] + c2[e] + c3[e];
+    sink[size_t(blockIdx.x) * 256 + threadIdx.x] = r;
+}
+
+hipError_t launch_probe_mfma(void* sink, int iters, DType dt, hipStream_t s)
+{
+    if (dt == F16) probe_mfma_kernel<f16x8_t><<<kProbeBlocks, 256, 0, s>>>((float*)sink, iters);
+    else           probe_mfma_kernel<bf16x8_t><<<kProbeBlocks, 256, 0, s>>>((float*)sink, iters);
+    return hipGetLastError();
+}
+
+}  // namespace rmsnl
+
+extern "C" size_t rl_probe_mfma_sink_floats(void) { return size_t(rmsnl::kProbeBlocks) * 256; }
+extern "C" double rl_probe_mfma_flops(int iters)
+{
+    return double(rmsnl::kProbeBlocks) * 4.0 * double(iters) * 4.0 * (32.0 * 32.0 * 16.0 * 2.0);
+}

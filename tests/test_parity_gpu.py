@@ -1,0 +1,332 @@
+"""Parity of the HIP library against the fp64 oracle, through the C ABI.  Needs an MI355X.
+
+Bar: max |err| <= 2e-2 * rms(Y) for f16/bf16 and <= 1e-5 * rms(Y) for f32, per checked row and
+over all checked rows; NaN positions must agree.  Inputs are the seeded synthetic workloads.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from util import TOL, compare, to_device, to_host_f64, upload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rl():
+    import torch
+    import paper_2405_05751_amd as pkg
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    yield pkg
+    pkg.rl_set_variant("auto")
+    pkg.rl_set_tuning(0, 0)
+
+
+_cache = {}
+
+
+def _workload(name):
+    if name not in _cache:
+        w = workloads.config(name)
+        Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps, rows=w.check_rows)
+        _cache[name] = (w, Z)
+    return _cache[name]
+
+
+def _run(rl, w, variant="auto", tuning=(0, 0), rows=None):
+    import torch
+    rl.rl_set_variant(variant)
+    rl.rl_set_tuning(*tuning)
+    X, g, W = upload(w)
+    Y = rl.rmsnorm_linear(X, g, W, w.eps)
+    torch.cuda.synchronize()
+    used = rl.rl_last_variant()
+    rl.rl_set_variant("auto")
+    rl.rl_set_tuning(0, 0)
+    if rows is not None:
+        Y = Y[torch.from_numpy(np.asarray(rows)).cuda()]
+    return to_host_f64(Y, w.dtype), used
+
+
+NOT_BUILT = {"skinny", "tile"}       # variants whose kernels have not landed yet
+
+
+def _supported(variant, w):
+    if variant in NOT_BUILT:
+        return False
+    if variant == "auto":
+        return True
+    if variant == "naive":
+        return w.M <= 4096
+    if w.dtype == "f32" or w.N % 8 or w.K % 8:
+        return False
+    if variant == "gemv":
+        return w.M <= 16
+    if variant == "skinny":
+        return w.M <= 64
+    return True
+
+
+# ------------------------------------------------------------------ the five configurations
+@pytest.mark.parametrize("name", workloads.CONFIG_NAMES)
+def test_config_auto(rl, name):
+    w, Z = _workload(name)
+    Y, used = _run(rl, w, "auto", rows=w.check_rows)
+    ratio, rms = compare(Y, Z, w.dtype, f"{name}/auto->{used}")
+    print(f"{name}: variant {used}, max|err|/rms(Y) = {ratio:.3e}, rms(Y) = {rms:.4f}")
+    # a correct 16-bit kernel sits at the output-rounding floor, far above fp64 agreement
+    if w.dtype == "bf16":
+        assert ratio > 1e-3, "suspiciously small error: is the comparison against a rounded oracle?"
+
+
+@pytest.mark.parametrize("variant", ["naive", "gemv", "skinny", "tile"])
+@pytest.mark.parametrize("name", workloads.CONFIG_NAMES)
+def test_config_forced_variant(rl, name, variant):
+    shape = workloads.config_shape(name)
+    probe = workloads.Workload(name, shape[1], shape[2], shape[3], shape[4], shape[5],
+                               None, None, None, None, None)
+    if variant == "naive" and name == "prefill":
+        pytest.skip("the slow fallback would take minutes at 8192^3")
+    if not _supported(variant, probe):
+        pytest.skip(f"{variant} does not cover {name}")
+    w, Z = _workload(name)
+    Y, used = _run(rl, w, variant, rows=w.check_rows)
+    assert used == variant
+    ratio, _ = compare(Y, Z, w.dtype, f"{name}/{variant}")
+    print(f"{name}/{variant}: max|err|/rms(Y) = {ratio:.3e}")
+
+
+# ------------------------------------------------------------------ the paper's own shape
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("variant", ["auto", "naive", "gemv", "skinny", "tile"])
+def test_paper_shape(rl, dtype, variant):
+    """X[16,1024], G[1024], W[1024,4096] -> Z[16,4096] (shapes of the case-study figure)."""
+    w = workloads.make(16, 1024, 4096, dtype, 1e-6, 901)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used = _run(rl, w, variant)
+    compare(Y, Z, dtype, f"paper-shape/{variant}->{used}")
+
+
+# ------------------------------------------------------------------ ragged and edge shapes
+RAGGED = [
+    # M, K, N
+    (1, 8, 8), (1, 64, 8), (2, 72, 264), (3, 1000, 520), (5, 4104, 1032), (7, 136, 4096),
+    (15, 2048, 776), (16, 520, 256), (17, 512, 512), (33, 1032, 392), (64, 264, 1160),
+    (65, 256, 256), (100, 520, 776), (130, 1544, 520), (257, 264, 264), (300, 776, 1288),
+]
+
+
+@pytest.mark.parametrize("variant", ["auto", "gemv", "skinny", "tile"])
+@pytest.mark.parametrize("M,K,N", RAGGED)
+def test_ragged_shapes(rl, M, K, N, variant):
+    w = workloads.make(M, K, N, "bf16", 1e-5, 1000 + M * 7 + K + N, outlier_frac=0.1 if M > 8 else 0.0)
+    if not _supported(variant, w):
+        pytest.skip(f"{variant} does not cover M={M}")
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used = _run(rl, w, variant)
+    compare(Y, Z, w.dtype, f"ragged {M}x{K}x{N}/{variant}->{used}")
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 1, 1), (2, 3, 2), (3, 7, 5), (4, 513, 33), (9, 130, 1027), (70, 77, 99)])
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_any_shape_falls_back(rl, M, K, N, dtype):
+    """Sizes that are not multiples of 8 are served (by the fallback) rather than refused."""
+    w = workloads.make(M, K, N, dtype, 1e-5, 2000 + M + K + N)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used = _run(rl, w, "auto")
+    compare(Y, Z, dtype, f"odd {M}x{K}x{N} {dtype}->{used}")
+
+
+@pytest.mark.parametrize("n_tile,k_split", [(128, 1), (128, 3), (256, 1), (256, 2), (256, 7), (512, 4), (256, 64)])
+def test_gemv_launch_shapes(rl, n_tile, k_split):
+    """Every tile width and slab count of the split-K variant gives the same answer (to tolerance)."""
+    w = workloads.make(4, 2056, 1544, "bf16", 1e-5, 3000 + n_tile + k_split)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used = _run(rl, w, "gemv", tuning=(n_tile, k_split))
+    assert used == "gemv"
+    compare(Y, Z, w.dtype, f"gemv n_tile={n_tile} k_split={k_split}")
+
+
+# ------------------------------------------------------------------ fp32 path
+@pytest.mark.parametrize("M,K,N", [(8, 512, 512), (3, 4096, 1000), (16, 1024, 4096)])
+def test_fp32_path(rl, M, K, N):
+    w = workloads.make(M, K, N, "f32", 1e-6, 4000 + M)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used = _run(rl, w, "auto")
+    ratio, _ = compare(Y, Z, "f32", f"fp32 {M}x{K}x{N}->{used}")
+    print(f"fp32 {M}x{K}x{N}: max|err|/rms(Y) = {ratio:.3e}")
+
+
+# ------------------------------------------------------------------ hand cases through the GPU
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_hand_cases_on_gpu(rl, golden_hand_cases, dtype):
+    cases = {
+        "H1": ([[3, 4, 0], [1, 2, 2]], [1, 2, 0.5], [[1, 0], [0, 1], [2, -2]], 0.0),
+        "H3": ([[2, 2, 2], [-1, 0, 1]], [1, 1, 1], [[1, 0], [0, 1], [1, 1]], 5.0),
+    }
+    for name, (X, g, W, eps) in cases.items():
+        w = workloads.Workload(name, 2, 3, 2, dtype, eps,
+                               workloads.to_storage(np.array(X, np.float32), dtype),
+                               workloads.to_storage(np.array(g, np.float32), dtype),
+                               workloads.to_storage(np.array(W, np.float32), dtype),
+                               np.arange(2), np.zeros(0, np.int64))
+        Y, _ = _run(rl, w, "auto")
+        want = np.array([[golden_hand_cases[name][(i, j)] for j in range(2)] for i in range(2)])
+        compare(Y, want, dtype, f"{name} {dtype}")
+
+
+# ------------------------------------------------------------------ invariants on the GPU
+@pytest.mark.parametrize("variant", ["gemv", "skinny", "tile", "naive"])
+def test_scale_invariance_on_gpu(rl, variant):
+    """eps = 0: Y(cX) = Y(X); with c a power of two the inputs stay exact and so do the outputs."""
+    w = workloads.make(8, 512, 512, "bf16", 0.0, 5001)
+    if not _supported(variant, w):
+        pytest.skip("variant does not cover the shape")
+    Y1, _ = _run(rl, w, variant)
+    x4 = workloads.to_storage(workloads.to_f32(w.X, "bf16") * 4.0, "bf16")
+    w4 = workloads.Workload("x4", w.M, w.K, w.N, w.dtype, 0.0, x4, w.g, w.W, w.check_rows, w.outlier_rows)
+    Y4, _ = _run(rl, w4, variant)
+    # scaling X by 4 scales A by 16 and B by 4 exactly in binary floating point
+    np.testing.assert_array_equal(Y1, Y4)
+
+
+def test_unit_rms_on_gpu(rl):
+    K = 512
+    X = workloads.make(8, K, K, "f16", 0.0, 5002).X
+    w = workloads.Workload("unit", 8, K, K, "f16", 0.0, X,
+                           workloads.to_storage(np.ones(K, np.float32), "f16"),
+                           workloads.to_storage(np.eye(K, dtype=np.float32), "f16"),
+                           np.arange(8), np.zeros(0, np.int64))
+    for variant in ("gemv", "naive"):
+        Y, _ = _run(rl, w, variant)
+        np.testing.assert_allclose(np.sqrt((Y ** 2).mean(axis=1)), 1.0, rtol=2e-3)
+
+
+def test_zero_row_nan_positions(rl):
+    w = workloads.make(4, 256, 256, "bf16", 0.0, 5003)
+    w.X[2] = 0
+    with np.errstate(all="ignore"):
+        Z0 = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, 0.0)
+    assert np.isnan(Z0[2]).all()
+    for variant in ("gemv", "naive", "skinny"):
+        Y, _ = _run(rl, w, variant)
+        compare(Y, Z0, w.dtype, f"zero row eps=0/{variant}")
+    w.eps = float(np.float32(1e-6))
+    Z1 = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, _ = _run(rl, w, "auto")
+    assert np.all(Y[2] == 0.0)
+    compare(Y, Z1, w.dtype, "zero row eps>0")
+
+
+# ------------------------------------------------------------------ determinism and memory safety
+@pytest.mark.parametrize("name,variant", [("decode", "gemv"), ("qkv", "gemv"), ("qkv", "skinny"),
+                                          ("gateup", "skinny"), ("tiny", "tile")])
+def test_bit_reproducible(rl, name, variant):
+    w, _ = _workload(name)
+    Y1, _ = _run(rl, w, variant)
+    for _ in range(3):
+        Y2, _ = _run(rl, w, variant)
+        assert np.array_equal(Y1, Y2), f"{name}/{variant} differs between runs"
+
+
+@pytest.mark.parametrize("variant", ["auto", "gemv", "skinny", "tile", "naive"])
+def test_output_canaries(rl, variant):
+    """Y sits inside a larger buffer filled with a sentinel: nothing outside Y may change."""
+    import torch
+    w = workloads.make(5, 520, 776, "bf16", 1e-5, 6001)
+    if not _supported(variant, w):
+        pytest.skip("variant does not cover the shape")
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    X, g, W = upload(w)
+    pad = 4096
+    buf = torch.full((pad + w.M * w.N + pad,), 123.0, dtype=torch.bfloat16, device="cuda")
+    Y = buf[pad:pad + w.M * w.N].view(w.M, w.N)
+    Y.fill_(float("nan"))
+    rl.rl_set_variant(variant)
+    rl.rmsnorm_linear(X, g, W, w.eps, Y)
+    torch.cuda.synchronize()
+    rl.rl_set_variant("auto")
+    assert torch.all(buf[:pad] == 123.0) and torch.all(buf[pad + w.M * w.N:] == 123.0)
+    compare(to_host_f64(Y, w.dtype), Z, w.dtype, f"canary/{variant}")
+
+
+# ------------------------------------------------------------------ the unfused A/B pair
+@pytest.mark.parametrize("name", ["tiny", "decode", "qkv", "gateup"])
+def test_unfused_pair(rl, name):
+    import torch
+    w, Z = _workload(name)
+    X, g, W = upload(w)
+    Xn = rl.rmsnorm(X, g, w.eps)
+    torch.cuda.synchronize()
+    Yn_oracle = oracle.rmsnorm(w.X, w.g, w.dtype, w.eps)
+    compare(to_host_f64(Xn, w.dtype), Yn_oracle, w.dtype, f"{name}/rmsnorm")
+    Y = rl.matmul(Xn, W)
+    torch.cuda.synchronize()
+    # the product alone, against the oracle's product of the very same rounded intermediate
+    Xn_bits = Xn.view(torch.uint16).cpu().numpy() if w.dtype == "bf16" else Xn.cpu().numpy()
+    Zp = oracle.matmul(Xn_bits, w.W, w.dtype)
+    compare(to_host_f64(Y, w.dtype), Zp, w.dtype, f"{name}/matmul")
+    # and the pair end to end against the fused definition (one extra 16-bit rounding of Xn)
+    ratio, _ = compare(to_host_f64(Y, w.dtype), Z, w.dtype, f"{name}/pair")
+    print(f"{name}: unfused pair max|err|/rms(Y) = {ratio:.3e}")
+
+
+@pytest.mark.parametrize("M,K", [(1, 8), (3, 100), (5, 4096), (2, 16384), (4, 20000)])
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_rmsnorm_shapes(rl, M, K, dtype):
+    import torch
+    w = workloads.make(M, K, 8, dtype, 1e-5, 7000 + M + K)
+    X, g, _ = upload(w)
+    Xn = rl.rmsnorm(X, g, w.eps)
+    torch.cuda.synchronize()
+    compare(to_host_f64(Xn, dtype), oracle.rmsnorm(w.X, w.g, dtype, w.eps), dtype, f"rmsnorm {M}x{K} {dtype}")
+
+
+# ------------------------------------------------------------------ error paths that need a device
+def test_forced_variant_refuses_unsupported_shape(rl):
+    import torch
+    w = workloads.make(32, 64, 64, "bf16", 1e-5, 8001)
+    X, g, W = upload(w)
+    rl.rl_set_variant("gemv")
+    try:
+        with pytest.raises(rl.RmsnlError) as ei:
+            rl.rmsnorm_linear(X, g, W, w.eps)
+        assert ei.value.status == 2
+    finally:
+        rl.rl_set_variant("auto")
+    torch.cuda.synchronize()
+
+
+def test_lent_workspace(rl):
+    import torch
+    w, Z = _workload("decode")
+    need = rl.rl_workspace_bytes(w.M, w.K, w.N, torch.bfloat16)
+    assert need > 0
+    small = torch.zeros(need // 2 // 4, dtype=torch.float32, device="cuda")
+    big = torch.zeros(need // 4 + 16, dtype=torch.float32, device="cuda")
+    X, g, W = upload(w)
+    try:
+        rl.rl_set_workspace(small)
+        with pytest.raises(rl.RmsnlError) as ei:
+            rl.rmsnorm_linear(X, g, W, w.eps)
+        assert ei.value.status == 4
+        rl.rl_set_workspace(big)
+        Y = rl.rmsnorm_linear(X, g, W, w.eps)
+        torch.cuda.synchronize()
+        compare(to_host_f64(Y, w.dtype), Z, w.dtype, "decode with lent workspace")
+        assert big[: 64 * 1024 // 4].abs().sum().item() == 0      # counters returned to zero
+    finally:
+        rl.rl_set_workspace(None)
+
+
+def test_probes_run(rl):
+    import torch
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    rl.rl_probe_copy(dst, src)
+    sink = torch.zeros(rl.lib().rl_probe_mfma_sink_floats(), dtype=torch.float32, device="cuda")
+    rl.rl_probe_read(src, sink)
+    flops = rl.rl_probe_mfma(sink, 8)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src) and flops > 0
