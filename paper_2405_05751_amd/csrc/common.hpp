@@ -121,6 +121,23 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// Device-scope (all XCDs) relaxed stores and loads: written through to / read from memory that
+// every XCD's L2 agrees on.  Used for the split-K partials, which cross XCDs.
+__device__ __forceinline__ void st_dev(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_dev(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev2(float* p, float2_t v) {
+    __hip_atomic_store(reinterpret_cast<uint64_t*>(p), __builtin_bit_cast(uint64_t, v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2_t ld_dev2(const float* p) {
+    uint64_t u = __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __builtin_bit_cast(float2_t, u);
+}
+
 #endif  // __HIPCC__
 
 }  // namespace rmsnl

@@ -1,16 +1,22 @@
 // Split-K GEMV variant of the fused RMSNorm + MatMul for decode shapes (M <= 16), without matrix
-// cores.  The block is bound by streaming W once from HBM, so the design is about keeping many
-// 16-byte loads in flight per lane and touching every W byte exactly once:
+// cores.  The block is bound by streaming W once from HBM and, at these sizes, by the length of
+// the chain of dependent memory round trips, so the design keeps many 16-byte loads in flight per
+// lane from the first instruction on and touches every W byte exactly once:
 //
-//   * a workgroup (4 waves) owns N_TILE = 8*LPR columns and one K slab; a wave-wide dwordx4 load
-//     covers 64/LPR consecutive W rows of that column strip, i.e. 1 KiB of contiguous-per-row data;
-//   * X-hat = X (.) g for the slab is formed once in fp32 and kept in LDS as [k][MT] (a lane reads the
-//     MT values of its row with one broadcast read), while the same pass adds up the slab's share of
-//     A_i = sum_k X_ik^2 -- the two accumulations of the paper's fused kernel share the K loop;
-//   * B partials are reduced across the row groups of a wave by shuffles, across waves through LDS,
-//     and across K slabs through an fp32 workspace: every slab writes its partial B and partial A,
-//     the last workgroup to arrive at the tile's counter adds the S partials in slab order (so the
-//     result does not depend on arrival order), scales by 1/sqrt(A/K + eps), rounds once and stores.
+//   * a workgroup (4 waves) owns N_TILE = 8*LPR columns and one K slab.  A wave is cut into
+//     RPI = 64/LPR lane groups; each of the workgroup's 4*RPI groups owns a run of consecutive W
+//     rows, a lane owns 8 columns, so a wave-wide dwordx4 load covers RPI rows of 16*LPR
+//     contiguous bytes.  Loads are raw buffer loads: rows beyond the slab read as zero with no
+//     branch, and D batches of 8 rows per lane are in flight at any time;
+//   * X-hat = X (.) g (fp32).  For M <= 4 a lane group loads the 8 X and g values of its batch
+//     straight into registers next to the W batch (no LDS, no barrier); for M = 8, 16 the slab's
+//     X-hat is staged once in LDS as [m][k].  Either way the same pass adds up the slab's share of
+//     A_i = sum_k X_ik^2: the two accumulations of the paper's fused kernel share one K loop;
+//   * B partials are reduced across the lane groups of a wave by shuffles, across waves through
+//     LDS, and across K slabs through an fp32 workspace: every slab writes its partial B and
+//     partial A through to memory, the last workgroup to arrive at the tile's counter adds the S
+//     partials in slab order (so the result does not depend on arrival order), scales by
+//     1/sqrt(A/K + eps), rounds once and stores.
 #include "common.hpp"
 
 namespace rmsnl {
@@ -19,23 +25,29 @@ struct GemvArgs {
     const u16* X; const u16* g; const uint4_t* W; u16* Y;
     int M, K, N;
     float eps, inv_K;
-    int k_slab;      // rows of W per slab (multiple of 8)
+    int k_slab;      // rows of W per slab (multiple of 8 * number of lane groups)
     int S;           // number of slabs
     int n_tiles;
     float* ws_partial; float* ws_sumsq; unsigned* counter;
 };
 
-constexpr int kGemvU = 8;            // 16-byte loads in flight per lane and buffer
+constexpr int kWAux = 2;             // cache policy of the W loads: nt (streamed once)
 constexpr int kSumsqStride = 16;     // floats per slab in ws_sumsq
+constexpr int kOut = 0x7ffffff0;     // a byte offset beyond any buffer resource: reads as zero
+constexpr int kRsrcFlags = 0x00020000;
+
+// batches of 8 rows in flight per lane
+constexpr int gemv_depth(int MT) { return MT <= 2 ? 4 : 2; }
 
 template <typename T, int MT, int LPR, bool FUSED>
 __global__ __launch_bounds__(256) void gemv_splitk_kernel(GemvArgs a)
 {
     constexpr int N_TILE = LPR * 8;
-    constexpr int RPI = 64 / LPR;            // W rows per wave-wide load
-    constexpr int ROWS_IT = 4 * RPI;         // W rows per workgroup-wide load
-    constexpr int U = kGemvU;
-    extern __shared__ float smem[];          // max(xs, red): see gemv_lds_bytes()
+    constexpr int RPI = 64 / LPR;            // lane groups per wave = W rows per wave-wide load
+    constexpr int NG = 4 * RPI;              // lane groups per workgroup
+    constexpr int D = gemv_depth(MT);
+    constexpr bool XLDS = MT > 4;            // X-hat through LDS instead of registers
+    extern __shared__ float smem[];          // XLDS: xs [MT][k_slab]; later red [4][MT][N_TILE]
     __shared__ float s_sumsq[4][MT];
     __shared__ float s_rinv[MT];
     __shared__ int s_last;
@@ -44,7 +56,7 @@ __global__ __launch_bounds__(256) void gemv_splitk_kernel(GemvArgs a)
     const int grp = lane / LPR, col8 = lane % LPR;
 
     // workgroups are dealt round-robin to the 8 XCDs; renumber so that the slabs of one tile share
-    // an XCD (their partials and the counter then meet in one L2)
+    // an XCD (a locality hint only: nothing below depends on where a workgroup runs)
     int b = blockIdx.x;
     const int total = a.n_tiles * a.S;
     if ((total & 7) == 0) b = (b & 7) * (total >> 3) + (b >> 3);
@@ -52,51 +64,78 @@ __global__ __launch_bounds__(256) void gemv_splitk_kernel(GemvArgs a)
     const int n0 = tile * N_TILE;
     const int k0 = slab * a.k_slab;
     const int klen = min(a.k_slab, a.K - k0);
-    const int N8 = a.N >> 3;
-    const bool colvalid = n0 + col8 * 8 < a.N;
-    const uint4_t* Wp = a.W + size_t(k0) * N8 + (n0 >> 3) + col8;
-    const int nIt = (klen + ROWS_IT - 1) / ROWS_IT;
-    const int rbase = wave * RPI + grp;
+    const int R = a.k_slab / NG;             // rows per lane group, a multiple of 8
+    const int gi = wave * RPI + grp;
+    const int r0 = gi * R;                   // first row of this group inside the slab
+    const int nB = R >> 3;                   // batches of 8 rows per group (uniform; rows past klen are zero)
 
-    auto load_batch = [&](uint4_t (&w)[U], int it0) {
+    // The slab of W as a buffer resource: rows at or beyond klen read as zero.  Columns at or
+    // beyond N (ragged last tile) wrap into the next row; those lanes' sums are never stored.
+    const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint4_t*>(a.W + size_t(k0) * (a.N >> 3)), 0, klen * a.N * 2, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<u16*>(a.X), 0, a.M * a.K * 2, kRsrcFlags);        // rows >= M read as zero
+    const __amdgpu_buffer_rsrc_t grs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<u16*>(FUSED ? a.g : a.X), 0, a.K * 2, kRsrcFlags);
+    const int wrow = a.N * 2;
+    const int voff0 = (r0 * a.N + n0 + col8 * 8) * 2;
+
+    uint4_t w[D][8];
+    uint4_t xq[D][XLDS ? 1 : MT], gq[D];
+    auto issue = [&](int bi, int d) {        // batch bi of this group into register set d
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int r = (it0 + u) * ROWS_IT + rbase;
-            w[u] = (colvalid && r < klen) ? __builtin_nontemporal_load(Wp + size_t(r) * N8)
-                                          : uint4_t{0, 0, 0, 0};
+        for (int j = 0; j < 8; ++j)
+            w[d][j] = __builtin_amdgcn_raw_buffer_load_b128(wrs, voff0 + (bi * 8 + j) * wrow, 0, kWAux);
+        if (!XLDS) {
+            const int koff = (r0 + bi * 8 < klen) ? (k0 + r0 + bi * 8) * 2 : kOut;
+            if (FUSED) gq[d] = __builtin_amdgcn_raw_buffer_load_b128(grs, koff, 0, 0);
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+                xq[d][m] = __builtin_amdgcn_raw_buffer_load_b128(
+                    xrs, (r0 + bi * 8 < klen) ? koff + m * a.K * 2 : kOut, 0, 0);
         }
     };
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        if (d < nB) issue(d, d);             // the queue is full before anything else happens
 
-    uint4_t wa[U], wb[U];
-    load_batch(wa, 0);                      // first W loads go out before anything else
+    float ss[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) ss[m] = 0.f;
 
-    // ---- X-hat for this slab into LDS as [k][MT] fp32, and this slab's share of A_i
     float* xs = smem;
-    {
-        float ss[MT];
+    if (XLDS) {
+        // X-hat of the whole slab into LDS as [m][k]; thread t converts 8 consecutive k per step
+        for (int c = tid; c < (a.k_slab >> 3); c += 256) {
+            const int kk = c * 8;
+            const int koff = kk < klen ? (k0 + kk) * 2 : kOut;
+            uint4_t gv = uint4_t{0, 0, 0, 0};
+            if (FUSED) gv = __builtin_amdgcn_raw_buffer_load_b128(grs, koff, 0, 0);
+            uint4_t xv[MT];
 #pragma unroll
-        for (int m = 0; m < MT; ++m) ss[m] = 0.f;
-        const int kpad = nIt * ROWS_IT;      // rows the main loop may index
-        for (int kk = tid; kk < kpad; kk += 256) {
-            const bool kin = kk < klen;
-            float gk = 1.f;
-            if (FUSED) gk = kin ? Elem<T>::to_f32(a.g[k0 + kk]) : 0.f;
-#pragma unroll
-            for (int m = 0; m < MT; ++m) {
-                float x = (kin && m < a.M) ? Elem<T>::to_f32(a.X[size_t(m) * a.K + k0 + kk]) : 0.f;
-                if (FUSED) ss[m] = __fmaf_rn(x, x, ss[m]);
-                xs[kk * MT + m] = FUSED ? x * gk : x;
-            }
-        }
-        if (FUSED) {
+            for (int m = 0; m < MT; ++m)
+                xv[m] = __builtin_amdgcn_raw_buffer_load_b128(xrs, kk < klen ? koff + m * a.K * 2 : kOut, 0, 0);
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
-                float v = wave_sum(ss[m]);
-                if (lane == 0) s_sumsq[wave][m] = v;
+                float h[8];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float x0 = Elem<T>::lo(xv[m][e]), x1 = Elem<T>::hi(xv[m][e]);
+                    h[2 * e] = x0; h[2 * e + 1] = x1;
+                    if (FUSED) {
+                        ss[m] = __fmaf_rn(x0, x0, ss[m]);
+                        ss[m] = __fmaf_rn(x1, x1, ss[m]);
+                        h[2 * e] = x0 * Elem<T>::lo(gv[e]);
+                        h[2 * e + 1] = x1 * Elem<T>::hi(gv[e]);
+                    }
+                }
+                float4_t* dst = (float4_t*)(xs + m * a.k_slab + kk);
+                dst[0] = float4_t{h[0], h[1], h[2], h[3]};
+                dst[1] = float4_t{h[4], h[5], h[6], h[7]};
             }
         }
+        __syncthreads();
     }
-    __syncthreads();
 
     // ---- main loop: acc[m][8 columns] += xhat[m][k] * W[k][8 columns]
     float acc[MT][8];
@@ -105,44 +144,80 @@ __global__ __launch_bounds__(256) void gemv_splitk_kernel(GemvArgs a)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[m][e] = 0.f;
 
-    auto consume = [&](const uint4_t (&w)[U], int it0) {
+    auto consume = [&](int bi, int d) {
+        float h[MT][8];
+        if (XLDS) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int r = (it0 + u) * ROWS_IT + rbase;
-            if ((it0 + u) < nIt) {           // uniform over the wave
-                const float* xr = xs + r * MT;
-                float wf[8];
+            for (int m = 0; m < MT; ++m) {
+                const float4_t* src = (const float4_t*)(xs + m * a.k_slab + r0 + bi * 8);
+                const float4_t lo = src[0], hi = src[1];
+                h[m][0] = lo[0]; h[m][1] = lo[1]; h[m][2] = lo[2]; h[m][3] = lo[3];
+                h[m][4] = hi[0]; h[m][5] = hi[1]; h[m][6] = hi[2]; h[m][7] = hi[3];
+            }
+        } else {
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    wf[2 * e] = Elem<T>::lo(w[u][e]);
-                    wf[2 * e + 1] = Elem<T>::hi(w[u][e]);
+                    const float x0 = Elem<T>::lo(xq[d][m][e]), x1 = Elem<T>::hi(xq[d][m][e]);
+                    h[m][2 * e] = x0; h[m][2 * e + 1] = x1;
+                    if (FUSED) {
+                        ss[m] = __fmaf_rn(x0, x0, ss[m]);
+                        ss[m] = __fmaf_rn(x1, x1, ss[m]);
+                        h[m][2 * e] = x0 * Elem<T>::lo(gq[d][e]);
+                        h[m][2 * e + 1] = x1 * Elem<T>::hi(gq[d][e]);
+                    }
                 }
+        }
 #pragma unroll
-                for (int m = 0; m < MT; ++m) {
-                    const float xm = xr[m];
+        for (int j = 0; j < 8; ++j) {
+            float wf[8];
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[m][e] = __fmaf_rn(xm, wf[e], acc[m][e]);
-                }
+            for (int e = 0; e < 4; ++e) {
+                wf[2 * e] = Elem<T>::lo(w[d][j][e]);
+                wf[2 * e + 1] = Elem<T>::hi(w[d][j][e]);
             }
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[m][e] = __fmaf_rn(h[m][j], wf[e], acc[m][e]);
         }
     };
 
-    for (int it0 = 0; it0 < nIt; it0 += 2 * U) {
-        if (it0 + U < nIt) load_batch(wb, it0 + U);
-        consume(wa, it0);
-        if (it0 + 2 * U < nIt) load_batch(wa, it0 + 2 * U);
-        if (it0 + U < nIt) consume(wb, it0 + U);
+    for (int b0 = 0; b0 < nB; b0 += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int bi = b0 + d;
+            if (bi < nB) {                   // uniform over the workgroup
+                consume(bi, d);
+                if (bi + D < nB) issue(bi + D, d);
+            }
+        }
     }
 
-    // ---- reduce over the row groups of the wave, then over the four waves through LDS
+    // ---- reduce over the lane groups of the wave, then over the four waves through LDS.
+    // In register mode every lane of a group carries the same ss, so the group sum over lanes
+    // col8 == 0 is what the shuffles over the group index produce.
 #pragma unroll
-    for (int off = LPR; off < 64; off <<= 1)
+    for (int off = LPR; off < 64; off <<= 1) {
 #pragma unroll
         for (int m = 0; m < MT; ++m)
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[m][e] += __shfl_xor(acc[m][e], off, 64);
+        if (FUSED && !XLDS) {
+#pragma unroll
+            for (int m = 0; m < MT; ++m) ss[m] += __shfl_xor(ss[m], off, 64);
+        }
+    }
+    if (FUSED) {
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            const float v = XLDS ? wave_sum(ss[m]) : ss[m];
+            if (lane == 0) s_sumsq[wave][m] = v;
+        }
+    }
 
-    __syncthreads();                         // everyone is done reading xs
+    if (XLDS) __syncthreads();               // everyone is done reading xs
     float* red = smem;                       // [4][MT][N_TILE]
     if (grp == 0) {
 #pragma unroll
@@ -155,18 +230,21 @@ __global__ __launch_bounds__(256) void gemv_splitk_kernel(GemvArgs a)
     __syncthreads();
 
     constexpr int PAIRS = MT * N_TILE / 2;   // column pairs of the tile, 256 threads share them
-    const bool split = a.S > 1;
+    constexpr int PPT = (PAIRS + 255) / 256; // column pairs per thread
+    constexpr int WSTR = MT * N_TILE / 2;    // float2 stride between the waves' copies in red
     float asum = 0.f;
     if (FUSED && tid < MT) asum = (s_sumsq[0][tid] + s_sumsq[1][tid]) + (s_sumsq[2][tid] + s_sumsq[3][tid]);
 
-    if (!split) {
+    if (a.S == 1) {
         if (tid < MT) s_rinv[tid] = FUSED ? row_scale(asum, a.inv_K, a.eps) : 1.f;
         __syncthreads();
-        for (int p = tid; p < PAIRS; p += 256) {
+#pragma unroll
+        for (int pi = 0; pi < PPT; ++pi) {
+            const int p = tid + pi * 256;
             const int m = p / (N_TILE / 2), c = (p % (N_TILE / 2)) * 2;
-            if (m < a.M && n0 + c < a.N) {
-                const float2_t* r0 = (const float2_t*)(red + m * N_TILE + c);
-                float2_t v = (r0[0] + r0[MT * N_TILE / 2]) + (r0[2 * MT * N_TILE / 2] + r0[3 * MT * N_TILE / 2]);
+            if (p < PAIRS && m < a.M && n0 + c < a.N) {
+                const float2_t* q = (const float2_t*)(red + m * N_TILE + c);
+                const float2_t v = (q[0] + q[WSTR]) + (q[2 * WSTR] + q[3 * WSTR]);
                 const float ri = s_rinv[m];
                 *(uint32_t*)(a.Y + size_t(m) * a.N + n0 + c) = Elem<T>::pack(v[0] * ri, v[1] * ri);
             }
@@ -174,17 +252,21 @@ __global__ __launch_bounds__(256) void gemv_splitk_kernel(GemvArgs a)
         return;
     }
 
-    // ---- split-K: publish this slab's partial B and partial A
-    if (FUSED && tid < MT) a.ws_sumsq[slab * kSumsqStride + tid] = asum;
-    for (int p = tid; p < PAIRS; p += 256) {
+    // ---- split-K.  Partials are written through to memory with device-scope stores (no cache-wide
+    // write-back is needed to publish them); every wave waits for its own stores, the workgroup
+    // meets at a barrier, and only then one thread bumps the tile's counter.
+    if (FUSED && tid < MT) st_dev(a.ws_sumsq + slab * kSumsqStride + tid, asum);
+#pragma unroll
+    for (int pi = 0; pi < PPT; ++pi) {
+        const int p = tid + pi * 256;
         const int m = p / (N_TILE / 2), c = (p % (N_TILE / 2)) * 2;
-        if (m < a.M && n0 + c < a.N) {
-            const float2_t* r0 = (const float2_t*)(red + m * N_TILE + c);
-            float2_t v = (r0[0] + r0[MT * N_TILE / 2]) + (r0[2 * MT * N_TILE / 2] + r0[3 * MT * N_TILE / 2]);
-            *(float2_t*)(a.ws_partial + (size_t(slab) * a.M + m) * a.N + n0 + c) = v;
+        if (p < PAIRS && m < a.M && n0 + c < a.N) {
+            const float2_t* q = (const float2_t*)(red + m * N_TILE + c);
+            const float2_t v = (q[0] + q[WSTR]) + (q[2 * WSTR] + q[3 * WSTR]);
+            st_dev2(a.ws_partial + (size_t(slab) * a.M + m) * a.N + n0 + c, v);
         }
     }
-    __threadfence();                         // release: partials visible device-wide before the count
+    __builtin_amdgcn_s_waitcnt(0);           // this wave's stores have been acknowledged
     __syncthreads();
     if (tid == 0) {
         unsigned prev = __hip_atomic_fetch_add(a.counter + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -192,37 +274,58 @@ __global__ __launch_bounds__(256) void gemv_splitk_kernel(GemvArgs a)
     }
     __syncthreads();
     if (!s_last) return;
-    __threadfence();                         // acquire: see every slab's partials
 
-    if (tid < MT) {
-        float t = 0.f;
+    // ---- last arriver: device-scope loads see what the other slabs wrote through.
+    // A_i: wave 3 reads the S partial sums of squares, one slab per lane, all loads in flight at
+    // once; lane order and the shuffle tree fix the order of the additions.
+    if (wave == 3) {
+        float t[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) t[m] = 0.f;
         if (FUSED) {
-            for (int s = 0; s < a.S; ++s)
-                t += __builtin_nontemporal_load(a.ws_sumsq + s * kSumsqStride + tid);
+            for (int s = lane; s < a.S; s += 64)
+#pragma unroll
+                for (int m = 0; m < MT; ++m) t[m] += ld_dev(a.ws_sumsq + s * kSumsqStride + m);
         }
-        s_rinv[tid] = FUSED ? row_scale(t, a.inv_K, a.eps) : 1.f;
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            const float tot = wave_sum(t[m]);
+            if (lane == 0) s_rinv[m] = FUSED ? row_scale(tot, a.inv_K, a.eps) : 1.f;
+        }
     }
-    __syncthreads();
-    for (int p = tid; p < PAIRS; p += 256) {
+    float2_t yv[PPT];
+#pragma unroll
+    for (int pi = 0; pi < PPT; ++pi) {
+        const int p = tid + pi * 256;
         const int m = p / (N_TILE / 2), c = (p % (N_TILE / 2)) * 2;
-        if (m < a.M && n0 + c < a.N) {
+        yv[pi] = float2_t{0.f, 0.f};
+        if (p < PAIRS && m < a.M && n0 + c < a.N) {
             const float* src = a.ws_partial + size_t(m) * a.N + n0 + c;
             const size_t sstride = size_t(a.M) * a.N;
             float2_t v = {0.f, 0.f};
-            int s = 0;
-            for (; s + 4 <= a.S; s += 4) {   // four loads in flight, added in slab order
-                float2_t p0 = __builtin_nontemporal_load((const float2_t*)(src + (s + 0) * sstride));
-                float2_t p1 = __builtin_nontemporal_load((const float2_t*)(src + (s + 1) * sstride));
-                float2_t p2 = __builtin_nontemporal_load((const float2_t*)(src + (s + 2) * sstride));
-                float2_t p3 = __builtin_nontemporal_load((const float2_t*)(src + (s + 3) * sstride));
-                v += p0; v += p1; v += p2; v += p3;
+            for (int s0 = 0; s0 < a.S; s0 += 16) {   // sixteen loads in flight, added in slab order
+                float2_t q[16];
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    q[j] = (s0 + j < a.S) ? ld_dev2(src + (s0 + j) * sstride) : float2_t{0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < 16; ++j) v += q[j];
             }
-            for (; s < a.S; ++s) v += __builtin_nontemporal_load((const float2_t*)(src + s * sstride));
-            const float ri = s_rinv[m];
-            *(uint32_t*)(a.Y + size_t(m) * a.N + n0 + c) = Elem<T>::pack(v[0] * ri, v[1] * ri);
+            yv[pi] = v;
         }
     }
-    if (tid == 0) a.counter[tile] = 0;       // ready for the next call on this stream
+    __syncthreads();                         // s_rinv is ready
+#pragma unroll
+    for (int pi = 0; pi < PPT; ++pi) {
+        const int p = tid + pi * 256;
+        const int m = p / (N_TILE / 2), c = (p % (N_TILE / 2)) * 2;
+        if (p < PAIRS && m < a.M && n0 + c < a.N) {
+            const float ri = s_rinv[m];
+            *(uint32_t*)(a.Y + size_t(m) * a.N + n0 + c) = Elem<T>::pack(yv[pi][0] * ri, yv[pi][1] * ri);
+        }
+    }
+    if (tid == 0)                            // ready for the next call on this stream
+        __hip_atomic_store(a.counter + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ------------------------------------------------------------------------------------------- host
@@ -234,32 +337,41 @@ static GemvPlan gemv_plan(const Problem& p)
     pl.ok = false;
     if (p.dt == F32) { pl.why = "gemv variant handles 16-bit types only"; return pl; }
     if (p.M > 16) { pl.why = "gemv variant needs M <= 16"; return pl; }
-    if (p.N % 8 != 0) { pl.why = "gemv variant needs N % 8 == 0"; return pl; }
+    if (p.N % 8 != 0 || p.K % 8 != 0) { pl.why = "gemv variant needs N % 8 == 0 and K % 8 == 0"; return pl; }
+    if (int64_t(p.M) * p.K * 2 >= (int64_t(1) << 31)) { pl.why = "gemv variant needs M*K < 2^30"; return pl; }
     pl.MT = p.M <= 1 ? 1 : p.M <= 2 ? 2 : p.M <= 4 ? 4 : p.M <= 8 ? 8 : 16;
     int n_tile = p.n_tile ? p.n_tile : 256;
-    if (n_tile != 128 && n_tile != 256 && n_tile != 512) { pl.why = "gemv n_tile must be 128, 256 or 512"; return pl; }
+    if (n_tile != 64 && n_tile != 128 && n_tile != 256 && n_tile != 512) {
+        pl.why = "gemv n_tile must be 64, 128, 256 or 512";
+        return pl;
+    }
     if (pl.MT * n_tile > 4096) n_tile = 4096 / pl.MT;          // cross-wave reduction buffer <= 64 KiB
     pl.LPR = n_tile / 8;
     pl.n_tiles = (p.N + n_tile - 1) / n_tile;
-    const int rows_it = 4 * (64 / pl.LPR);
-    // slab length: as requested, else aim at about 512 workgroups
+    const int gran = 8 * 4 * (64 / pl.LPR);                    // 8 rows per batch and lane group
+    const int depth_rows = gran * gemv_depth(pl.MT);           // rows that fill the load queue once
     int S = p.k_split;
     if (S <= 0) {
-        S = (512 + pl.n_tiles - 1) / pl.n_tiles;
-        const int smax = (p.K + 63) / 64;                      // at least 64 rows per slab
-        if (S > smax) S = smax;
+        // as many slabs as give every workgroup one full queue of loads, but not more workgroups
+        // than about two per compute unit
+        S = (p.K + depth_rows - 1) / depth_rows;
+        const int s_cap = (512 + pl.n_tiles - 1) / pl.n_tiles;
+        if (S > s_cap) S = s_cap;
         if (S < 1) S = 1;
     }
     int k_slab = (p.K + S - 1) / S;
-    k_slab = (k_slab + rows_it - 1) / rows_it * rows_it;
-    const int k_max = (64 * 1024) / (4 * pl.MT) / rows_it * rows_it;   // xs <= 64 KiB
-    if (k_slab > k_max) k_slab = k_max;
+    k_slab = (k_slab + gran - 1) / gran * gran;
+    while (int64_t(k_slab) * p.N * 2 >= (int64_t(1) << 31)) k_slab = (k_slab / 2 + gran - 1) / gran * gran;
+    if (pl.MT > 4) {                                           // xs [MT][k_slab] fp32 <= 64 KiB
+        const int k_max = (64 * 1024) / (4 * pl.MT) / gran * gran;
+        if (k_slab > k_max) k_slab = k_max;
+    }
     S = (p.K + k_slab - 1) / k_slab;
     pl.S = S;
     pl.k_slab = k_slab;
     if (pl.n_tiles > kMaxCounters) { pl.why = "too many column tiles"; return pl; }
     if (S * kSumsqStride > kMaxSumsqFloats) { pl.why = "too many K slabs"; return pl; }
-    const size_t xs = size_t(k_slab + rows_it) * pl.MT * 4;
+    const size_t xs = pl.MT > 4 ? size_t(k_slab) * pl.MT * 4 : 0;
     const size_t red = size_t(4) * pl.MT * n_tile * 4;
     pl.lds = xs > red ? xs : red;
     pl.ok = true;
@@ -298,6 +410,7 @@ static hipError_t gemv_lpr(const GemvArgs& a, bool fused, const GemvPlan& pl, hi
     if constexpr (MT * 512 <= 4096) { if (pl.LPR == 64) return gemv_go<T, MT, 64>(a, fused, pl, s); }
     if constexpr (MT * 256 <= 4096) { if (pl.LPR == 32) return gemv_go<T, MT, 32>(a, fused, pl, s); }
     if (pl.LPR == 16) return gemv_go<T, MT, 16>(a, fused, pl, s);
+    if (pl.LPR == 8) return gemv_go<T, MT, 8>(a, fused, pl, s);
     return hipErrorInvalidValue;
 }
 

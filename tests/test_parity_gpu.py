@@ -103,6 +103,8 @@ def test_config_forced_variant(rl, name, variant):
 def test_paper_shape(rl, dtype, variant):
     """X[16,1024], G[1024], W[1024,4096] -> Z[16,4096] (shapes of the case-study figure)."""
     w = workloads.make(16, 1024, 4096, dtype, 1e-6, 901)
+    if not _supported(variant, w):
+        pytest.skip(f"{variant} does not cover the shape")
     Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
     Y, used = _run(rl, w, variant)
     compare(Y, Z, dtype, f"paper-shape/{variant}->{used}")
@@ -210,8 +212,9 @@ def test_zero_row_nan_positions(rl):
         Z0 = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, 0.0)
     assert np.isnan(Z0[2]).all()
     for variant in ("gemv", "naive", "skinny"):
-        Y, _ = _run(rl, w, variant)
-        compare(Y, Z0, w.dtype, f"zero row eps=0/{variant}")
+        if _supported(variant, w):
+            Y, _ = _run(rl, w, variant)
+            compare(Y, Z0, w.dtype, f"zero row eps=0/{variant}")
     w.eps = float(np.float32(1e-6))
     Z1 = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
     Y, _ = _run(rl, w, "auto")
@@ -223,6 +226,8 @@ def test_zero_row_nan_positions(rl):
 @pytest.mark.parametrize("name,variant", [("decode", "gemv"), ("qkv", "gemv"), ("qkv", "skinny"),
                                           ("gateup", "skinny"), ("tiny", "tile")])
 def test_bit_reproducible(rl, name, variant):
+    if variant in NOT_BUILT:
+        pytest.skip(f"{variant} not built")
     w, _ = _workload(name)
     Y1, _ = _run(rl, w, variant)
     for _ in range(3):
@@ -303,7 +308,7 @@ def test_lent_workspace(rl):
     w, Z = _workload("decode")
     need = rl.rl_workspace_bytes(w.M, w.K, w.N, torch.bfloat16)
     assert need > 0
-    small = torch.zeros(need // 2 // 4, dtype=torch.float32, device="cuda")
+    small = torch.zeros((320 * 1024 + 4096) // 4, dtype=torch.float32, device="cuda")   # head fits, partials do not
     big = torch.zeros(need // 4 + 16, dtype=torch.float32, device="cuda")
     X, g, W = upload(w)
     try:
