@@ -97,12 +97,23 @@ rl_status rl_set_tuning(int n_tile, int k_split);
  * allocates rl_workspace_default_bytes() once per device on first need and keeps it until
  * the process ends.  rl_set_workspace lends a caller-owned DEVICE buffer instead (for the
  * current device; bytes must be >= rl_workspace_bytes() of every later call; the first
- * 64 KiB must be zero when lent); NULL returns to the library's own buffer.
+ * 256 KiB must be zero when lent); NULL returns to the library's own buffer.
  * rl_workspace_bytes gives the bytes a call of that shape needs (0 if none).
  */
 rl_status rl_set_workspace(void* dev_ptr, size_t bytes);
 size_t rl_workspace_bytes(int64_t M, int64_t K, int64_t N, rl_dtype dt);
 size_t rl_workspace_default_bytes(void);
+
+/*
+ * Stage trace (diagnostics).  While a DEVICE buffer is registered, thread 0 of workgroup b of
+ * the split-K kernel stores the 100 MHz constant clock into 64-bit slot b*rl_trace_slots()+i
+ * when it reaches stage i (0 start, 1 first loads issued, 2 K loop done, 3 workgroup partial
+ * reduced, 4 partials published, 5 counter bumped, 6 all slabs read, 7 Y stored); workgroups
+ * beyond bytes / (8 * rl_trace_slots()) are not traced.  NULL switches it off (the default).
+ * The buffer is caller-owned and must outlive every traced call.
+ */
+rl_status rl_set_trace(void* dev_ptr, size_t bytes);
+size_t rl_trace_slots(void);
 
 /*
  * Measurement helpers (not on the hot path): a plain device-to-device copy kernel of

@@ -14,7 +14,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "librmsnl.so")
+LIB_PATH = os.environ.get("RMSNL_LIB") or os.path.join(_HERE, "librmsnl.so")
 
 RL_OK, RL_ERR_INVALID_ARG, RL_ERR_UNSUPPORTED, RL_ERR_HIP, RL_ERR_WORKSPACE = range(5)
 RL_F16, RL_BF16, RL_F32 = range(3)
@@ -38,6 +38,8 @@ EXPORTS = {
     "rl_last_variant": (ctypes.c_int, []),
     "rl_set_tuning": (ctypes.c_int, [ctypes.c_int, ctypes.c_int]),
     "rl_set_workspace": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t]),
+    "rl_set_trace": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t]),
+    "rl_trace_slots": (ctypes.c_size_t, []),
     "rl_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]),
     "rl_workspace_default_bytes": (ctypes.c_size_t, []),
     "rl_probe_copy": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
@@ -154,6 +156,18 @@ def rl_set_workspace(buf: Optional[torch.Tensor]) -> None:
         _check(lib().rl_set_workspace(None, 0))
     else:
         _check(lib().rl_set_workspace(_dev(buf, "workspace"), buf.numel() * buf.element_size()))
+
+
+def rl_set_trace(buf: Optional[torch.Tensor]) -> None:
+    """Register (or with None remove) a device int64 buffer for per-workgroup stage time stamps."""
+    if buf is None:
+        _check(lib().rl_set_trace(None, 0))
+    else:
+        _check(lib().rl_set_trace(_dev(buf, "trace"), buf.numel() * buf.element_size()))
+
+
+def rl_trace_slots() -> int:
+    return int(lib().rl_trace_slots())
 
 
 def rl_workspace_bytes(M: int, K: int, N: int, dtype: torch.dtype) -> int:

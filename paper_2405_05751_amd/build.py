@@ -24,8 +24,8 @@ FLAGS = [
 ]
 
 
-def _compile(src: str, extra) -> str:
-    out = os.path.join(OBJ, src.replace(".hip", ".o"))
+def _compile(src: str, extra, objdir: str = OBJ) -> str:
+    out = os.path.join(objdir, src.replace(".hip", ".o"))
     cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", out]
     r = subprocess.run(cmd, capture_output=True, text=True)
     msgs = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
@@ -37,20 +37,29 @@ def _compile(src: str, extra) -> str:
     return out
 
 
-def build(force: bool = True, extra_flags=()) -> str:
+def build(force: bool = True, extra_flags=(), out: str = LIB) -> str:
+    """Compile and link; `out` and `extra_flags` let experiments build side-by-side variants."""
+    if out != LIB:
+        return _link(out, extra_flags, os.path.join(OBJ, os.path.basename(out) + ".d"))
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    deps = srcs + [os.path.join(CSRC, "common.hpp"), os.path.join(HERE, "..", "include", "rmsnl.h")]
+    deps = srcs + [os.path.join(CSRC, "common.hpp"), os.path.join(CSRC, "splitk.hpp"), os.path.join(HERE, "..", "include", "rmsnl.h")]
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
         return LIB
-    os.makedirs(OBJ, exist_ok=True)
+    return _link(LIB, extra_flags, OBJ)
+
+
+def _link(out: str, extra_flags, objdir: str) -> str:
+    os.makedirs(objdir, exist_ok=True)
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
-    tmp = LIB + f".tmp{os.getpid()}"
+        objs = list(ex.map(lambda s: _compile(s, list(extra_flags), objdir), SOURCES))
+    tmp = out + f".tmp{os.getpid()}"
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]
     subprocess.run(cmd, check=True)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":
-    print(build(extra_flags=sys.argv[1:]))
+    flags = [a for a in sys.argv[1:] if not a.startswith("--out=")]
+    outs = [a[6:] for a in sys.argv[1:] if a.startswith("--out=")]
+    print(build(extra_flags=flags, out=os.path.abspath(outs[0]) if outs else LIB))

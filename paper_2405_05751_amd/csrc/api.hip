@@ -2,6 +2,7 @@
 #include "../../include/rmsnl.h"
 #include "common.hpp"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -22,6 +23,8 @@ std::mutex g_mu;
 bool g_env_read = false;
 rl_variant g_variant = RL_AUTO;
 int g_n_tile = 0, g_k_split = 0;
+unsigned long long* g_trace = nullptr;
+int g_trace_groups = 0;
 struct Workspace { void* ptr; size_t bytes; bool owned; };
 Workspace g_ws[kMaxDevices] = {};
 Workspace g_lent[kMaxDevices] = {};
@@ -110,6 +113,8 @@ rl_status run(Problem& p, void* stream)
         forced = g_variant;
         p.n_tile = g_n_tile;
         p.k_split = g_k_split;
+        p.trace = g_trace;
+        p.trace_groups = g_trace_groups;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     rl_variant order[4];
@@ -226,6 +231,18 @@ rl_status rl_set_tuning(int n_tile, int k_split)
     return RL_OK;
 }
 
+rl_status rl_set_trace(void* dev_ptr, size_t bytes)
+{
+    if (dev_ptr && ((reinterpret_cast<uintptr_t>(dev_ptr) & 7u) || bytes < kTraceSlots * 8))
+        return fail(RL_ERR_INVALID_ARG, "trace buffer must be 8-byte aligned and hold at least one workgroup");
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_trace = static_cast<unsigned long long*>(dev_ptr);
+    g_trace_groups = dev_ptr ? int(std::min<size_t>(bytes / (kTraceSlots * 8), size_t(1) << 30)) : 0;
+    return RL_OK;
+}
+
+size_t rl_trace_slots(void) { return kTraceSlots; }
+
 rl_status rl_set_workspace(void* dev_ptr, size_t bytes)
 {
     int dev = 0;
@@ -233,7 +250,7 @@ rl_status rl_set_workspace(void* dev_ptr, size_t bytes)
     if (e != hipSuccess) return fail(RL_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
     if (dev < 0 || dev >= kMaxDevices) return fail(RL_ERR_UNSUPPORTED, "device index out of range");
     if (dev_ptr && (!aligned16(dev_ptr) || bytes <= kHeadBytes))
-        return fail(RL_ERR_INVALID_ARG, "workspace must be 16-byte aligned and larger than 320 KiB");
+        return fail(RL_ERR_INVALID_ARG, "workspace must be 16-byte aligned and larger than 1280 KiB");
     std::lock_guard<std::mutex> lk(g_mu);
     g_lent[dev] = Workspace{dev_ptr, dev_ptr ? bytes : 0, false};
     return RL_OK;

@@ -23,12 +23,17 @@ struct Problem {
     DType dt;
     // split-K workspace (may be null when the chosen launch needs none)
     float* ws_partial;    // [S][M][N] partial B
-    float* ws_sumsq;      // [S][Mpad] partial A
+    float* ws_sumsq;      // [tiles][S][Mpad] partial A
     unsigned* ws_counter; // one arrival counter per N tile, zero between calls
     // launch-shape overrides, 0 = automatic
     int n_tile;
     int k_split;
+    // optional stage trace: kTraceSlots 64-bit time stamps per workgroup, or null
+    unsigned long long* trace;
+    int trace_groups;     // workgroups the trace buffer has room for
 };
+
+constexpr int kTraceSlots = 16;
 
 // Launchers: return hipSuccess/err of the launch; `why` (optional) gets a static string when
 // the variant cannot run the shape (then nothing was launched and the return is hipErrorInvalidValue).
@@ -47,10 +52,12 @@ hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStrea
 hipError_t launch_probe_mfma(void* sink, int iters, DType dt, hipStream_t s);
 
 // workspace head: arrival counters, then the per-slab partial sums of squares; partial B follows
-constexpr size_t kCounterBytes = 64 * 1024;
-constexpr size_t kSumsqBytes = 256 * 1024;
+// Counters sit one per 128-byte line so that the tiles' atomics spread over memory channels.
+constexpr size_t kCounterBytes = 256 * 1024;
+constexpr size_t kSumsqBytes = 1024 * 1024;
 constexpr size_t kHeadBytes = kCounterBytes + kSumsqBytes;
-constexpr int kMaxCounters = int(kCounterBytes / sizeof(unsigned));
+constexpr int kCounterStride = 32;                         // unsigneds between two counters
+constexpr int kMaxCounters = int(kCounterBytes / sizeof(unsigned)) / kCounterStride;
 constexpr int kMaxSumsqFloats = int(kSumsqBytes / sizeof(float));
 
 // ------------------------------------------------------------------ device helpers
@@ -136,6 +143,12 @@ __device__ __forceinline__ void st_dev2(float* p, float2_t v) {
 __device__ __forceinline__ float2_t ld_dev2(const float* p) {
     uint64_t u = __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return __builtin_bit_cast(float2_t, u);
+}
+
+// Stage trace: thread 0 of a workgroup stores the constant-rate (100 MHz) clock into its slot.
+__device__ __forceinline__ void trace_stamp(unsigned long long* trace, int groups, int slot) {
+    if (trace && threadIdx.x == 0 && int(blockIdx.x) < groups)
+        trace[size_t(blockIdx.x) * kTraceSlots + slot] = wall_clock64();
 }
 
 #endif  // __HIPCC__

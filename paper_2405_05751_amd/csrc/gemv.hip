@@ -18,6 +18,7 @@
 //     partials in slab order (so the result does not depend on arrival order), scales by
 //     1/sqrt(A/K + eps), rounds once and stores.
 #include "common.hpp"
+#include "splitk.hpp"
 
 namespace rmsnl {
 
@@ -29,10 +30,10 @@ struct GemvArgs {
     int S;           // number of slabs
     int n_tiles;
     float* ws_partial; float* ws_sumsq; unsigned* counter;
+    unsigned long long* trace; int trace_groups;
 };
 
 constexpr int kWAux = 2;             // cache policy of the W loads: nt (streamed once)
-constexpr int kSumsqStride = 16;     // floats per slab in ws_sumsq
 constexpr int kOut = 0x7ffffff0;     // a byte offset beyond any buffer resource: reads as zero
 constexpr int kRsrcFlags = 0x00020000;
 
@@ -54,6 +55,7 @@ __global__ __launch_bounds__(256) void gemv_splitk_kernel(GemvArgs a)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int grp = lane / LPR, col8 = lane % LPR;
+    trace_stamp(a.trace, a.trace_groups, 0);         // start
 
     // workgroups are dealt round-robin to the 8 XCDs; renumber so that the slabs of one tile share
     // an XCD (a locality hint only: nothing below depends on where a workgroup runs)
@@ -98,6 +100,7 @@ __global__ __launch_bounds__(256) void gemv_splitk_kernel(GemvArgs a)
 #pragma unroll
     for (int d = 0; d < D; ++d)
         if (d < nB) issue(d, d);             // the queue is full before anything else happens
+    trace_stamp(a.trace, a.trace_groups, 1);         // first loads issued
 
     float ss[MT];
 #pragma unroll
@@ -195,6 +198,7 @@ __global__ __launch_bounds__(256) void gemv_splitk_kernel(GemvArgs a)
         }
     }
 
+    trace_stamp(a.trace, a.trace_groups, 2);         // K loop done (all W consumed by wave 0)
     // ---- reduce over the lane groups of the wave, then over the four waves through LDS.
     // In register mode every lane of a group carries the same ss, so the group sum over lanes
     // col8 == 0 is what the shuffles over the group index produce.
@@ -229,103 +233,9 @@ __global__ __launch_bounds__(256) void gemv_splitk_kernel(GemvArgs a)
     }
     __syncthreads();
 
-    constexpr int PAIRS = MT * N_TILE / 2;   // column pairs of the tile, 256 threads share them
-    constexpr int PPT = (PAIRS + 255) / 256; // column pairs per thread
-    constexpr int WSTR = MT * N_TILE / 2;    // float2 stride between the waves' copies in red
-    float asum = 0.f;
-    if (FUSED && tid < MT) asum = (s_sumsq[0][tid] + s_sumsq[1][tid]) + (s_sumsq[2][tid] + s_sumsq[3][tid]);
-
-    if (a.S == 1) {
-        if (tid < MT) s_rinv[tid] = FUSED ? row_scale(asum, a.inv_K, a.eps) : 1.f;
-        __syncthreads();
-#pragma unroll
-        for (int pi = 0; pi < PPT; ++pi) {
-            const int p = tid + pi * 256;
-            const int m = p / (N_TILE / 2), c = (p % (N_TILE / 2)) * 2;
-            if (p < PAIRS && m < a.M && n0 + c < a.N) {
-                const float2_t* q = (const float2_t*)(red + m * N_TILE + c);
-                const float2_t v = (q[0] + q[WSTR]) + (q[2 * WSTR] + q[3 * WSTR]);
-                const float ri = s_rinv[m];
-                *(uint32_t*)(a.Y + size_t(m) * a.N + n0 + c) = Elem<T>::pack(v[0] * ri, v[1] * ri);
-            }
-        }
-        return;
-    }
-
-    // ---- split-K.  Partials are written through to memory with device-scope stores (no cache-wide
-    // write-back is needed to publish them); every wave waits for its own stores, the workgroup
-    // meets at a barrier, and only then one thread bumps the tile's counter.
-    if (FUSED && tid < MT) st_dev(a.ws_sumsq + slab * kSumsqStride + tid, asum);
-#pragma unroll
-    for (int pi = 0; pi < PPT; ++pi) {
-        const int p = tid + pi * 256;
-        const int m = p / (N_TILE / 2), c = (p % (N_TILE / 2)) * 2;
-        if (p < PAIRS && m < a.M && n0 + c < a.N) {
-            const float2_t* q = (const float2_t*)(red + m * N_TILE + c);
-            const float2_t v = (q[0] + q[WSTR]) + (q[2 * WSTR] + q[3 * WSTR]);
-            st_dev2(a.ws_partial + (size_t(slab) * a.M + m) * a.N + n0 + c, v);
-        }
-    }
-    __builtin_amdgcn_s_waitcnt(0);           // this wave's stores have been acknowledged
-    __syncthreads();
-    if (tid == 0) {
-        unsigned prev = __hip_atomic_fetch_add(a.counter + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = (prev == unsigned(a.S - 1));
-    }
-    __syncthreads();
-    if (!s_last) return;
-
-    // ---- last arriver: device-scope loads see what the other slabs wrote through.
-    // A_i: wave 3 reads the S partial sums of squares, one slab per lane, all loads in flight at
-    // once; lane order and the shuffle tree fix the order of the additions.
-    if (wave == 3) {
-        float t[MT];
-#pragma unroll
-        for (int m = 0; m < MT; ++m) t[m] = 0.f;
-        if (FUSED) {
-            for (int s = lane; s < a.S; s += 64)
-#pragma unroll
-                for (int m = 0; m < MT; ++m) t[m] += ld_dev(a.ws_sumsq + s * kSumsqStride + m);
-        }
-#pragma unroll
-        for (int m = 0; m < MT; ++m) {
-            const float tot = wave_sum(t[m]);
-            if (lane == 0) s_rinv[m] = FUSED ? row_scale(tot, a.inv_K, a.eps) : 1.f;
-        }
-    }
-    float2_t yv[PPT];
-#pragma unroll
-    for (int pi = 0; pi < PPT; ++pi) {
-        const int p = tid + pi * 256;
-        const int m = p / (N_TILE / 2), c = (p % (N_TILE / 2)) * 2;
-        yv[pi] = float2_t{0.f, 0.f};
-        if (p < PAIRS && m < a.M && n0 + c < a.N) {
-            const float* src = a.ws_partial + size_t(m) * a.N + n0 + c;
-            const size_t sstride = size_t(a.M) * a.N;
-            float2_t v = {0.f, 0.f};
-            for (int s0 = 0; s0 < a.S; s0 += 16) {   // sixteen loads in flight, added in slab order
-                float2_t q[16];
-#pragma unroll
-                for (int j = 0; j < 16; ++j)
-                    q[j] = (s0 + j < a.S) ? ld_dev2(src + (s0 + j) * sstride) : float2_t{0.f, 0.f};
-#pragma unroll
-                for (int j = 0; j < 16; ++j) v += q[j];
-            }
-            yv[pi] = v;
-        }
-    }
-    __syncthreads();                         // s_rinv is ready
-#pragma unroll
-    for (int pi = 0; pi < PPT; ++pi) {
-        const int p = tid + pi * 256;
-        const int m = p / (N_TILE / 2), c = (p % (N_TILE / 2)) * 2;
-        if (p < PAIRS && m < a.M && n0 + c < a.N) {
-            const float ri = s_rinv[m];
-            *(uint32_t*)(a.Y + size_t(m) * a.N + n0 + c) = Elem<T>::pack(yv[pi][0] * ri, yv[pi][1] * ri);
-        }
-    }
-    if (tid == 0)                            // ready for the next call on this stream
-        __hip_atomic_store(a.counter + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    trace_stamp(a.trace, a.trace_groups, 3);         // workgroup partial in LDS
+    TailArgs ta{a.Y, a.M, a.N, a.eps, a.inv_K, a.S, a.ws_partial, a.ws_sumsq, a.counter, a.trace, a.trace_groups};
+    splitk_tail<T, MT, N_TILE, FUSED>(ta, red, &s_sumsq[0][0], s_rinv, &s_last, tile, slab, n0);
 }
 
 // ------------------------------------------------------------------------------------------- host
@@ -340,7 +250,7 @@ static GemvPlan gemv_plan(const Problem& p)
     if (p.N % 8 != 0 || p.K % 8 != 0) { pl.why = "gemv variant needs N % 8 == 0 and K % 8 == 0"; return pl; }
     if (int64_t(p.M) * p.K * 2 >= (int64_t(1) << 31)) { pl.why = "gemv variant needs M*K < 2^30"; return pl; }
     pl.MT = p.M <= 1 ? 1 : p.M <= 2 ? 2 : p.M <= 4 ? 4 : p.M <= 8 ? 8 : 16;
-    int n_tile = p.n_tile ? p.n_tile : 256;
+    int n_tile = p.n_tile ? p.n_tile : 128;
     if (n_tile != 64 && n_tile != 128 && n_tile != 256 && n_tile != 512) {
         pl.why = "gemv n_tile must be 64, 128, 256 or 512";
         return pl;
@@ -349,14 +259,12 @@ static GemvPlan gemv_plan(const Problem& p)
     pl.LPR = n_tile / 8;
     pl.n_tiles = (p.N + n_tile - 1) / n_tile;
     const int gran = 8 * 4 * (64 / pl.LPR);                    // 8 rows per batch and lane group
-    const int depth_rows = gran * gemv_depth(pl.MT);           // rows that fill the load queue once
     int S = p.k_split;
     if (S <= 0) {
-        // as many slabs as give every workgroup one full queue of loads, but not more workgroups
-        // than about two per compute unit
-        S = (p.K + depth_rows - 1) / depth_rows;
-        const int s_cap = (512 + pl.n_tiles - 1) / pl.n_tiles;
-        if (S > s_cap) S = s_cap;
+        // about two workgroups per compute unit, but no slab shorter than two batches per lane group
+        S = (512 + pl.n_tiles - 1) / pl.n_tiles;
+        const int s_max = (p.K + 2 * gran - 1) / (2 * gran);
+        if (S > s_max) S = s_max;
         if (S < 1) S = 1;
     }
     int k_slab = (p.K + S - 1) / S;
@@ -370,7 +278,8 @@ static GemvPlan gemv_plan(const Problem& p)
     pl.S = S;
     pl.k_slab = k_slab;
     if (pl.n_tiles > kMaxCounters) { pl.why = "too many column tiles"; return pl; }
-    if (S * kSumsqStride > kMaxSumsqFloats) { pl.why = "too many K slabs"; return pl; }
+    if (int64_t(pl.n_tiles) * S * kSumsqStride > kMaxSumsqFloats) { pl.why = "too many K slabs"; return pl; }
+    if (int64_t(S + 8) * p.M * p.N * 4 >= (int64_t(1) << 31)) { pl.why = "split-K partials too large"; return pl; }
     const size_t xs = pl.MT > 4 ? size_t(k_slab) * pl.MT * 4 : 0;
     const size_t red = size_t(4) * pl.MT * n_tile * 4;
     pl.lds = xs > red ? xs : red;
@@ -439,6 +348,7 @@ hipError_t launch_gemv(const Problem& p, hipStream_t s, const char** why)
     a.M = p.M; a.K = p.K; a.N = p.N; a.eps = p.eps; a.inv_K = 1.0f / float(p.K);
     a.k_slab = pl.k_slab; a.S = pl.S; a.n_tiles = pl.n_tiles;
     a.ws_partial = p.ws_partial; a.ws_sumsq = p.ws_sumsq; a.counter = p.ws_counter;
+    a.trace = p.trace; a.trace_groups = p.trace_groups;
     return p.dt == F16 ? gemv_mt<Fp16>(a, p.fused != 0, pl, s) : gemv_mt<Bf16>(a, p.fused != 0, pl, s);
 }
 

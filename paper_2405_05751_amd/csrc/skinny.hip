@@ -1,14 +1,280 @@
-// Matrix-core variant for small M (placeholder until the kernel lands).
+// Matrix-core variant of the fused RMSNorm + MatMul for small M (M <= 64): still bound by streaming
+// W once from HBM, but each W element now meets up to 64 rows of X-hat, which plain FMAs could not
+// keep up with.  One v_mfma_f32_16x16x32 per 16 rows x 16 columns x 32 k.
+//
+// W never passes through LDS.  The matrix instruction wants, per lane, 8 consecutive k of ONE
+// column, while W [K][N] offers 8 consecutive columns of one k per 16-byte load.  The k index
+// inside an instruction is only a label, so the lanes are laid out as i = lane % 16 (column
+// chunk) and q = lane / 16 (k group): lane (i, q) loads the 8x8 block
+// W[kb + 8q .. +7][n0 + 8i .. +7] with eight coalesced dwordx4 loads (a wave-wide load covers 4
+// rows of 256 contiguous bytes).  For each of the 8 columns c of the block, the B operand of MFMA
+// #c is the column of that register block -- four v_perm_b32 pick it out -- and MFMA #c as a whole
+// computes the 16 strided columns {n0 + 8i + c}.  The A operand of lane (m, q) is
+// X-hat[m][kb + 8q .. +7]: one 16-byte load of X, times g, rounded once to the 16-bit type;
+// the squares of the raw X feed A_i in the same pass (the paper's two accumulators in one K loop).
+//
+// A workgroup owns 128 columns and one K slab; its four waves take alternate 32-row steps of the
+// slab, so nothing in the K loop needs a barrier.  The waves' fp32 tiles meet in LDS, and the
+// common split-K epilogue finishes (see splitk.hpp).
 #include "common.hpp"
+#include "splitk.hpp"
 
 namespace rmsnl {
 
-size_t skinny_workspace_bytes(const Problem&) { return 0; }
+struct SkinnyArgs {
+    const u16* X; const u16* g; const uint4_t* W; u16* Y;
+    int M, K, N;
+    float eps, inv_K;
+    int k_slab;      // rows of W per slab, a multiple of 128 (4 waves x 32 rows)
+    int S;
+    int n_tiles;
+    float* ws_partial; float* ws_sumsq; unsigned* counter;
+    unsigned long long* trace; int trace_groups;
+};
 
-hipError_t launch_skinny(const Problem&, hipStream_t, const char** why)
+constexpr int kSkinnyTile = 128;     // columns per workgroup
+constexpr int kSkAux = 2;            // W loads: nt
+constexpr int kSkOut = 0x7ffffff0;
+constexpr int kSkFlags = 0x00020000;
+
+template <typename T> struct Mfma16;
+template <> struct Mfma16<Bf16> {
+    static __device__ __forceinline__ float4_t run(uint4_t a, uint4_t b, float4_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+};
+template <> struct Mfma16<Fp16> {
+    static __device__ __forceinline__ float4_t run(uint4_t a, uint4_t b, float4_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a),
+                                                      __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+    }
+};
+
+// steps (8 W loads per lane each) kept in flight per wave
+constexpr int skinny_depth(int MB) { return MB <= 2 ? 4 : 3; }
+
+template <typename T, int MB, bool FUSED>
+__global__ __launch_bounds__(256) void skinny_kernel(SkinnyArgs a)
 {
-    if (why) *why = "skinny variant not built yet";
-    return hipErrorInvalidValue;
+    constexpr int MT = 16 * MB;
+    constexpr int N_TILE = kSkinnyTile;
+    constexpr int D = skinny_depth(MB);
+    extern __shared__ float smem[];          // red [4][MT][N_TILE]
+    __shared__ float s_sumsq[4][MT];
+    __shared__ float s_rinv[MT];
+    __shared__ int s_last;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 15, q = lane >> 4;
+    trace_stamp(a.trace, a.trace_groups, 0);
+
+    int b = blockIdx.x;
+    const int total = a.n_tiles * a.S;
+    if ((total & 7) == 0) b = (b & 7) * (total >> 3) + (b >> 3);   // slabs of a tile share an XCD (hint)
+    const int tile = b / a.S, slab = b % a.S;
+    const int n0 = tile * N_TILE;
+    const int k0 = slab * a.k_slab;
+    const int klen = min(a.k_slab, a.K - k0);
+    const int nSteps = a.k_slab >> 7;        // 32-row steps per wave (uniform; rows past klen read zero)
+
+    const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint4_t*>(a.W + size_t(k0) * (a.N >> 3)), 0, klen * a.N * 2, kSkFlags);
+    const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<u16*>(a.X), 0, a.M * a.K * 2, kSkFlags);           // rows >= M read as zero
+    const __amdgpu_buffer_rsrc_t grs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<u16*>(FUSED ? a.g : a.X), 0, a.K * 2, kSkFlags);
+    const int wrow = a.N * 2;
+    // step s of this wave covers slab rows (4s + wave)*32 .. +31; this lane's rows start 8q in
+    const int woff0 = ((wave * 32 + q * 8) * a.N + n0 + i * 8) * 2;
+    const int wstep = 128 * a.N * 2;
+    const int xrow0 = i * a.K * 2;           // row i of X (row 16*mb + i adds mb * 16 rows)
+
+    uint4_t w[D][8];
+    uint4_t xq[D][MB], gq[D];
+    auto issue = [&](int s, int d) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            w[d][j] = __builtin_amdgcn_raw_buffer_load_b128(wrs, woff0 + s * wstep + j * wrow, 0, kSkAux);
+        const int kr = (4 * s + wave) * 32 + q * 8;               // slab-relative k of this lane's chunk
+        const int koff = kr < klen ? (k0 + kr) * 2 : kSkOut;
+        if (FUSED) gq[d] = __builtin_amdgcn_raw_buffer_load_b128(grs, koff, 0, 0);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+            xq[d][mb] = __builtin_amdgcn_raw_buffer_load_b128(
+                xrs, kr < klen ? koff + xrow0 + mb * 16 * a.K * 2 : kSkOut, 0, 0);
+    };
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        if (d < nSteps) issue(d, d);
+    trace_stamp(a.trace, a.trace_groups, 1);
+
+    float4_t acc[MB][8];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[mb][c] = float4_t{0.f, 0.f, 0.f, 0.f};
+    float ss[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) ss[mb] = 0.f;
+
+    auto consume = [&](int d) {
+        // A operands: X-hat = X (.) g rounded once to the storage type; squares of the raw X
+        uint4_t aop[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            if (FUSED) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float x0 = Elem<T>::lo(xq[d][mb][e]), x1 = Elem<T>::hi(xq[d][mb][e]);
+                    ss[mb] = __fmaf_rn(x0, x0, ss[mb]);
+                    ss[mb] = __fmaf_rn(x1, x1, ss[mb]);
+                    aop[mb][e] = Elem<T>::pack(x0 * Elem<T>::lo(gq[d][e]), x1 * Elem<T>::hi(gq[d][e]));
+                }
+            } else {
+                aop[mb] = xq[d][mb];
+            }
+        }
+        // B operands: column c of the lane's 8x8 block, rows paired (2t, 2t+1)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            uint4_t bop;
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                bop[t] = __builtin_amdgcn_perm(w[d][2 * t + 1][c >> 1], w[d][2 * t][c >> 1],
+                                               (c & 1) ? 0x07060302u : 0x05040100u);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) acc[mb][c] = Mfma16<T>::run(aop[mb], bop, acc[mb][c]);
+        }
+    };
+
+    for (int s0 = 0; s0 < nSteps; s0 += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int s = s0 + d;
+            if (s < nSteps) {                // uniform over the workgroup
+                consume(d);
+                if (s + D < nSteps) issue(s + D, d);
+            }
+        }
+    }
+    trace_stamp(a.trace, a.trace_groups, 2);
+
+    // ---- A_i: add the four k groups of the wave (lanes i, i+16, i+32, i+48 hold row i's shares)
+    if (FUSED) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            float v = ss[mb];
+            v += __shfl_xor(v, 16, 64);
+            v += __shfl_xor(v, 32, 64);
+            if (q == 0) s_sumsq[wave][mb * 16 + i] = v;
+        }
+    }
+    // ---- B: lane (i, q) holds rows 16mb + 4q + r, columns n0 + 8i + c of its wave's partial tile
+    float* red = smem;                       // [4][MT][N_TILE]
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float4_t* dst = (float4_t*)(red + ((wave * MT) + mb * 16 + q * 4 + r) * N_TILE + i * 8);
+            dst[0] = float4_t{acc[mb][0][r], acc[mb][1][r], acc[mb][2][r], acc[mb][3][r]};
+            dst[1] = float4_t{acc[mb][4][r], acc[mb][5][r], acc[mb][6][r], acc[mb][7][r]};
+        }
+    __syncthreads();
+    trace_stamp(a.trace, a.trace_groups, 3);
+
+    TailArgs ta{a.Y, a.M, a.N, a.eps, a.inv_K, a.S, a.ws_partial, a.ws_sumsq, a.counter, a.trace, a.trace_groups};
+    splitk_tail<T, MT, N_TILE, FUSED>(ta, red, &s_sumsq[0][0], s_rinv, &s_last, tile, slab, n0);
+}
+
+// ------------------------------------------------------------------------------------------- host
+struct SkinnyPlan { int MB, S, k_slab, n_tiles; size_t lds; bool ok; const char* why; };
+
+static SkinnyPlan skinny_plan(const Problem& p)
+{
+    SkinnyPlan pl{};
+    pl.ok = false;
+    if (p.dt == F32) { pl.why = "skinny variant handles 16-bit types only"; return pl; }
+    if (p.M > 64) { pl.why = "skinny variant needs M <= 64"; return pl; }
+    if (p.N % 8 != 0 || p.K % 8 != 0) { pl.why = "skinny variant needs N % 8 == 0 and K % 8 == 0"; return pl; }
+    if (int64_t(p.M) * p.K * 2 >= (int64_t(1) << 31)) { pl.why = "skinny variant needs M*K < 2^30"; return pl; }
+    if (p.n_tile != 0 && p.n_tile != kSkinnyTile) { pl.why = "skinny n_tile must be 128"; return pl; }
+    pl.MB = (p.M + 15) / 16;
+    pl.n_tiles = (p.N + kSkinnyTile - 1) / kSkinnyTile;
+    const int gran = 128;
+    int S = p.k_split;
+    if (S <= 0) {
+        // the largest power of two that keeps the grid at or under one workgroup per compute unit:
+        // every extra slab adds a tile of fp32 partials to write and read back
+        S = 1;
+        while (2 * S * pl.n_tiles <= 256 && 2 * S * gran * 2 <= p.K) S *= 2;
+    }
+    int k_slab = (p.K + S - 1) / S;
+    k_slab = (k_slab + gran - 1) / gran * gran;
+    while (int64_t(k_slab) * p.N * 2 >= (int64_t(1) << 31)) k_slab = (k_slab / 2 + gran - 1) / gran * gran;
+    S = (p.K + k_slab - 1) / k_slab;
+    pl.S = S;
+    pl.k_slab = k_slab;
+    if (pl.n_tiles > kMaxCounters) { pl.why = "too many column tiles"; return pl; }
+    if (int64_t(pl.n_tiles) * S * kSumsqStride > kMaxSumsqFloats) { pl.why = "too many K slabs"; return pl; }
+    if (int64_t(S + 8) * p.M * p.N * 4 >= (int64_t(1) << 31)) { pl.why = "split-K partials too large"; return pl; }
+    pl.lds = size_t(4) * 16 * pl.MB * kSkinnyTile * 4;
+    pl.ok = true;
+    return pl;
+}
+
+size_t skinny_workspace_bytes(const Problem& p)
+{
+    SkinnyPlan pl = skinny_plan(p);
+    if (!pl.ok || pl.S <= 1) return 0;
+    return size_t(pl.S) * p.M * p.N * 4;
+}
+
+template <typename T, int MB>
+static hipError_t skinny_go(const SkinnyArgs& a, bool fused, const SkinnyPlan& pl, hipStream_t s)
+{
+    dim3 grid(pl.n_tiles * pl.S);
+    static bool lds_raised = false;          // 128 KiB of dynamic LDS at MB = 4
+    if (!lds_raised) {
+        hipError_t e = hipFuncSetAttribute((const void*)skinny_kernel<T, MB, true>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void*)skinny_kernel<T, MB, false>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+        if (e != hipSuccess) return e;
+        lds_raised = true;
+    }
+    if (fused) skinny_kernel<T, MB, true><<<grid, 256, pl.lds, s>>>(a);
+    else       skinny_kernel<T, MB, false><<<grid, 256, pl.lds, s>>>(a);
+    return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t skinny_mb(const SkinnyArgs& a, bool fused, const SkinnyPlan& pl, hipStream_t s)
+{
+    switch (pl.MB) {
+    case 1:  return skinny_go<T, 1>(a, fused, pl, s);
+    case 2:  return skinny_go<T, 2>(a, fused, pl, s);
+    case 3:  return skinny_go<T, 3>(a, fused, pl, s);
+    default: return skinny_go<T, 4>(a, fused, pl, s);
+    }
+}
+
+hipError_t launch_skinny(const Problem& p, hipStream_t s, const char** why)
+{
+    SkinnyPlan pl = skinny_plan(p);
+    if (!pl.ok) { if (why) *why = pl.why; return hipErrorInvalidValue; }
+    if (pl.S > 1 && (!p.ws_partial || !p.ws_sumsq || !p.ws_counter)) {
+        if (why) *why = "split-K needs the workspace";
+        return hipErrorInvalidValue;
+    }
+    SkinnyArgs a;
+    a.X = (const u16*)p.X; a.g = (const u16*)p.g; a.W = (const uint4_t*)p.W; a.Y = (u16*)p.Y;
+    a.M = p.M; a.K = p.K; a.N = p.N; a.eps = p.eps; a.inv_K = 1.0f / float(p.K);
+    a.k_slab = pl.k_slab; a.S = pl.S; a.n_tiles = pl.n_tiles;
+    a.ws_partial = p.ws_partial; a.ws_sumsq = p.ws_sumsq; a.counter = p.ws_counter;
+    a.trace = p.trace; a.trace_groups = p.trace_groups;
+    return p.dt == F16 ? skinny_mb<Fp16>(a, p.fused != 0, pl, s) : skinny_mb<Bf16>(a, p.fused != 0, pl, s);
 }
 
 }  // namespace rmsnl

@@ -49,7 +49,7 @@ def _run(rl, w, variant="auto", tuning=(0, 0), rows=None):
     return to_host_f64(Y, w.dtype), used
 
 
-NOT_BUILT = {"skinny", "tile"}       # variants whose kernels have not landed yet
+NOT_BUILT = {"tile"}                 # variants whose kernels have not landed yet
 
 
 def _supported(variant, w):
@@ -308,7 +308,7 @@ def test_lent_workspace(rl):
     w, Z = _workload("decode")
     need = rl.rl_workspace_bytes(w.M, w.K, w.N, torch.bfloat16)
     assert need > 0
-    small = torch.zeros((320 * 1024 + 4096) // 4, dtype=torch.float32, device="cuda")   # head fits, partials do not
+    small = torch.zeros((need - 8192) // 4, dtype=torch.float32, device="cuda")   # head fits, partials do not
     big = torch.zeros(need // 4 + 16, dtype=torch.float32, device="cuda")
     X, g, W = upload(w)
     try:
@@ -320,7 +320,7 @@ def test_lent_workspace(rl):
         Y = rl.rmsnorm_linear(X, g, W, w.eps)
         torch.cuda.synchronize()
         compare(to_host_f64(Y, w.dtype), Z, w.dtype, "decode with lent workspace")
-        assert big[: 64 * 1024 // 4].abs().sum().item() == 0      # counters returned to zero
+        assert big[: 256 * 1024 // 4].abs().sum().item() == 0      # counters returned to zero
     finally:
         rl.rl_set_workspace(None)
 
