@@ -1,12 +1,272 @@
-// Matrix-core variant for large M (placeholder until the kernel lands).
+// Matrix-core variant of the fused RMSNorm + MatMul for large M (prefill): bound by the dense
+// contraction, so the design is a 256x256 output tile per workgroup on v_mfma_f32_32x32x16.
+//
+//   * 4 waves in a 2x2 arrangement, each owning 128x128 of the tile = 4x4 MFMA tiles, 256 fp32
+//     accumulators per lane (the B accumulator of the paper's fused kernel);
+//   * K advances in steps of 64 through two LDS buffers.  X goes global -> registers -> LDS, and on
+//     the way it is multiplied by g, rounded once to the 16-bit type (X-hat), and its raw squares
+//     are added to a per-row running sum (the A accumulator): the two accumulations share the K
+//     loop and the work is done once per workgroup, at staging, not per wave on fragments;
+//   * W goes global -> registers -> LDS as it lies in memory ([k][n], n contiguous).  The matrix
+//     instruction wants 8 consecutive k of one column per lane, so the B fragments are fetched with
+//     the transposing LDS read (ds_read_b64_tr_b16): within 16 lanes, lane j supplies the address
+//     of 4 columns of row j/4 and receives the 4 rows of column j;
+//   * LDS rows are padded (X-hat rows to 144 B, W rows to 576 B) so that the 16-byte fragment reads
+//     and the transposing reads fall on distinct banks;
+//   * epilogue: rinv_i = 1/sqrt(A_i/K + eps) per row, Y = B * rinv in fp32, one rounding, store.
+//
+// Out-of-range rows of X and W read as zero through buffer resources; ragged M, N and K % 64 are
+// handled by those reads and by guarded stores (N % 8 == 0 and K % 8 == 0 are required).
 #include "common.hpp"
 
 namespace rmsnl {
 
-hipError_t launch_tile(const Problem&, hipStream_t, const char** why)
+struct TileArgs {
+    const u16* X; const u16* g; const u16* W; u16* Y;
+    int M, K, N;
+    float eps, inv_K;
+    int tiles_m, tiles_n;
+};
+
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int LDA = BK + 8;          // elements per X-hat row in LDS (144 bytes)
+constexpr int LDB = BN + 32;         // elements per W row in LDS (576 bytes)
+constexpr int kTileOut = 0x7ffffff0;
+constexpr int kTileFlags = 0x00020000;
+constexpr size_t kTileLds = size_t(2) * (BM * LDA + BK * LDB) * 2 + BM * 4 * 2;
+
+template <typename T> struct Mfma32;
+template <> struct Mfma32<Bf16> {
+    static __device__ __forceinline__ float16_t run(uint4_t a, uint4_t b, float16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+};
+template <> struct Mfma32<Fp16> {
+    static __device__ __forceinline__ float16_t run(uint4_t a, uint4_t b, float16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a),
+                                                      __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+    }
+};
+
+typedef __attribute__((ext_vector_type(4))) short short4_t;
+typedef __attribute__((address_space(3))) short4_t* lds_short4_ptr;
+
+// transposing LDS read of 4 x 16-bit values (see the header comment)
+__device__ __forceinline__ uint2_t lds_read_tr(const u16* p) {
+    short4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(p));
+    return __builtin_bit_cast(uint2_t, v);
+}
+
+template <typename T, bool FUSED>
+__global__ __launch_bounds__(256, 1) void tile_kernel(TileArgs a)
 {
-    if (why) *why = "tile variant not built yet";
-    return hipErrorInvalidValue;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    u16* As = (u16*)lds_raw;                             // [2][BM][LDA]
+    u16* Bs = As + 2 * BM * LDA;                         // [2][BK][LDB]
+    float* s_ss = (float*)(Bs + 2 * BK * LDB);           // [BM] sums of squares
+    float* s_rinv = s_ss + BM;                           // [BM]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // Tile order: workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  When the
+    // grid allows, XCD x works through a band of tile rows, four rows at a time, so the ~32 tiles
+    // it runs together share few X and W panels in that L2.
+    int tm, tn;
+    {
+        const int b = blockIdx.x, total = a.tiles_m * a.tiles_n;
+        if ((a.tiles_m & 7) == 0) {
+            const int band = a.tiles_m >> 3;             // tile rows per XCD
+            const int x = b & 7, idx = b >> 3;           // idx in [0, band * tiles_n)
+            const int grp_rows = (band & 3) == 0 ? 4 : (band & 1) == 0 ? 2 : 1;
+            const int per_grp = grp_rows * a.tiles_n;
+            const int grp = idx / per_grp, in = idx % per_grp;
+            tm = x * band + grp * grp_rows + in % grp_rows;
+            tn = in / grp_rows;
+        } else {
+            tm = b / a.tiles_n; tn = b % a.tiles_n;
+        }
+        (void)total;
+    }
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int rows_here = min(BM, a.M - m0);
+
+    const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<u16*>(a.X + size_t(m0) * a.K), 0, rows_here * a.K * 2, kTileFlags);
+    const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<u16*>(a.W), 0, a.K * a.N * 2, kTileFlags);
+    const __amdgpu_buffer_rsrc_t grs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<u16*>(FUSED ? a.g : a.X), 0, a.K * 2, kTileFlags);
+
+    // staging roles: X chunk (row ar + 32 j, 8 k at ac) and W chunk (row br + 8 j, 8 columns at bc)
+    const int ar = tid >> 3, ac = (tid & 7) * 8;
+    const int br = tid >> 5, bc = (tid & 31) * 8;
+    const bool bcol_ok = n0 + bc < a.N;
+
+    uint4_t xa[8], wb[8], gv;
+    auto load_global = [&](int k0) {
+        const bool kin = k0 + ac < a.K;
+        if (FUSED) gv = __builtin_amdgcn_raw_buffer_load_b128(grs, kin ? (k0 + ac) * 2 : kTileOut, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            xa[j] = __builtin_amdgcn_raw_buffer_load_b128(
+                xrs, kin ? ((ar + 32 * j) * a.K + k0 + ac) * 2 : kTileOut, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            wb[j] = __builtin_amdgcn_raw_buffer_load_b128(
+                wrs, bcol_ok ? ((k0 + br + 8 * j) * a.N + n0 + bc) * 2 : kTileOut, 0, 0);
+    };
+
+    float ssq[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ssq[j] = 0.f;
+
+    auto store_lds = [&](int buf) {
+        u16* Ab = As + buf * BM * LDA;
+        u16* Bb = Bs + buf * BK * LDB;
+        float gf[8];
+        if (FUSED) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { gf[2 * e] = Elem<T>::lo(gv[e]); gf[2 * e + 1] = Elem<T>::hi(gv[e]); }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            uint4_t o = xa[j];
+            if (FUSED) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float x0 = Elem<T>::lo(xa[j][e]), x1 = Elem<T>::hi(xa[j][e]);
+                    ssq[j] = __fmaf_rn(x0, x0, ssq[j]);
+                    ssq[j] = __fmaf_rn(x1, x1, ssq[j]);
+                    o[e] = Elem<T>::pack(x0 * gf[2 * e], x1 * gf[2 * e + 1]);
+                }
+            }
+            *(uint4_t*)(Ab + (ar + 32 * j) * LDA + ac) = o;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) *(uint4_t*)(Bb + (br + 8 * j) * LDB + bc) = wb[j];
+    };
+
+    float16_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // fragment addresses (elements): A row l%32 of each MFMA tile, 8 k at 8*(l/32);
+    // B: 16-lane block blk, lane j in it: row 8*(blk/2) + j/4 (+4 second read), columns 16*(blk%2) + 4*(j%4)
+    const int a_off = (wm * 128 + (lane & 31)) * LDA + 8 * (lane >> 5);
+    const int blk = lane >> 4, jj = lane & 15;
+    const int b_off = (8 * (blk >> 1) + (jj >> 2)) * LDB + wn * 128 + 16 * (blk & 1) + 4 * (jj & 3);
+
+    auto compute = [&](int buf) {
+        const u16* Ab = As + buf * BM * LDA + a_off;
+        const u16* Bb = Bs + buf * BK * LDB + b_off;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            uint4_t af[4], bf[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) af[i] = *(const uint4_t*)(Ab + i * 32 * LDA + ks * 16);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint2_t lo = lds_read_tr(Bb + (ks * 16) * LDB + j * 32);
+                const uint2_t hi = lds_read_tr(Bb + (ks * 16 + 4) * LDB + j * 32);
+                bf[j] = uint4_t{lo[0], lo[1], hi[0], hi[1]};
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = Mfma32<T>::run(af[i], bf[j], acc[i][j]);
+        }
+    };
+
+    const int nk = (a.K + BK - 1) / BK;
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 1 < nk) load_global((kt + 1) * BK);
+        compute(kt & 1);
+        if (kt + 1 < nk) store_lds((kt + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- A_i: the 8 threads that share a row (tid & 7) add their shares
+    if (FUSED) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            float v = ssq[j];
+            v += __shfl_xor(v, 1, 64);
+            v += __shfl_xor(v, 2, 64);
+            v += __shfl_xor(v, 4, 64);
+            if ((tid & 7) == 0) s_ss[ar + 32 * j] = v;
+        }
+        __syncthreads();
+        s_rinv[tid] = row_scale(s_ss[tid], a.inv_K, a.eps);
+        __syncthreads();
+    }
+
+    // ---- epilogue: D register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its tile
+    const int col_l = lane & 31, rowq = 4 * (lane >> 5);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = wm * 128 + i * 32 + 8 * (r >> 2) + rowq + (r & 3);
+            const float ri = FUSED ? s_rinv[row] : 1.f;
+            if (m0 + row < a.M) {
+                u16* yrow = a.Y + size_t(m0 + row) * a.N + n0 + wn * 128 + col_l;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (n0 + wn * 128 + j * 32 + col_l < a.N) yrow[j * 32] = Elem<T>::from_f32(acc[i][j][r] * ri);
+            }
+        }
+}
+
+// ------------------------------------------------------------------------------------------- host
+hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
+{
+    if (p.dt == F32) { if (why) *why = "tile variant handles 16-bit types only"; return hipErrorInvalidValue; }
+    if (p.N % 8 != 0 || p.K % 8 != 0) {
+        if (why) *why = "tile variant needs N % 8 == 0 and K % 8 == 0";
+        return hipErrorInvalidValue;
+    }
+    if (int64_t(p.K) * p.N * 2 >= (int64_t(1) << 31) || int64_t(BM) * p.K * 2 >= (int64_t(1) << 31)) {
+        if (why) *why = "tile variant needs K*N < 2^30";
+        return hipErrorInvalidValue;
+    }
+    TileArgs a;
+    a.X = (const u16*)p.X; a.g = (const u16*)p.g; a.W = (const u16*)p.W; a.Y = (u16*)p.Y;
+    a.M = p.M; a.K = p.K; a.N = p.N; a.eps = p.eps; a.inv_K = 1.0f / float(p.K);
+    a.tiles_m = (p.M + BM - 1) / BM;
+    a.tiles_n = (p.N + BN - 1) / BN;
+    if (int64_t(a.tiles_m) * a.tiles_n >= (int64_t(1) << 31)) {
+        if (why) *why = "too many tiles";
+        return hipErrorInvalidValue;
+    }
+    dim3 grid(a.tiles_m * a.tiles_n);
+    static bool lds_raised = false;
+    if (!lds_raised) {
+        const void* fns[4] = {(const void*)tile_kernel<Bf16, true>, (const void*)tile_kernel<Bf16, false>,
+                              (const void*)tile_kernel<Fp16, true>, (const void*)tile_kernel<Fp16, false>};
+        for (const void* f : fns) {
+            hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, int(kTileLds));
+            if (e != hipSuccess) return e;
+        }
+        lds_raised = true;
+    }
+    const bool fused = p.fused != 0;
+    if (p.dt == F16) {
+        if (fused) tile_kernel<Fp16, true><<<grid, 256, kTileLds, s>>>(a);
+        else       tile_kernel<Fp16, false><<<grid, 256, kTileLds, s>>>(a);
+    } else {
+        if (fused) tile_kernel<Bf16, true><<<grid, 256, kTileLds, s>>>(a);
+        else       tile_kernel<Bf16, false><<<grid, 256, kTileLds, s>>>(a);
+    }
+    return hipGetLastError();
 }
 
 }  // namespace rmsnl
