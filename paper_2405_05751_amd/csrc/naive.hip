@@ -235,19 +235,27 @@ template <> __device__ __forceinline__ float16_t mfma32<f16x8_t>(f16x8_t a, f16x
 template <typename V>
 __global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ sink, int iters)
 {
+    // operands: pseudo-random values in (-2, 2), different per lane, element and accumulator, so the
+    // datapath toggles like it does on real activations (constant operands draw less power and clock higher)
     typedef __attribute__((ext_vector_type(8))) float float8_t;
-    float8_t af, bf;
-    for (int e = 0; e < 8; ++e) {
-        af[e] = float((threadIdx.x + e) & 7) * 0.125f;
-        bf[e] = float((threadIdx.x * 3 + e) & 7) * 0.0625f;
+    V a[4], b[4];
+    for (int j = 0; j < 4; ++j) {
+        float8_t af, bf;
+        for (int e = 0; e < 8; ++e) {
+            uint32_t h = (threadIdx.x * 8u + e) * 2654435761u + j * 0x9e3779b9u + blockIdx.x * 40503u;
+            h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+            af[e] = float(int(h & 0xffff) - 32768) * (1.0f / 16384.0f);
+            bf[e] = float(int(h >> 16) - 32768) * (1.0f / 16384.0f);
+        }
+        a[j] = __builtin_convertvector(af, V);
+        b[j] = __builtin_convertvector(bf, V);
     }
-    V a = __builtin_convertvector(af, V), b = __builtin_convertvector(bf, V);
     float16_t c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
     for (int it = 0; it < iters; ++it) {
-        c0 = mfma32<V>(a, b, c0);
-        c1 = mfma32<V>(a, b, c1);
-        c2 = mfma32<V>(a, b, c2);
-        c3 = mfma32<V>(a, b, c3);
+        c0 = mfma32<V>(a[0], b[0], c0);
+        c1 = mfma32<V>(a[1], b[1], c1);
+        c2 = mfma32<V>(a[2], b[2], c2);
+        c3 = mfma32<V>(a[3], b[3], c3);
     }
     float r = 0.f;
     for (int e = 0; e < 16; ++e) r += c0[e] + c1[e] + c2[e] + c3[e];

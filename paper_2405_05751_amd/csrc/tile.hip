@@ -19,6 +19,10 @@
 // handled by those reads and by guarded stores (N % 8 == 0 and K % 8 == 0 are required).
 #include "common.hpp"
 
+#ifndef RL_TILE_SKIP
+#define RL_TILE_SKIP 0     // timing experiments only: 1 no fragment reads, 2 no staging, 4 no global loads,
+#endif                     // 8 no barrier, 16 stage constants instead of the loaded data
+
 namespace rmsnl {
 
 struct TileArgs {
@@ -89,6 +93,7 @@ __global__ __launch_bounds__(256, 1) void tile_kernel(TileArgs a)
         }
         (void)total;
     }
+    if (RL_TILE_SKIP & 32) { tm = 0; tn = 0; }
     const int m0 = tm * BM, n0 = tn * BN;
     const int rows_here = min(BM, a.M - m0);
 
@@ -105,47 +110,49 @@ __global__ __launch_bounds__(256, 1) void tile_kernel(TileArgs a)
     const bool bcol_ok = n0 + bc < a.N;
 
     uint4_t xa[8], wb[8], gv;
-    auto load_global = [&](int k0) {
+    // one quarter of a tile's global loads: X rows 32*(h*4+i) + ar (+g with the very first), W rows 8*(h*4+i) + br
+    auto load_piece = [&](int k0, int h, int i) {        // k0 >= K: every load is out of range, zero
         const bool kin = k0 + ac < a.K;
-        if (FUSED) gv = __builtin_amdgcn_raw_buffer_load_b128(grs, kin ? (k0 + ac) * 2 : kTileOut, 0, 0);
+        const int j = h * 4 + i;
+        if (FUSED && j == 0) gv = __builtin_amdgcn_raw_buffer_load_b128(grs, kin ? (k0 + ac) * 2 : kTileOut, 0, 0);
+        xa[j] = __builtin_amdgcn_raw_buffer_load_b128(
+            xrs, kin ? ((ar + 32 * j) * a.K + k0 + ac) * 2 : kTileOut, 0, 0);
+        wb[j] = __builtin_amdgcn_raw_buffer_load_b128(
+            wrs, bcol_ok ? ((k0 + br + 8 * j) * a.N + n0 + bc) * 2 : kTileOut, 0, 0);
+    };
+    auto load_global = [&](int k0) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            xa[j] = __builtin_amdgcn_raw_buffer_load_b128(
-                xrs, kin ? ((ar + 32 * j) * a.K + k0 + ac) * 2 : kTileOut, 0, 0);
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-            wb[j] = __builtin_amdgcn_raw_buffer_load_b128(
-                wrs, bcol_ok ? ((k0 + br + 8 * j) * a.N + n0 + bc) * 2 : kTileOut, 0, 0);
+        for (int j = 0; j < 8; ++j) load_piece(k0, j >> 2, j & 3);
     };
 
     float ssq[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) ssq[j] = 0.f;
 
-    auto store_lds = [&](int buf) {
-        u16* Ab = As + buf * BM * LDA;
-        u16* Bb = Bs + buf * BK * LDB;
-        float gf[8];
+    // one staged X chunk: squares of the raw values, times g, one rounding, into LDS
+    float gf[8];
+    auto unpack_g = [&]() {
         if (FUSED) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) { gf[2 * e] = Elem<T>::lo(gv[e]); gf[2 * e + 1] = Elem<T>::hi(gv[e]); }
         }
+    };
+    auto stage_x = [&](int buf, int j) {
+        uint4_t o = (RL_TILE_SKIP & 16) ? uint4_t{uint32_t(tid), uint32_t(j), 3u, 4u} : xa[j];
+        if (FUSED) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            uint4_t o = xa[j];
-            if (FUSED) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float x0 = Elem<T>::lo(xa[j][e]), x1 = Elem<T>::hi(xa[j][e]);
-                    ssq[j] = __fmaf_rn(x0, x0, ssq[j]);
-                    ssq[j] = __fmaf_rn(x1, x1, ssq[j]);
-                    o[e] = Elem<T>::pack(x0 * gf[2 * e], x1 * gf[2 * e + 1]);
-                }
+            for (int e = 0; e < 4; ++e) {
+                const float x0 = Elem<T>::lo(xa[j][e]), x1 = Elem<T>::hi(xa[j][e]);
+                ssq[j] = __fmaf_rn(x0, x0, ssq[j]);
+                ssq[j] = __fmaf_rn(x1, x1, ssq[j]);
+                o[e] = Elem<T>::pack(x0 * gf[2 * e], x1 * gf[2 * e + 1]);
             }
-            *(uint4_t*)(Ab + (ar + 32 * j) * LDA + ac) = o;
         }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) *(uint4_t*)(Bb + (br + 8 * j) * LDB + bc) = wb[j];
+        *(uint4_t*)(As + buf * BM * LDA + (ar + 32 * j) * LDA + ac) = o;
+    };
+    auto stage_w = [&](int buf, int j) {
+        *(uint4_t*)(Bs + buf * BK * LDB + (br + 8 * j) * LDB + bc) =
+            (RL_TILE_SKIP & 16) ? uint4_t{uint32_t(tid), uint32_t(j), 5u, 6u} : wb[j];
     };
 
     float16_t acc[4][4];
@@ -162,37 +169,82 @@ __global__ __launch_bounds__(256, 1) void tile_kernel(TileArgs a)
     const int blk = lane >> 4, jj = lane & 15;
     const int b_off = (8 * (blk >> 1) + (jj >> 2)) * LDB + wn * 128 + 16 * (blk & 1) + 4 * (jj & 3);
 
-    auto compute = [&](int buf) {
-        const u16* Ab = As + buf * BM * LDA + a_off;
-        const u16* Bb = Bs + buf * BK * LDB + b_off;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            uint4_t af[4], bf[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) af[i] = *(const uint4_t*)(Ab + i * 32 * LDA + ks * 16);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint2_t lo = lds_read_tr(Bb + (ks * 16) * LDB + j * 32);
-                const uint2_t hi = lds_read_tr(Bb + (ks * 16 + 4) * LDB + j * 32);
-                bf[j] = uint4_t{lo[0], lo[1], hi[0], hi[1]};
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = Mfma32<T>::run(af[i], bf[j], acc[i][j]);
-        }
+    // Two sets of fragments: while the matrix cores work on one 16-deep K step, the LDS reads of
+    // the next step land in the other set.
+    uint4_t af[2][4], bf[2][4];
+    auto read_frag = [&](int set, int buf, int ks, int i) {      // A fragment i and B fragment i of step ks
+        const u16* Ab = As + buf * BM * LDA + a_off + ks * 16;
+        const u16* Bb = Bs + buf * BK * LDB + b_off + (ks * 16) * LDB;
+        af[set][i] = *(const uint4_t*)(Ab + i * 32 * LDA);
+        const uint2_t lo = lds_read_tr(Bb + i * 32);
+        const uint2_t hi = lds_read_tr(Bb + 4 * LDB + i * 32);
+        bf[set][i] = uint4_t{lo[0], lo[1], hi[0], hi[1]};
     };
+    auto mfma_row = [&](int set, int i) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = Mfma32<T>::run(af[set][i], bf[set][j], acc[i][j]);
+    };
+#define RL_SB() __builtin_amdgcn_sched_barrier(0)
 
+    // ---- prologue: tile 0 into LDS buffer 0, its first fragments into set 0, tile 1 on its way
     const int nk = (a.K + BK - 1) / BK;
     load_global(0);
-    store_lds(0);
+    unpack_g();
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { stage_x(0, j); stage_w(0, j); }
     __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) load_piece(BK, 0, i);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) read_frag(0, 0, 0, i);
+
+    // ---- main loop, branch free: beyond the last tile the loads return zeros and the extra LDS
+    // traffic touches only the buffer nobody reads any more.
+    //   step 0: MFMA on set 0 | read step 1 -> set 1 | global loads, second half of the next tile
+    //   step 1: MFMA on set 1 | read step 2 -> set 0 | stage X rows 0-3, W rows 0-3 of the next tile
+    //   step 2: MFMA on set 0 | read step 3 -> set 1 | stage X rows 4-7, W rows 4-7
+    //   barrier (next tile complete in the other buffer; this tile's fragments are all in registers)
+    //   step 3: MFMA on set 1 | read next tile's step 0 -> set 0 | global loads, first half of the tile after
+    // Global loads are dealt out a few per group of MFMAs: a wave that issues them all at once sits
+    // in the memory pipeline's queue while its matrix pipe runs dry.
     for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) load_global((kt + 1) * BK);
-        compute(kt & 1);
-        if (kt + 1 < nk) store_lds((kt + 1) & 1);
-        __syncthreads();
+        const int cur = kt & 1, nxt = cur ^ 1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (!(RL_TILE_SKIP & 1)) read_frag(1, cur, 1, i);
+            mfma_row(0, i);
+            if (!(RL_TILE_SKIP & 4)) load_piece((kt + 1) * BK, 1, i);
+            RL_SB();
+        }
+        if (!(RL_TILE_SKIP & 2)) unpack_g();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (!(RL_TILE_SKIP & 1)) read_frag(0, cur, 2, i);
+            mfma_row(1, i);
+            if (!(RL_TILE_SKIP & 2)) { stage_x(nxt, i); stage_w(nxt, i); }
+            RL_SB();
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (!(RL_TILE_SKIP & 1)) read_frag(1, cur, 3, i);
+            mfma_row(0, i);
+            if (!(RL_TILE_SKIP & 2)) { stage_x(nxt, 4 + i); stage_w(nxt, 4 + i); }
+            RL_SB();
+        }
+        if (RL_TILE_SKIP & 64) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { asm volatile("" :: "v"(xa[j])); asm volatile("" :: "v"(wb[j])); }
+        }
+        if (!(RL_TILE_SKIP & 8)) __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (!(RL_TILE_SKIP & 1)) read_frag(0, nxt, 0, i);
+            mfma_row(1, i);
+            if (!(RL_TILE_SKIP & 4)) load_piece((kt + 2) * BK, 0, i);
+            RL_SB();
+        }
     }
+#undef RL_SB
 
     // ---- A_i: the 8 threads that share a row (tid & 7) add their shares
     if (FUSED) {
