@@ -234,7 +234,7 @@ __global__ __launch_bounds__(256) void gemv_splitk_kernel(GemvArgs a)
     __syncthreads();
 
     trace_stamp(a.trace, a.trace_groups, 3);         // workgroup partial in LDS
-    TailArgs ta{a.Y, a.M, a.N, a.eps, a.inv_K, a.S, a.ws_partial, a.ws_sumsq, a.counter, a.trace, a.trace_groups};
+    TailArgs ta{a.Y, a.M, a.N, N_TILE, a.eps, a.inv_K, a.S, a.ws_partial, a.ws_sumsq, a.counter, a.trace, a.trace_groups};
     splitk_tail<T, MT, N_TILE, FUSED>(ta, red, &s_sumsq[0][0], s_rinv, &s_last, tile, slab, n0);
 }
 

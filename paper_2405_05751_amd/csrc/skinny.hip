@@ -28,11 +28,12 @@ struct SkinnyArgs {
     int k_slab;      // rows of W per slab, a multiple of 128 (4 waves x 32 rows)
     int S;
     int n_tiles;
+    int n_tile;      // live columns per workgroup: a multiple of 8, at most kSkinnyTile
     float* ws_partial; float* ws_sumsq; unsigned* counter;
     unsigned long long* trace; int trace_groups;
 };
 
-constexpr int kSkinnyTile = 128;     // columns per workgroup
+constexpr int kSkinnyTile = 128;     // most columns per workgroup (16 lanes x 8)
 constexpr int kSkAux = 2;            // W loads: nt
 constexpr int kSkOut = 0x7ffffff0;
 constexpr int kSkFlags = 0x00020000;
@@ -73,7 +74,8 @@ __global__ __launch_bounds__(256) void skinny_kernel(SkinnyArgs a)
     const int total = a.n_tiles * a.S;
     if ((total & 7) == 0) b = (b & 7) * (total >> 3) + (b >> 3);   // slabs of a tile share an XCD (hint)
     const int tile = b / a.S, slab = b % a.S;
-    const int n0 = tile * N_TILE;
+    const int n0 = tile * a.n_tile;
+    const bool live = i * 8 < a.n_tile;      // narrower tiles leave the last column chunks idle
     const int k0 = slab * a.k_slab;
     const int klen = min(a.k_slab, a.K - k0);
     const int nSteps = a.k_slab >> 7;        // 32-row steps per wave (uniform; rows past klen read zero)
@@ -86,7 +88,8 @@ __global__ __launch_bounds__(256) void skinny_kernel(SkinnyArgs a)
         const_cast<u16*>(FUSED ? a.g : a.X), 0, a.K * 2, kSkFlags);
     const int wrow = a.N * 2;
     // step s of this wave covers slab rows (4s + wave)*32 .. +31; this lane's rows start 8q in
-    const int woff0 = ((wave * 32 + q * 8) * a.N + n0 + i * 8) * 2;
+    // idle lanes start at 2^31: their offsets stay beyond every resource (sizes are below 2^31) and read zero
+    const unsigned woff0 = live ? unsigned(((wave * 32 + q * 8) * a.N + n0 + i * 8) * 2) : 0x80000000u;
     const int wstep = 128 * a.N * 2;
     const int xrow0 = i * a.K * 2;           // row i of X (row 16*mb + i adds mb * 16 rows)
 
@@ -95,7 +98,8 @@ __global__ __launch_bounds__(256) void skinny_kernel(SkinnyArgs a)
     auto issue = [&](int s, int d) {
 #pragma unroll
         for (int j = 0; j < 8; ++j)
-            w[d][j] = __builtin_amdgcn_raw_buffer_load_b128(wrs, woff0 + s * wstep + j * wrow, 0, kSkAux);
+            w[d][j] = __builtin_amdgcn_raw_buffer_load_b128(
+                wrs, int(woff0 + unsigned(s * wstep + j * wrow)), 0, kSkAux);
         const int kr = (4 * s + wave) * 32 + q * 8;               // slab-relative k of this lane's chunk
         const int koff = kr < klen ? (k0 + kr) * 2 : kSkOut;
         if (FUSED) gq[d] = __builtin_amdgcn_raw_buffer_load_b128(grs, koff, 0, 0);
@@ -183,12 +187,12 @@ __global__ __launch_bounds__(256) void skinny_kernel(SkinnyArgs a)
     __syncthreads();
     trace_stamp(a.trace, a.trace_groups, 3);
 
-    TailArgs ta{a.Y, a.M, a.N, a.eps, a.inv_K, a.S, a.ws_partial, a.ws_sumsq, a.counter, a.trace, a.trace_groups};
+    TailArgs ta{a.Y, a.M, a.N, a.n_tile, a.eps, a.inv_K, a.S, a.ws_partial, a.ws_sumsq, a.counter, a.trace, a.trace_groups};
     splitk_tail<T, MT, N_TILE, FUSED>(ta, red, &s_sumsq[0][0], s_rinv, &s_last, tile, slab, n0);
 }
 
 // ------------------------------------------------------------------------------------------- host
-struct SkinnyPlan { int MB, S, k_slab, n_tiles; size_t lds; bool ok; const char* why; };
+struct SkinnyPlan { int MB, S, k_slab, n_tiles, n_tile; size_t lds; bool ok; const char* why; };
 
 static SkinnyPlan skinny_plan(const Problem& p)
 {
@@ -198,17 +202,41 @@ static SkinnyPlan skinny_plan(const Problem& p)
     if (p.M > 64) { pl.why = "skinny variant needs M <= 64"; return pl; }
     if (p.N % 8 != 0 || p.K % 8 != 0) { pl.why = "skinny variant needs N % 8 == 0 and K % 8 == 0"; return pl; }
     if (int64_t(p.M) * p.K * 2 >= (int64_t(1) << 31)) { pl.why = "skinny variant needs M*K < 2^30"; return pl; }
-    if (p.n_tile != 0 && p.n_tile != kSkinnyTile) { pl.why = "skinny n_tile must be 128"; return pl; }
-    pl.MB = (p.M + 15) / 16;
-    pl.n_tiles = (p.N + kSkinnyTile - 1) / kSkinnyTile;
-    const int gran = 128;
-    int S = p.k_split;
-    if (S <= 0) {
-        // the largest power of two that keeps the grid at or under one workgroup per compute unit:
-        // every extra slab adds a tile of fp32 partials to write and read back
-        S = 1;
-        while (2 * S * pl.n_tiles <= 256 && 2 * S * gran * 2 <= p.K) S *= 2;
+    if (p.n_tile != 0 && (p.n_tile % 8 != 0 || p.n_tile < 8 || p.n_tile > kSkinnyTile)) {
+        pl.why = "skinny n_tile must be a multiple of 8 in [8, 128]";
+        return pl;
     }
+    pl.MB = (p.M + 15) / 16;
+    const int gran = 128;
+    int n_tile = p.n_tile, S = p.k_split;
+    if (n_tile == 0 || S <= 0) {
+        // Pick the tile width and slab count with a small cost model: W streams at the rate a grid
+        // of that size can pull (whole rounds of 256 compute units), and every extra slab costs the
+        // split-K epilogue's latency plus a write and a read of an fp32 partial tile set.
+        double best = 1e30;
+        int best_nt = kSkinnyTile, best_s = 1;
+        // (narrower tiles measured slower: their row segments stop being whole 128-byte lines, so
+        // the width stays at 128 unless the caller asks otherwise)
+        for (int nt = (p.n_tile ? p.n_tile : kSkinnyTile); nt >= (p.n_tile ? p.n_tile : kSkinnyTile); nt -= 8) {
+            const int tiles = (p.N + nt - 1) / nt;
+            for (int s = (p.k_split > 0 ? p.k_split : 1); s <= (p.k_split > 0 ? p.k_split : 16); s *= 2) {
+                if (s > 1 && 2 * s * gran > p.K) break;
+                if (tiles > kMaxCounters || int64_t(tiles) * s * kSumsqStride > kMaxSumsqFloats) continue;
+                if (s > 1 && int64_t(s) * p.M * p.N * 4 > (int64_t(48) << 20)) continue;   // fits the library workspace
+                const double wgs = double(tiles) * s;
+                const double rounds = double((int64_t(wgs) + 255) / 256);
+                const double fill = wgs / (rounds * 256.0);
+                const double stream_us = double(p.K) * p.N * 2.0 / (5.0e6 * fill);          // 5 TB/s when full
+                const double tail_us = s > 1 ? 3.0 + 2.0 * s * double(p.M) * p.N * 4.0 / 2.0e6 : 0.5;
+                const double t = stream_us + tail_us;
+                if (t < best) { best = t; best_nt = nt; best_s = s; }
+            }
+        }
+        n_tile = best_nt;
+        S = best_s;
+    }
+    pl.n_tile = n_tile;
+    pl.n_tiles = (p.N + n_tile - 1) / n_tile;
     int k_slab = (p.K + S - 1) / S;
     k_slab = (k_slab + gran - 1) / gran * gran;
     while (int64_t(k_slab) * p.N * 2 >= (int64_t(1) << 31)) k_slab = (k_slab / 2 + gran - 1) / gran * gran;
@@ -271,7 +299,7 @@ hipError_t launch_skinny(const Problem& p, hipStream_t s, const char** why)
     SkinnyArgs a;
     a.X = (const u16*)p.X; a.g = (const u16*)p.g; a.W = (const uint4_t*)p.W; a.Y = (u16*)p.Y;
     a.M = p.M; a.K = p.K; a.N = p.N; a.eps = p.eps; a.inv_K = 1.0f / float(p.K);
-    a.k_slab = pl.k_slab; a.S = pl.S; a.n_tiles = pl.n_tiles;
+    a.k_slab = pl.k_slab; a.S = pl.S; a.n_tiles = pl.n_tiles; a.n_tile = pl.n_tile;
     a.ws_partial = p.ws_partial; a.ws_sumsq = p.ws_sumsq; a.counter = p.ws_counter;
     a.trace = p.trace; a.trace_groups = p.trace_groups;
     return p.dt == F16 ? skinny_mb<Fp16>(a, p.fused != 0, pl, s) : skinny_mb<Bf16>(a, p.fused != 0, pl, s);

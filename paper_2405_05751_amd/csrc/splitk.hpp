@@ -16,6 +16,7 @@ constexpr int kSumsqStride = 64;     // floats per (tile, slab) in ws_sumsq: roo
 struct TailArgs {
     u16* Y;
     int M, N;
+    int n_live;      // columns of the tile that belong to it (<= N_TILE)
     float eps, inv_K;
     int S;
     float* ws_partial; float* ws_sumsq; unsigned* counter;
@@ -53,7 +54,7 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
         for (int qi = 0; qi < QPT; ++qi) {
             const int p = tid + qi * 256;
             const int m = p / (N_TILE / 4), c = (p % (N_TILE / 4)) * 4;
-            if (p < QUADS && m < a.M && n0 + c < a.N) store_y(m, c, wg_sum(m, c), s_rinv[m]);
+            if (p < QUADS && m < a.M && c < a.n_live && n0 + c < a.N) store_y(m, c, wg_sum(m, c), s_rinv[m]);
         }
         return;
     }
@@ -69,7 +70,7 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
     for (int qi = 0; qi < QPT; ++qi) {
         const int p = tid + qi * 256;
         const int m = p / (N_TILE / 4), c = (p % (N_TILE / 4)) * 4;
-        if (p < QUADS && m < a.M && n0 + c < a.N) {
+        if (p < QUADS && m < a.M && c < a.n_live && n0 + c < a.N) {
             const float4_t v = wg_sum(m, c);
             __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uint4_t, v), prs,
                                                    slab * slab_bytes + (m * a.N + n0 + c) * 4, 0, kDev);
@@ -88,30 +89,23 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
     if (!*s_last_p) return;
 
     // ---- last arriver: device-scope loads see what the other slabs wrote through.
-    // A_i: wave 3 reads the S partial sums of squares, one slab per lane, all loads in flight at
-    // once; lane order and the shuffle tree fix the order of the additions.
-    if (wave == 3) {
-        float t[MT];
-#pragma unroll
-        for (int m = 0; m < MT; ++m) t[m] = 0.f;
+    // A_i: lane m of wave 3 reads row m's S partial sums of squares (consecutive lanes read
+    // consecutive floats), sixteen loads in flight, and adds them in slab order.
+    if (wave == 3 && lane < MT) {
+        float t = 0.f;
         if (FUSED) {
-            constexpr int V = (MT + 3) / 4;  // 16-byte loads per slab (the row block is padded to 64 floats)
             const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(
                 a.ws_sumsq + size_t(tile) * a.S * kSumsqStride, 0, a.S * kSumsqStride * 4, 0x00020000);
-            for (int s = lane; s < a.S; s += 64) {
-                uint4_t u[V];
+            for (int s0 = 0; s0 < a.S; s0 += 16) {
+                float u[16];
 #pragma unroll
-                for (int v = 0; v < V; ++v)
-                    u[v] = __builtin_amdgcn_raw_buffer_load_b128(srs, (s * kSumsqStride + 4 * v) * 4, 0, kDev);
+                for (int j = 0; j < 16; ++j)         // slabs at or beyond S are out of range: zero
+                    u[j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(srs, ((s0 + j) * kSumsqStride + lane) * 4, 0, kDev));
 #pragma unroll
-                for (int m = 0; m < MT; ++m) t[m] += __uint_as_float(u[m / 4][m % 4]);
+                for (int j = 0; j < 16; ++j) t += u[j];
             }
         }
-#pragma unroll
-        for (int m = 0; m < MT; ++m) {
-            const float tot = wave_sum(t[m]);
-            if (lane == 0) s_rinv[m] = FUSED ? row_scale(tot, a.inv_K, a.eps) : 1.f;
-        }
+        s_rinv[lane] = FUSED ? row_scale(t, a.inv_K, a.eps) : 1.f;
     }
     float4_t yv[QPT];
 #pragma unroll
@@ -119,7 +113,7 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
         const int p = tid + qi * 256;
         const int m = p / (N_TILE / 4), c = (p % (N_TILE / 4)) * 4;
         float4_t v = {0.f, 0.f, 0.f, 0.f};
-        if (p < QUADS && m < a.M && n0 + c < a.N) {
+        if (p < QUADS && m < a.M && c < a.n_live && n0 + c < a.N) {
             const int off = (m * a.N + n0 + c) * 4;
             for (int s0 = 0; s0 < a.S; s0 += 8) {    // eight loads in flight, added in slab order
                 uint4_t q[8];
@@ -138,7 +132,7 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
     for (int qi = 0; qi < QPT; ++qi) {
         const int p = tid + qi * 256;
         const int m = p / (N_TILE / 4), c = (p % (N_TILE / 4)) * 4;
-        if (p < QUADS && m < a.M && n0 + c < a.N) store_y(m, c, yv[qi], s_rinv[m]);
+        if (p < QUADS && m < a.M && c < a.n_live && n0 + c < a.N) store_y(m, c, yv[qi], s_rinv[m]);
     }
     trace_stamp(a.trace, a.trace_groups, 7);         // Y stored
     if (tid == 0)                            // ready for the next call on this stream
