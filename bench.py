@@ -31,6 +31,10 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0        # MI355X dense bf16/fp16 matrix, published (2.5 PFLOP/s)
 ROTATE_BYTES = 512 << 20
+# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same counters
+# read for the plain copy kernel (x2.0 and x1.0): profiles/hbm_traffic_pmc.md.  Counters cannot be read from
+# inside this process, so the table is refreshed by hand when a kernel's launch shape changes.
+MEASURED_TRAFFIC_BYTES = {"decode": 34.47e6, "qkv": 54.99e6, "gateup": 243.02e6, "prefill": 1745.8e6}
 
 
 def _time_region(fn_enqueue, torch):
@@ -165,6 +169,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="enqueue the timed steps one by one")
     ap.add_argument("--others", action="store_true", help="also time the other four configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
+    ap.add_argument("--probe-copy", type=int, default=0, metavar="MiB",
+                    help="only run the plain copy kernel on MiB of data ten times (memory-counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (sharding is design-only, see DESIGN.md)",
@@ -178,6 +184,16 @@ def main():
     import paper_2405_05751_amd as rl
     rl.lib()                                      # fail loudly if the HIP library is not built
 
+    if args.probe_copy:
+        n = args.probe_copy << 20
+        src = torch.randint(0, 1 << 30, (n // 4,), dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            rl.rl_probe_copy(dst, src)
+        torch.cuda.synchronize()
+        print(json.dumps({"probe_copy_bytes_read": n, "probe_copy_bytes_written": n, "launches": 10}))
+        return
+
     name = args.workload
     steps = args.steps if args.steps is not None else (20 if name == "prefill" else 200)
     res, w = run_workload(rl, torch, name, steps, args.warmup, args.variant, use_graph=not args.no_graph)
@@ -189,7 +205,7 @@ def main():
         metric, unit, value = "fused RMSNorm+MatMul TFLOP/s", "TFLOP/s", res["TFLOPs"]
         roof = {"bound": "mfma", "achieved": res["TFLOPs"], "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(name) if args.variant == "auto" else None
     roof["kernel"] = res["variant"]
     roof["us_per_launch"] = res["us_per_step"]
 
