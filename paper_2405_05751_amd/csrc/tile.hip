@@ -19,10 +19,6 @@
 // handled by those reads and by guarded stores (N % 8 == 0 and K % 8 == 0 are required).
 #include "common.hpp"
 
-#ifndef RL_TILE_SKIP
-#define RL_TILE_SKIP 0     // timing experiments only: 1 no fragment reads, 2 no staging, 4 no global loads,
-#endif                     // 8 no barrier, 16 stage constants instead of the loaded data
-
 namespace rmsnl {
 
 struct TileArgs {
@@ -37,6 +33,7 @@ constexpr int LDA = BK + 8;          // elements per X-hat row in LDS (144 bytes
 constexpr int LDB = BN + 32;         // elements per W row in LDS (576 bytes)
 constexpr int kTileOut = 0x7ffffff0;
 constexpr int kTileFlags = 0x00020000;
+constexpr int kTileDefaultWaves = 8;
 constexpr size_t kTileLds = size_t(2) * (BM * LDA + BK * LDB) * 2 + BM * 4 * 2;
 
 template <typename T> struct Mfma32;
@@ -62,9 +59,16 @@ __device__ __forceinline__ uint2_t lds_read_tr(const u16* p) {
     return __builtin_bit_cast(uint2_t, v);
 }
 
-template <typename T, bool FUSED>
-__global__ __launch_bounds__(256, 1) void tile_kernel(TileArgs a)
+// NW waves per workgroup: 4 (2x2, 128x128 per wave, one wave per SIMD) or 8 (2x4, 128x64 per
+// wave, two waves per SIMD that cover each other's stalls).
+template <typename T, bool FUSED, int NW>
+__global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
 {
+    constexpr int NT = 64 * NW;                  // threads
+    constexpr int WN = NW / 2;                   // waves along N
+    constexpr int TM = 4, TN = BN / WN / 32;     // MFMA tiles per wave along M and N
+    constexpr int NJ = 2048 / NT;                // 16-byte chunks of X (and of W) a thread stages per K tile
+    constexpr int XR = NT / 8, WR = NT / 32;     // row stride between a thread's X chunks / W chunks
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     u16* As = (u16*)lds_raw;                             // [2][BM][LDA]
     u16* Bs = As + 2 * BM * LDA;                         // [2][BK][LDB]
@@ -72,14 +76,14 @@ __global__ __launch_bounds__(256, 1) void tile_kernel(TileArgs a)
     float* s_rinv = s_ss + BM;                           // [BM]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
 
     // Tile order: workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  When the
     // grid allows, XCD x works through a band of tile rows, four rows at a time, so the ~32 tiles
     // it runs together share few X and W panels in that L2.
     int tm, tn;
     {
-        const int b = blockIdx.x, total = a.tiles_m * a.tiles_n;
+        const int b = blockIdx.x;
         if ((a.tiles_m & 7) == 0) {
             const int band = a.tiles_m >> 3;             // tile rows per XCD
             const int x = b & 7, idx = b >> 3;           // idx in [0, band * tiles_n)
@@ -91,9 +95,7 @@ __global__ __launch_bounds__(256, 1) void tile_kernel(TileArgs a)
         } else {
             tm = b / a.tiles_n; tn = b % a.tiles_n;
         }
-        (void)total;
     }
-    if (RL_TILE_SKIP & 32) { tm = 0; tn = 0; }
     const int m0 = tm * BM, n0 = tn * BN;
     const int rows_here = min(BM, a.M - m0);
 
@@ -104,30 +106,24 @@ __global__ __launch_bounds__(256, 1) void tile_kernel(TileArgs a)
     const __amdgpu_buffer_rsrc_t grs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<u16*>(FUSED ? a.g : a.X), 0, a.K * 2, kTileFlags);
 
-    // staging roles: X chunk (row ar + 32 j, 8 k at ac) and W chunk (row br + 8 j, 8 columns at bc)
+    // staging roles: X chunk (row ar + XR j, 8 k at ac) and W chunk (row br + WR j, 8 columns at bc)
     const int ar = tid >> 3, ac = (tid & 7) * 8;
     const int br = tid >> 5, bc = (tid & 31) * 8;
     const bool bcol_ok = n0 + bc < a.N;
 
-    uint4_t xa[8], wb[8], gv;
-    // one quarter of a tile's global loads: X rows 32*(h*4+i) + ar (+g with the very first), W rows 8*(h*4+i) + br
-    auto load_piece = [&](int k0, int h, int i) {        // k0 >= K: every load is out of range, zero
+    uint4_t xa[NJ], wb[NJ], gv;
+    auto load_piece = [&](int k0, int j) {               // k0 >= K: every load is out of range, zero
         const bool kin = k0 + ac < a.K;
-        const int j = h * 4 + i;
         if (FUSED && j == 0) gv = __builtin_amdgcn_raw_buffer_load_b128(grs, kin ? (k0 + ac) * 2 : kTileOut, 0, 0);
         xa[j] = __builtin_amdgcn_raw_buffer_load_b128(
-            xrs, kin ? ((ar + 32 * j) * a.K + k0 + ac) * 2 : kTileOut, 0, 0);
+            xrs, kin ? ((ar + XR * j) * a.K + k0 + ac) * 2 : kTileOut, 0, 0);
         wb[j] = __builtin_amdgcn_raw_buffer_load_b128(
-            wrs, bcol_ok ? ((k0 + br + 8 * j) * a.N + n0 + bc) * 2 : kTileOut, 0, 0);
-    };
-    auto load_global = [&](int k0) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) load_piece(k0, j >> 2, j & 3);
+            wrs, bcol_ok ? ((k0 + br + WR * j) * a.N + n0 + bc) * 2 : kTileOut, 0, 0);
     };
 
-    float ssq[8];
+    float ssq[NJ];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) ssq[j] = 0.f;
+    for (int j = 0; j < NJ; ++j) ssq[j] = 0.f;
 
     // one staged X chunk: squares of the raw values, times g, one rounding, into LDS
     float gf[8];
@@ -137,8 +133,8 @@ __global__ __launch_bounds__(256, 1) void tile_kernel(TileArgs a)
             for (int e = 0; e < 4; ++e) { gf[2 * e] = Elem<T>::lo(gv[e]); gf[2 * e + 1] = Elem<T>::hi(gv[e]); }
         }
     };
-    auto stage_x = [&](int buf, int j) {
-        uint4_t o = (RL_TILE_SKIP & 16) ? uint4_t{uint32_t(tid), uint32_t(j), 3u, 4u} : xa[j];
+    auto stage = [&](int buf, int j) {
+        uint4_t o = xa[j];
         if (FUSED) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -148,18 +144,15 @@ __global__ __launch_bounds__(256, 1) void tile_kernel(TileArgs a)
                 o[e] = Elem<T>::pack(x0 * gf[2 * e], x1 * gf[2 * e + 1]);
             }
         }
-        *(uint4_t*)(As + buf * BM * LDA + (ar + 32 * j) * LDA + ac) = o;
-    };
-    auto stage_w = [&](int buf, int j) {
-        *(uint4_t*)(Bs + buf * BK * LDB + (br + 8 * j) * LDB + bc) =
-            (RL_TILE_SKIP & 16) ? uint4_t{uint32_t(tid), uint32_t(j), 5u, 6u} : wb[j];
+        *(uint4_t*)(As + buf * BM * LDA + (ar + XR * j) * LDA + ac) = o;
+        *(uint4_t*)(Bs + buf * BK * LDB + (br + WR * j) * LDB + bc) = wb[j];
     };
 
-    float16_t acc[4][4];
+    float16_t acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
@@ -167,118 +160,135 @@ __global__ __launch_bounds__(256, 1) void tile_kernel(TileArgs a)
     // B: 16-lane block blk, lane j in it: row 8*(blk/2) + j/4 (+4 second read), columns 16*(blk%2) + 4*(j%4)
     const int a_off = (wm * 128 + (lane & 31)) * LDA + 8 * (lane >> 5);
     const int blk = lane >> 4, jj = lane & 15;
-    const int b_off = (8 * (blk >> 1) + (jj >> 2)) * LDB + wn * 128 + 16 * (blk & 1) + 4 * (jj & 3);
+    const int b_off = (8 * (blk >> 1) + (jj >> 2)) * LDB + wn * (BN / WN) + 16 * (blk & 1) + 4 * (jj & 3);
 
     // Two sets of fragments: while the matrix cores work on one 16-deep K step, the LDS reads of
     // the next step land in the other set.
-    uint4_t af[2][4], bf[2][4];
+    uint4_t af[2][TM], bf[2][TN];
     auto read_frag = [&](int set, int buf, int ks, int i) {      // A fragment i and B fragment i of step ks
         const u16* Ab = As + buf * BM * LDA + a_off + ks * 16;
         const u16* Bb = Bs + buf * BK * LDB + b_off + (ks * 16) * LDB;
         af[set][i] = *(const uint4_t*)(Ab + i * 32 * LDA);
-        const uint2_t lo = lds_read_tr(Bb + i * 32);
-        const uint2_t hi = lds_read_tr(Bb + 4 * LDB + i * 32);
-        bf[set][i] = uint4_t{lo[0], lo[1], hi[0], hi[1]};
+        if (i < TN) {
+            const uint2_t lo = lds_read_tr(Bb + i * 32);
+            const uint2_t hi = lds_read_tr(Bb + 4 * LDB + i * 32);
+            bf[set][i] = uint4_t{lo[0], lo[1], hi[0], hi[1]};
+        }
     };
     auto mfma_row = [&](int set, int i) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = Mfma32<T>::run(af[set][i], bf[set][j], acc[i][j]);
+        for (int j = 0; j < TN; ++j) acc[i][j] = Mfma32<T>::run(af[set][i], bf[set][j], acc[i][j]);
+    };
+    // the half-tile of staging work (loads or LDS stores) that belongs to group i of a step
+    auto for_pieces = [&](int i, auto fn) {
+#pragma unroll
+        for (int p = 0; p < NJ / 2; ++p)
+            if (p * 8 / NJ == i) fn(p);
     };
 #define RL_SB() __builtin_amdgcn_sched_barrier(0)
 
     // ---- prologue: tile 0 into LDS buffer 0, its first fragments into set 0, tile 1 on its way
     const int nk = (a.K + BK - 1) / BK;
-    load_global(0);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) load_piece(0, j);
     unpack_g();
 #pragma unroll
-    for (int j = 0; j < 8; ++j) { stage_x(0, j); stage_w(0, j); }
+    for (int j = 0; j < NJ; ++j) stage(0, j);
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 4; ++i) load_piece(BK, 0, i);
+    for (int j = 0; j < NJ; ++j) load_piece(BK, j);
 #pragma unroll
     for (int i = 0; i < 4; ++i) read_frag(0, 0, 0, i);
 
     // ---- main loop, branch free: beyond the last tile the loads return zeros and the extra LDS
     // traffic touches only the buffer nobody reads any more.
-    //   step 0: MFMA on set 0 | read step 1 -> set 1 | global loads, second half of the next tile
-    //   step 1: MFMA on set 1 | read step 2 -> set 0 | stage X rows 0-3, W rows 0-3 of the next tile
-    //   step 2: MFMA on set 0 | read step 3 -> set 1 | stage X rows 4-7, W rows 4-7
+    //   step 0: MFMA on set 0 | read step 1 -> set 1
+    //   step 1: MFMA on set 1 | read step 2 -> set 0 | stage the first half of the next tile
+    //   step 2: MFMA on set 0 | read step 3 -> set 1 | stage the second half
     //   barrier (next tile complete in the other buffer; this tile's fragments are all in registers)
-    //   step 3: MFMA on set 1 | read next tile's step 0 -> set 0 | global loads, first half of the tile after
-    // Global loads are dealt out a few per group of MFMAs: a wave that issues them all at once sits
-    // in the memory pipeline's queue while its matrix pipe runs dry.
+    //   step 3: MFMA on set 1 | read next tile's step 0 -> set 0
+    // A staging register is reloaded, for the tile after the next, in the very group that has just
+    // stored it: every global load then has a whole K tile of matrix work to arrive in, the loads
+    // stay spread out one or two per group of MFMAs, and they complete in the order they are used.
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1, nxt = cur ^ 1;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (!(RL_TILE_SKIP & 1)) read_frag(1, cur, 1, i);
-            mfma_row(0, i);
-            if (!(RL_TILE_SKIP & 4)) load_piece((kt + 1) * BK, 1, i);
-            RL_SB();
-        }
-        if (!(RL_TILE_SKIP & 2)) unpack_g();
+        for (int i = 0; i < 4; ++i) { read_frag(1, cur, 1, i); mfma_row(0, i); RL_SB(); }
+        unpack_g();
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            if (!(RL_TILE_SKIP & 1)) read_frag(0, cur, 2, i);
+            read_frag(0, cur, 2, i);
             mfma_row(1, i);
-            if (!(RL_TILE_SKIP & 2)) { stage_x(nxt, i); stage_w(nxt, i); }
+            for_pieces(i, [&](int p) { stage(nxt, p); load_piece((kt + 2) * BK, p); });
             RL_SB();
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            if (!(RL_TILE_SKIP & 1)) read_frag(1, cur, 3, i);
+            read_frag(1, cur, 3, i);
             mfma_row(0, i);
-            if (!(RL_TILE_SKIP & 2)) { stage_x(nxt, 4 + i); stage_w(nxt, 4 + i); }
+            for_pieces(i, [&](int p) { stage(nxt, NJ / 2 + p); load_piece((kt + 2) * BK, NJ / 2 + p); });
             RL_SB();
         }
-        if (RL_TILE_SKIP & 64) {
+        __syncthreads();
 #pragma unroll
-            for (int j = 0; j < 8; ++j) { asm volatile("" :: "v"(xa[j])); asm volatile("" :: "v"(wb[j])); }
-        }
-        if (!(RL_TILE_SKIP & 8)) __syncthreads();
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (!(RL_TILE_SKIP & 1)) read_frag(0, nxt, 0, i);
-            mfma_row(1, i);
-            if (!(RL_TILE_SKIP & 4)) load_piece((kt + 2) * BK, 0, i);
-            RL_SB();
-        }
+        for (int i = 0; i < 4; ++i) { read_frag(0, nxt, 0, i); mfma_row(1, i); RL_SB(); }
     }
 #undef RL_SB
 
     // ---- A_i: the 8 threads that share a row (tid & 7) add their shares
     if (FUSED) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < NJ; ++j) {
             float v = ssq[j];
             v += __shfl_xor(v, 1, 64);
             v += __shfl_xor(v, 2, 64);
             v += __shfl_xor(v, 4, 64);
-            if ((tid & 7) == 0) s_ss[ar + 32 * j] = v;
+            if ((tid & 7) == 0) s_ss[ar + XR * j] = v;
         }
         __syncthreads();
-        s_rinv[tid] = row_scale(s_ss[tid], a.inv_K, a.eps);
+        if (tid < BM) s_rinv[tid] = row_scale(s_ss[tid], a.inv_K, a.eps);
         __syncthreads();
     }
 
     // ---- epilogue: D register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its tile
     const int col_l = lane & 31, rowq = 4 * (lane >> 5);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int row = wm * 128 + i * 32 + 8 * (r >> 2) + rowq + (r & 3);
             const float ri = FUSED ? s_rinv[row] : 1.f;
             if (m0 + row < a.M) {
-                u16* yrow = a.Y + size_t(m0 + row) * a.N + n0 + wn * 128 + col_l;
+                const int c0 = n0 + wn * (BN / WN) + col_l;
+                u16* yrow = a.Y + size_t(m0 + row) * a.N + c0;
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (n0 + wn * 128 + j * 32 + col_l < a.N) yrow[j * 32] = Elem<T>::from_f32(acc[i][j][r] * ri);
+                for (int j = 0; j < TN; ++j)
+                    if (c0 + j * 32 < a.N) yrow[j * 32] = Elem<T>::from_f32(acc[i][j][r] * ri);
             }
         }
 }
 
 // ------------------------------------------------------------------------------------------- host
+template <typename T, bool FUSED, int NW>
+static hipError_t tile_go(const TileArgs& a, dim3 grid, hipStream_t s)
+{
+    static bool lds_raised = false;
+    if (!lds_raised) {
+        hipError_t e = hipFuncSetAttribute((const void*)tile_kernel<T, FUSED, NW>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, int(kTileLds));
+        if (e != hipSuccess) return e;
+        lds_raised = true;
+    }
+    tile_kernel<T, FUSED, NW><<<grid, 64 * NW, kTileLds, s>>>(a);
+    return hipGetLastError();
+}
+
+template <typename T, bool FUSED>
+static hipError_t tile_nw(const TileArgs& a, dim3 grid, int nw, hipStream_t s)
+{
+    return nw == 8 ? tile_go<T, FUSED, 8>(a, grid, s) : tile_go<T, FUSED, 4>(a, grid, s);
+}
+
 hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
 {
     if (p.dt == F32) { if (why) *why = "tile variant handles 16-bit types only"; return hipErrorInvalidValue; }
@@ -290,6 +300,12 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
         if (why) *why = "tile variant needs K*N < 2^30";
         return hipErrorInvalidValue;
     }
+    // tuning: k_split carries the waves per workgroup for this variant (0 = default)
+    if (p.k_split != 0 && p.k_split != 4 && p.k_split != 8) {
+        if (why) *why = "tile variant: k_split selects 4 or 8 waves per workgroup";
+        return hipErrorInvalidValue;
+    }
+    const int nw = p.k_split ? p.k_split : kTileDefaultWaves;
     TileArgs a;
     a.X = (const u16*)p.X; a.g = (const u16*)p.g; a.W = (const u16*)p.W; a.Y = (u16*)p.Y;
     a.M = p.M; a.K = p.K; a.N = p.N; a.eps = p.eps; a.inv_K = 1.0f / float(p.K);
@@ -300,25 +316,10 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
         return hipErrorInvalidValue;
     }
     dim3 grid(a.tiles_m * a.tiles_n);
-    static bool lds_raised = false;
-    if (!lds_raised) {
-        const void* fns[4] = {(const void*)tile_kernel<Bf16, true>, (const void*)tile_kernel<Bf16, false>,
-                              (const void*)tile_kernel<Fp16, true>, (const void*)tile_kernel<Fp16, false>};
-        for (const void* f : fns) {
-            hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, int(kTileLds));
-            if (e != hipSuccess) return e;
-        }
-        lds_raised = true;
-    }
     const bool fused = p.fused != 0;
-    if (p.dt == F16) {
-        if (fused) tile_kernel<Fp16, true><<<grid, 256, kTileLds, s>>>(a);
-        else       tile_kernel<Fp16, false><<<grid, 256, kTileLds, s>>>(a);
-    } else {
-        if (fused) tile_kernel<Bf16, true><<<grid, 256, kTileLds, s>>>(a);
-        else       tile_kernel<Bf16, false><<<grid, 256, kTileLds, s>>>(a);
-    }
-    return hipGetLastError();
+    if (p.dt == F16)
+        return fused ? tile_nw<Fp16, true>(a, grid, nw, s) : tile_nw<Fp16, false>(a, grid, nw, s);
+    return fused ? tile_nw<Bf16, true>(a, grid, nw, s) : tile_nw<Bf16, false>(a, grid, nw, s);
 }
 
 }  // namespace rmsnl
