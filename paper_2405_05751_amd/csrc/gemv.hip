@@ -279,7 +279,7 @@ static GemvPlan gemv_plan(const Problem& p)
     pl.k_slab = k_slab;
     if (pl.n_tiles > kMaxCounters) { pl.why = "too many column tiles"; return pl; }
     if (int64_t(pl.n_tiles) * S * kSumsqStride > kMaxSumsqFloats) { pl.why = "too many K slabs"; return pl; }
-    if (int64_t(S + 8) * p.M * p.N * 4 >= (int64_t(1) << 31)) { pl.why = "split-K partials too large"; return pl; }
+    if (int64_t(S + 16) * p.M * p.N * 4 >= (int64_t(1) << 31)) { pl.why = "split-K partials too large"; return pl; }
     const size_t xs = pl.MT > 4 ? size_t(k_slab) * pl.MT * 4 : 0;
     const size_t red = size_t(4) * pl.MT * n_tile * 4;
     pl.lds = xs > red ? xs : red;

@@ -13,8 +13,8 @@
 // X-hat[m][kb + 8q .. +7]: one 16-byte load of X, times g, rounded once to the 16-bit type;
 // the squares of the raw X feed A_i in the same pass (the paper's two accumulators in one K loop).
 //
-// A workgroup owns 128 columns and one K slab; its four waves take alternate 32-row steps of the
-// slab, so nothing in the K loop needs a barrier.  The waves' fp32 tiles meet in LDS, and the
+// A workgroup owns 128 columns and one K slab; its NW waves take alternate 64-row runs of the
+// slab, two 32-row steps each, so nothing in the K loop needs a barrier.  The waves' fp32 tiles meet in LDS, and the
 // common split-K epilogue finishes (see splitk.hpp).
 #include "common.hpp"
 #include "splitk.hpp"
@@ -25,7 +25,7 @@ struct SkinnyArgs {
     const u16* X; const u16* g; const uint4_t* W; u16* Y;
     int M, K, N;
     float eps, inv_K;
-    int k_slab;      // rows of W per slab, a multiple of 128 (4 waves x 32 rows)
+    int k_slab;      // rows of W per slab, a multiple of 64 rows x the waves of a workgroup
     int S;
     int n_tiles;
     int n_tile;      // live columns per workgroup: a multiple of 8, at most kSkinnyTile
@@ -53,16 +53,18 @@ template <> struct Mfma16<Fp16> {
 };
 
 // steps (8 W loads per lane each) kept in flight per wave
-constexpr int skinny_depth(int MB) { return MB <= 2 ? 4 : 3; }
+constexpr int skinny_depth(int MB) { return MB == 1 ? 4 : 3; }
+constexpr int skinny_waves(int MB) { return 4; }    // 8 (two waves per SIMD, MB <= 2 only) measured no faster
 
 template <typename T, int MB, bool FUSED>
-__global__ __launch_bounds__(256) void skinny_kernel(SkinnyArgs a)
+__global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArgs a)
 {
+    constexpr int NW = skinny_waves(MB);
     constexpr int MT = 16 * MB;
     constexpr int N_TILE = kSkinnyTile;
     constexpr int D = skinny_depth(MB);
-    extern __shared__ float smem[];          // red [4][MT][N_TILE]
-    __shared__ float s_sumsq[4][MT];
+    extern __shared__ float smem[];          // red [NW][MT][N_TILE]
+    __shared__ float s_sumsq[NW][MT];
     __shared__ float s_rinv[MT];
     __shared__ int s_last;
 
@@ -78,7 +80,7 @@ __global__ __launch_bounds__(256) void skinny_kernel(SkinnyArgs a)
     const bool live = i * 8 < a.n_tile;      // narrower tiles leave the last column chunks idle
     const int k0 = slab * a.k_slab;
     const int klen = min(a.k_slab, a.K - k0);
-    const int nSteps = a.k_slab >> 7;        // 32-row steps per wave (uniform; rows past klen read zero)
+    const int nSteps = a.k_slab / (32 * NW); // 32-row steps per wave, an even number (uniform; rows past klen read zero)
 
     const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint4_t*>(a.W + size_t(k0) * (a.N >> 3)), 0, klen * a.N * 2, kSkFlags);
@@ -87,20 +89,24 @@ __global__ __launch_bounds__(256) void skinny_kernel(SkinnyArgs a)
     const __amdgpu_buffer_rsrc_t grs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<u16*>(FUSED ? a.g : a.X), 0, a.K * 2, kSkFlags);
     const int wrow = a.N * 2;
-    // step s of this wave covers slab rows (4s + wave)*32 .. +31; this lane's rows start 8q in
+    // Steps come in pairs: steps 2t and 2t+1 of this wave cover the 64 slab rows from
+    // (NW t + wave)*64; lane (i, q) owns rows 16q + 8h .. +7 of them in step 2t + h.  The four k
+    // groups of a wave then read, over the two steps, whole 128-byte lines of every X row, and no
+    // other wave touches those lines.
     // idle lanes start at 2^31: their offsets stay beyond every resource (sizes are below 2^31) and read zero
-    const unsigned woff0 = live ? unsigned(((wave * 32 + q * 8) * a.N + n0 + i * 8) * 2) : 0x80000000u;
-    const int wstep = 128 * a.N * 2;
+    const unsigned woff0 = live ? unsigned(((wave * 64 + q * 16) * a.N + n0 + i * 8) * 2) : 0x80000000u;
+    const int wpair = 64 * NW * a.N * 2;     // bytes of W between two pairs of steps
     const int xrow0 = i * a.K * 2;           // row i of X (row 16*mb + i adds mb * 16 rows)
 
     uint4_t w[D][8];
     uint4_t xq[D][MB], gq[D];
     auto issue = [&](int s, int d) {
+        const int t = s >> 1, h = s & 1;
 #pragma unroll
         for (int j = 0; j < 8; ++j)
             w[d][j] = __builtin_amdgcn_raw_buffer_load_b128(
-                wrs, int(woff0 + unsigned(s * wstep + j * wrow)), 0, kSkAux);
-        const int kr = (4 * s + wave) * 32 + q * 8;               // slab-relative k of this lane's chunk
+                wrs, int(woff0 + unsigned(t * wpair + (8 * h + j) * wrow)), 0, kSkAux);
+        const int kr = (NW * t + wave) * 64 + q * 16 + h * 8;     // slab-relative k of this lane's chunk
         const int koff = kr < klen ? (k0 + kr) * 2 : kSkOut;
         if (FUSED) gq[d] = __builtin_amdgcn_raw_buffer_load_b128(grs, koff, 0, 0);
 #pragma unroll
@@ -175,7 +181,7 @@ __global__ __launch_bounds__(256) void skinny_kernel(SkinnyArgs a)
         }
     }
     // ---- B: lane (i, q) holds rows 16mb + 4q + r, columns n0 + 8i + c of its wave's partial tile
-    float* red = smem;                       // [4][MT][N_TILE]
+    float* red = smem;                       // [NW][MT][N_TILE]
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -188,7 +194,7 @@ __global__ __launch_bounds__(256) void skinny_kernel(SkinnyArgs a)
     trace_stamp(a.trace, a.trace_groups, 3);
 
     TailArgs ta{a.Y, a.M, a.N, a.n_tile, a.eps, a.inv_K, a.S, a.ws_partial, a.ws_sumsq, a.counter, a.trace, a.trace_groups};
-    splitk_tail<T, MT, N_TILE, FUSED>(ta, red, &s_sumsq[0][0], s_rinv, &s_last, tile, slab, n0);
+    splitk_tail<T, MT, N_TILE, FUSED, NW>(ta, red, &s_sumsq[0][0], s_rinv, &s_last, tile, slab, n0);
 }
 
 // ------------------------------------------------------------------------------------------- host
@@ -207,7 +213,7 @@ static SkinnyPlan skinny_plan(const Problem& p)
         return pl;
     }
     pl.MB = (p.M + 15) / 16;
-    const int gran = 128;
+    const int gran = 64 * skinny_waves(pl.MB);
     int n_tile = p.n_tile, S = p.k_split;
     if (n_tile == 0 || S <= 0) {
         // Pick the tile width and slab count with a small cost model: W streams at the rate a grid
@@ -245,8 +251,8 @@ static SkinnyPlan skinny_plan(const Problem& p)
     pl.k_slab = k_slab;
     if (pl.n_tiles > kMaxCounters) { pl.why = "too many column tiles"; return pl; }
     if (int64_t(pl.n_tiles) * S * kSumsqStride > kMaxSumsqFloats) { pl.why = "too many K slabs"; return pl; }
-    if (int64_t(S + 8) * p.M * p.N * 4 >= (int64_t(1) << 31)) { pl.why = "split-K partials too large"; return pl; }
-    pl.lds = size_t(4) * 16 * pl.MB * kSkinnyTile * 4;
+    if (int64_t(S + 16) * p.M * p.N * 4 >= (int64_t(1) << 31)) { pl.why = "split-K partials too large"; return pl; }
+    pl.lds = size_t(skinny_waves(pl.MB)) * 16 * pl.MB * kSkinnyTile * 4;
     pl.ok = true;
     return pl;
 }
@@ -272,8 +278,8 @@ static hipError_t skinny_go(const SkinnyArgs& a, bool fused, const SkinnyPlan& p
         if (e != hipSuccess) return e;
         lds_raised = true;
     }
-    if (fused) skinny_kernel<T, MB, true><<<grid, 256, pl.lds, s>>>(a);
-    else       skinny_kernel<T, MB, false><<<grid, 256, pl.lds, s>>>(a);
+    if (fused) skinny_kernel<T, MB, true><<<grid, 64 * skinny_waves(MB), pl.lds, s>>>(a);
+    else       skinny_kernel<T, MB, false><<<grid, 64 * skinny_waves(MB), pl.lds, s>>>(a);
     return hipGetLastError();
 }
 

@@ -23,24 +23,32 @@ struct TailArgs {
     unsigned long long* trace; int trace_groups;
 };
 
-// red: [4][MT][N_TILE] fp32 in LDS (one copy per wave), complete and visible (barrier passed);
-// s_sumsq: [4][MT] per-wave partial sums of squares; s_rinv: [MT] scratch; s_last: 1 int scratch.
-template <typename T, int MT, int N_TILE, bool FUSED>
+// NW waves per workgroup (4 or 8).  red: [NW][MT][N_TILE] fp32 in LDS (one copy per wave), complete
+// and visible (barrier passed); s_sumsq: [NW][MT] per-wave partial sums of squares; s_rinv: [MT]
+// scratch; s_last: 1 int scratch.
+template <typename T, int MT, int N_TILE, bool FUSED, int NW = 4>
 __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red, const float* s_sumsq,
                                             float* s_rinv, int* s_last_p, int tile, int slab, int n0)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    constexpr int QUADS = MT * N_TILE / 4;   // groups of 4 columns in the tile, 256 threads share them
-    constexpr int QPT = (QUADS + 255) / 256; // quads per thread
+    const int tid = threadIdx.x;
+    constexpr int NT = 64 * NW;              // threads
+    constexpr int QUADS = MT * N_TILE / 4;   // groups of 4 columns in the tile, the threads share them
+    constexpr int QPT = (QUADS + NT - 1) / NT; // quads per thread
     constexpr int WSTR = MT * N_TILE / 4;    // float4 stride between the waves' copies in red
     constexpr int kDev = 16;                 // buffer cache policy sc1: device scope, across XCDs
     float asum = 0.f;
-    if (FUSED && tid < MT) asum = (s_sumsq[tid] + s_sumsq[MT + tid]) + (s_sumsq[2 * MT + tid] + s_sumsq[3 * MT + tid]);
+    if (FUSED && tid < MT) {
+        asum = (s_sumsq[tid] + s_sumsq[MT + tid]) + (s_sumsq[2 * MT + tid] + s_sumsq[3 * MT + tid]);
+        if (NW == 8)
+            asum += (s_sumsq[4 * MT + tid] + s_sumsq[5 * MT + tid]) + (s_sumsq[6 * MT + tid] + s_sumsq[7 * MT + tid]);
+    }
 
-    // sum of the four waves' copies of quad p of the tile
+    // sum of the waves' copies of a quad of the tile, in a fixed order
     auto wg_sum = [&](int m, int c) {
         const float4_t* q = (const float4_t*)(red + m * N_TILE + c);
-        return (q[0] + q[WSTR]) + (q[2 * WSTR] + q[3 * WSTR]);
+        float4_t v = (q[0] + q[WSTR]) + (q[2 * WSTR] + q[3 * WSTR]);
+        if (NW == 8) v += (q[4 * WSTR] + q[5 * WSTR]) + (q[6 * WSTR] + q[7 * WSTR]);
+        return v;
     };
     auto store_y = [&](int m, int c, float4_t v, float ri) {
         uint2_t o = {Elem<T>::pack(v[0] * ri, v[1] * ri), Elem<T>::pack(v[2] * ri, v[3] * ri)};
@@ -52,7 +60,7 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
         __syncthreads();
 #pragma unroll
         for (int qi = 0; qi < QPT; ++qi) {
-            const int p = tid + qi * 256;
+            const int p = tid + qi * NT;
             const int m = p / (N_TILE / 4), c = (p % (N_TILE / 4)) * 4;
             if (p < QUADS && m < a.M && c < a.n_live && n0 + c < a.N) store_y(m, c, wg_sum(m, c), s_rinv[m]);
         }
@@ -68,7 +76,7 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
     if (FUSED && tid < MT) st_dev(a.ws_sumsq + (tile * a.S + slab) * kSumsqStride + tid, asum);
 #pragma unroll
     for (int qi = 0; qi < QPT; ++qi) {
-        const int p = tid + qi * 256;
+        const int p = tid + qi * NT;
         const int m = p / (N_TILE / 4), c = (p % (N_TILE / 4)) * 4;
         if (p < QUADS && m < a.M && c < a.n_live && n0 + c < a.N) {
             const float4_t v = wg_sum(m, c);
@@ -88,51 +96,55 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
     trace_stamp(a.trace, a.trace_groups, 5);         // counter bumped
     if (!*s_last_p) return;
 
-    // ---- last arriver: device-scope loads see what the other slabs wrote through.
-    // A_i: lane m of wave 3 reads row m's S partial sums of squares (consecutive lanes read
-    // consecutive floats), sixteen loads in flight, and adds them in slab order.
-    if (wave == 3 && lane < MT) {
-        float t = 0.f;
-        if (FUSED) {
-            const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(
-                a.ws_sumsq + size_t(tile) * a.S * kSumsqStride, 0, a.S * kSumsqStride * 4, 0x00020000);
-            for (int s0 = 0; s0 < a.S; s0 += 16) {
-                float u[16];
-#pragma unroll
-                for (int j = 0; j < 16; ++j)         // slabs at or beyond S are out of range: zero
-                    u[j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(srs, ((s0 + j) * kSumsqStride + lane) * 4, 0, kDev));
-#pragma unroll
-                for (int j = 0; j < 16; ++j) t += u[j];
-            }
-        }
-        s_rinv[lane] = FUSED ? row_scale(t, a.inv_K, a.eps) : 1.f;
-    }
+    // ---- last arriver: device-scope loads see what the other slabs wrote through.  A round trip
+    // to the memory side of the fabric costs microseconds here, so every thread asks for all the
+    // slabs' shares of its quads, and of its rows' sums of squares, before it uses any of them, and
+    // adds them in slab order once they are in.  No barrier, no LDS in this part.
+    constexpr int SB = QPT >= 8 ? 4 : QPT >= 4 ? 8 : 16;       // slabs per batch: QPT * SB <= 32 loads of each kind in flight
+    const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(
+        a.ws_sumsq + size_t(tile) * a.S * kSumsqStride, 0, a.S * kSumsqStride * 4, 0x00020000);
+    constexpr int kNowhere = 0x7ffffff0;     // beyond either resource: reads as zero
     float4_t yv[QPT];
+    float asq[QPT];
+    int poff[QPT], soff[QPT];                // byte offsets; kNowhere plus any slab offset stays out of range (sizes < 2^31)
 #pragma unroll
     for (int qi = 0; qi < QPT; ++qi) {
-        const int p = tid + qi * 256;
+        const int p = tid + qi * NT;
         const int m = p / (N_TILE / 4), c = (p % (N_TILE / 4)) * 4;
-        float4_t v = {0.f, 0.f, 0.f, 0.f};
-        if (p < QUADS && m < a.M && c < a.n_live && n0 + c < a.N) {
-            const int off = (m * a.N + n0 + c) * 4;
-            for (int s0 = 0; s0 < a.S; s0 += 8) {    // eight loads in flight, added in slab order
-                uint4_t q[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j)          // slabs at or beyond S are out of range: zero
-                    q[j] = __builtin_amdgcn_raw_buffer_load_b128(prs, (s0 + j) * slab_bytes + off, 0, kDev);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) v += __builtin_bit_cast(float4_t, q[j]);
-            }
-        }
-        yv[qi] = v;
+        const bool ok = p < QUADS && m < a.M && c < a.n_live && n0 + c < a.N;
+        poff[qi] = ok ? (m * a.N + n0 + c) * 4 : kNowhere;
+        soff[qi] = ok ? m * 4 : kNowhere;
+        yv[qi] = float4_t{0.f, 0.f, 0.f, 0.f};
+        asq[qi] = 0.f;
     }
-    __syncthreads();                         // s_rinv is ready
+    for (int s0 = 0; s0 < a.S; s0 += SB) {   // slabs at or beyond S are out of range: zero
+        uint4_t q[QPT][SB];
+        float u[QPT][SB];
+#pragma unroll
+        for (int qi = 0; qi < QPT; ++qi)
+#pragma unroll
+            for (int j = 0; j < SB; ++j) {
+                // the whole offset goes through the range check (a scalar offset would not)
+                q[qi][j] = __builtin_amdgcn_raw_buffer_load_b128(
+                    prs, int(unsigned(poff[qi]) + unsigned((s0 + j) * slab_bytes)), 0, kDev);
+                if (FUSED)
+                    u[qi][j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+                        srs, int(unsigned(soff[qi]) + unsigned((s0 + j) * kSumsqStride * 4)), 0, kDev));
+            }
+#pragma unroll
+        for (int qi = 0; qi < QPT; ++qi)
+#pragma unroll
+            for (int j = 0; j < SB; ++j) {
+                yv[qi] += __builtin_bit_cast(float4_t, q[qi][j]);
+                if (FUSED) asq[qi] += u[qi][j];
+            }
+    }
     trace_stamp(a.trace, a.trace_groups, 6);         // all slabs' partials read
 #pragma unroll
     for (int qi = 0; qi < QPT; ++qi) {
-        const int p = tid + qi * 256;
+        const int p = tid + qi * NT;
         const int m = p / (N_TILE / 4), c = (p % (N_TILE / 4)) * 4;
-        if (p < QUADS && m < a.M && c < a.n_live && n0 + c < a.N) store_y(m, c, yv[qi], s_rinv[m]);
+        if (poff[qi] != kNowhere) store_y(m, c, yv[qi], FUSED ? row_scale(asq[qi], a.inv_K, a.eps) : 1.f);
     }
     trace_stamp(a.trace, a.trace_groups, 7);         // Y stored
     if (tid == 0)                            // ready for the next call on this stream
