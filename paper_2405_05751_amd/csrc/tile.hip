@@ -18,6 +18,7 @@
 // Out-of-range rows of X and W read as zero through buffer resources; ragged M, N and K % 64 are
 // handled by those reads and by guarded stores (N % 8 == 0 and K % 8 == 0 are required).
 #include "common.hpp"
+#include <type_traits>
 
 namespace rmsnl {
 
@@ -30,11 +31,10 @@ struct TileArgs {
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int LDA = BK + 8;          // elements per X-hat row in LDS (144 bytes)
-constexpr int LDB = BN + 32;         // elements per W row in LDS (576 bytes)
 constexpr int kTileOut = 0x7ffffff0;
 constexpr int kTileFlags = 0x00020000;
 constexpr int kTileDefaultWaves = 8;
-constexpr size_t kTileLds = size_t(2) * (BM * LDA + BK * LDB) * 2 + BM * 4 * 2;
+constexpr size_t kTileLds = size_t(2) * (BM * LDA + BK * BN) * 2 + BM * 4 * 2;
 
 template <typename T> struct Mfma32;
 template <> struct Mfma32<Bf16> {
@@ -59,6 +59,25 @@ __device__ __forceinline__ uint2_t lds_read_tr(const u16* p) {
     return __builtin_bit_cast(uint2_t, v);
 }
 
+// sum of the squares of a packed pair of 16-bit values, added to acc (one v_dot2c instead of two
+// unpacks and two fused multiply-adds)
+template <typename T> struct SqPair;
+template <> struct SqPair<Bf16> {
+    static __device__ __forceinline__ float add(uint32_t p, float acc) {
+        const bf16x2_t v = __builtin_bit_cast(bf16x2_t, p);
+        return __builtin_amdgcn_fdot2_f32_bf16(v, v, acc, false);
+    }
+};
+template <> struct SqPair<Fp16> {
+    static __device__ __forceinline__ float add(uint32_t p, float acc) {
+        const f16x2_t v = __builtin_bit_cast(f16x2_t, p);
+        return __builtin_amdgcn_fdot2(v, v, acc, false);
+    }
+};
+
+// s_waitcnt that waits only for the vector-memory counter to drop to n (n <= 63)
+#define RL_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+
 // NW waves per workgroup: 4 (2x2, 128x128 per wave, one wave per SIMD) or 8 (2x4, 128x64 per
 // wave, two waves per SIMD that cover each other's stalls).
 template <typename T, bool FUSED, int NW>
@@ -67,15 +86,17 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
     constexpr int NT = 64 * NW;                  // threads
     constexpr int WN = NW / 2;                   // waves along N
     constexpr int TM = 4, TN = BN / WN / 32;     // MFMA tiles per wave along M and N
-    constexpr int NJ = 2048 / NT;                // 16-byte chunks of X (and of W) a thread stages per K tile
-    constexpr int XR = NT / 8, WR = NT / 32;     // row stride between a thread's X chunks / W chunks
+    constexpr int NJ = 2048 / NT;                // 16-byte chunks of X a thread stages per K tile
+    constexpr int XR = NT / 8;                   // row stride between a thread's X chunks
+    constexpr int NP = 32 / NW;                  // direct-to-LDS loads of W per wave and K tile (2 rows each)
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     u16* As = (u16*)lds_raw;                             // [2][BM][LDA]
-    u16* Bs = As + 2 * BM * LDA;                         // [2][BK][LDB]
-    float* s_ss = (float*)(Bs + 2 * BK * LDB);           // [BM] sums of squares
+    u16* Bs = As + 2 * BM * LDA;                         // [2][BK][BN], chunks swizzled
+    float* s_ss = (float*)(Bs + 2 * BK * BN);            // [BM] sums of squares
     float* s_rinv = s_ss + BM;                           // [BM]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
 
     // Tile order: workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  When the
@@ -106,19 +127,54 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
     const __amdgpu_buffer_rsrc_t grs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<u16*>(FUSED ? a.g : a.X), 0, a.K * 2, kTileFlags);
 
-    // staging roles: X chunk (row ar + XR j, 8 k at ac) and W chunk (row br + WR j, 8 columns at bc)
+    // ---- X staging role: chunk j of this thread is row ar + XR j, the 8 k from ac.  Byte offsets
+    // inside the tile's rows; a row at or beyond rows_here lies beyond the resource and reads zero.
     const int ar = tid >> 3, ac = (tid & 7) * 8;
-    const int br = tid >> 5, bc = (tid & 31) * 8;
-    const bool bcol_ok = n0 + bc < a.N;
+    int xoff[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) xoff[j] = ((ar + XR * j) * a.K + ac) * 2;
 
-    uint4_t xa[NJ], wb[NJ], gv;
-    auto load_piece = [&](int k0, int j) {               // k0 >= K: every load is out of range, zero
-        const bool kin = k0 + ac < a.K;
-        if (FUSED && j == 0) gv = __builtin_amdgcn_raw_buffer_load_b128(grs, kin ? (k0 + ac) * 2 : kTileOut, 0, 0);
-        xa[j] = __builtin_amdgcn_raw_buffer_load_b128(
-            xrs, kin ? ((ar + XR * j) * a.K + k0 + ac) * 2 : kTileOut, 0, 0);
-        wb[j] = __builtin_amdgcn_raw_buffer_load_b128(
-            wrs, bcol_ok ? ((k0 + br + WR * j) * a.N + n0 + bc) * 2 : kTileOut, 0, 0);
+    // ---- W role: load p of this wave brings rows 2(wave + NW p), +1 of the K tile (two rows of
+    // 256 columns = 1 KiB) straight into LDS.  A direct load writes lane l's 16 bytes at byte 16 l
+    // of that KiB, so lane l fetches the chunk that belongs there: row rsel = l / 32, and, with the
+    // swizzle "chunk c of row r sits at chunk c ^ 4 (r & 3)", chunk (l % 32) ^ 4 (r & 3).
+    // (2 NW p is a multiple of 4, so r & 3 does not depend on p.)
+    const int wrow = 2 * wave + (lane >> 5);
+    const int wchunk = (lane & 31) ^ (4 * (wrow & 3));
+    const int woff = n0 + 8 * wchunk < a.N ? (wrow * a.N + n0 + 8 * wchunk) * 2 : kTileOut;
+
+    uint4_t xa[NJ], gv;
+    // Global loads of tile k0.  Unchecked form (the whole tile lies inside K): per-thread offsets
+    // never change, the tile's position rides in the scalar offset.  Checked form: everything goes
+    // through the vector offset, which is what the range check looks at, so that k at or beyond K
+    // reads zero (ragged last tile, and the prefetches that run past the end).
+    auto load_x = [&](auto checked, int k0, int j) {
+        if constexpr (decltype(checked)::value) {
+            const bool kin = k0 + ac < a.K;
+            if (FUSED && j == 0) gv = __builtin_amdgcn_raw_buffer_load_b128(grs, kin ? (k0 + ac) * 2 : kTileOut, 0, 0);
+            xa[j] = __builtin_amdgcn_raw_buffer_load_b128(xrs, kin ? xoff[j] + k0 * 2 : kTileOut, 0, 0);
+        } else {
+            if (FUSED && j == 0) gv = __builtin_amdgcn_raw_buffer_load_b128(grs, ac * 2, k0 * 2, 0);
+            xa[j] = __builtin_amdgcn_raw_buffer_load_b128(xrs, xoff[j], k0 * 2, 0);
+        }
+    };
+    // The direct load is written in assembly: as a builtin, the compiler takes every later LDS read
+    // for a possible reader of the bytes in flight and waits for all outstanding loads first.  The
+    // waits for these loads are therefore placed by hand (RL_WAIT_VM before the barriers).
+    uint4_t wdesc = {uint32_t(uintptr_t(a.W)), uint32_t(uintptr_t(a.W) >> 32), uint32_t(a.K * a.N * 2),
+                           uint32_t(kTileFlags)};
+    uint32_t bs_base = uint32_t(uintptr_t(Bs)) + uint32_t(wave) * 2 * BN * 2;   // LDS byte address of this wave's first row pair
+    auto load_w = [&](auto checked, int buf, int k0, int p) {
+        const uint32_t dst = bs_base + uint32_t(buf * BK * BN * 2 + NW * p * 2 * BN * 2);
+        const unsigned rowoff = unsigned(k0 + 2 * NW * p) * unsigned(a.N) * 2u;
+        int v = woff, so = int(rowoff);
+        if constexpr (decltype(checked)::value) {
+            v = woff == kTileOut ? kTileOut : int(unsigned(woff) + rowoff);
+            so = 0;
+        }
+        const uint4_t desc = wdesc;          // (operands of an asm inside a generic lambda must be its own locals)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     :: "s"(dst), "v"(v), "s"(desc), "s"(so) : "memory", "m0");
     };
 
     float ssq[NJ];
@@ -138,14 +194,11 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
         if (FUSED) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float x0 = Elem<T>::lo(xa[j][e]), x1 = Elem<T>::hi(xa[j][e]);
-                ssq[j] = __fmaf_rn(x0, x0, ssq[j]);
-                ssq[j] = __fmaf_rn(x1, x1, ssq[j]);
-                o[e] = Elem<T>::pack(x0 * gf[2 * e], x1 * gf[2 * e + 1]);
+                ssq[j] = SqPair<T>::add(o[e], ssq[j]);
+                o[e] = Elem<T>::pack(Elem<T>::lo(o[e]) * gf[2 * e], Elem<T>::hi(o[e]) * gf[2 * e + 1]);
             }
         }
         *(uint4_t*)(As + buf * BM * LDA + (ar + XR * j) * LDA + ac) = o;
-        *(uint4_t*)(Bs + buf * BK * LDB + (br + WR * j) * LDB + bc) = wb[j];
     };
 
     float16_t acc[TM][TN];
@@ -156,22 +209,27 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // fragment addresses (elements): A row l%32 of each MFMA tile, 8 k at 8*(l/32);
-    // B: 16-lane block blk, lane j in it: row 8*(blk/2) + j/4 (+4 second read), columns 16*(blk%2) + 4*(j%4)
+    // fragment addresses.  A: row wm*128 + i*32 + lane%32, k chunk 8*(lane/32) of the 16-deep step.
+    // B: 16-lane block blk, lane jj in it: row 8*(blk/2) + jj/4 (+4 for the second read), columns
+    // 16*(blk%2) + 4*(jj%4) of MFMA tile i, at the swizzled place of that row.
     const int a_off = (wm * 128 + (lane & 31)) * LDA + 8 * (lane >> 5);
     const int blk = lane >> 4, jj = lane & 15;
-    const int b_off = (8 * (blk >> 1) + (jj >> 2)) * LDB + wn * (BN / WN) + 16 * (blk & 1) + 4 * (jj & 3);
+    const int b_row = 8 * (blk >> 1) + (jj >> 2);
+    int b_off[TN];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+        b_off[i] = b_row * BN + ((wn * (BN / WN) + i * 32 + 16 * (blk & 1)) ^ (32 * (b_row & 3))) + 4 * (jj & 3);
 
     // Two sets of fragments: while the matrix cores work on one 16-deep K step, the LDS reads of
     // the next step land in the other set.
     uint4_t af[2][TM], bf[2][TN];
     auto read_frag = [&](int set, int buf, int ks, int i) {      // A fragment i and B fragment i of step ks
         const u16* Ab = As + buf * BM * LDA + a_off + ks * 16;
-        const u16* Bb = Bs + buf * BK * LDB + b_off + (ks * 16) * LDB;
+        const u16* Bb = Bs + buf * BK * BN + (ks * 16) * BN;
         af[set][i] = *(const uint4_t*)(Ab + i * 32 * LDA);
         if (i < TN) {
-            const uint2_t lo = lds_read_tr(Bb + i * 32);
-            const uint2_t hi = lds_read_tr(Bb + 4 * LDB + i * 32);
+            const uint2_t lo = lds_read_tr(Bb + b_off[i]);
+            const uint2_t hi = lds_read_tr(Bb + b_off[i] + 4 * BN);
             bf[set][i] = uint4_t{lo[0], lo[1], hi[0], hi[1]};
         }
     };
@@ -179,38 +237,48 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = Mfma32<T>::run(af[set][i], bf[set][j], acc[i][j]);
     };
-    // the half-tile of staging work (loads or LDS stores) that belongs to group i of a step
-    auto for_pieces = [&](int i, auto fn) {
+    // the staging work that belongs to group i (of 4) of a step
+    auto for_pieces = [&](int n, int i, auto fn) {
 #pragma unroll
-        for (int p = 0; p < NJ / 2; ++p)
-            if (p * 8 / NJ == i) fn(p);
+        for (int p = 0; p < n; ++p)
+            if (p * 4 / n == i) fn(p);
     };
 #define RL_SB() __builtin_amdgcn_sched_barrier(0)
+    const std::integral_constant<bool, true> checked_c;
+    const std::integral_constant<bool, false> unchecked_c;
 
     // ---- prologue: tile 0 into LDS buffer 0, its first fragments into set 0, tile 1 on its way
     const int nk = (a.K + BK - 1) / BK;
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) load_piece(0, j);
+    for (int p = 0; p < NP; ++p) load_w(checked_c, 0, 0, p);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) load_x(checked_c, 0, j);
     unpack_g();
 #pragma unroll
     for (int j = 0; j < NJ; ++j) stage(0, j);
+    RL_WAIT_VM(0);                                       // this wave's part of W tile 0 is in LDS
     __syncthreads();
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) load_piece(BK, j);
+    for (int p = 0; p < NP; ++p) load_w(checked_c, 1, BK, p);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) load_x(checked_c, BK, j);
 #pragma unroll
     for (int i = 0; i < 4; ++i) read_frag(0, 0, 0, i);
 
     // ---- main loop, branch free: beyond the last tile the loads return zeros and the extra LDS
-    // traffic touches only the buffer nobody reads any more.
+    // traffic touches only the buffer nobody reads any more.  At entry of iteration kt: LDS buffer
+    // cur holds tile kt, fragment set 0 its first step, the X registers tile kt+1 (on its way),
+    // and the direct loads of W tile kt+1 into buffer nxt are on their way.
     //   step 0: MFMA on set 0 | read step 1 -> set 1
-    //   step 1: MFMA on set 1 | read step 2 -> set 0 | stage the first half of the next tile
-    //   step 2: MFMA on set 0 | read step 3 -> set 1 | stage the second half
-    //   barrier (next tile complete in the other buffer; this tile's fragments are all in registers)
-    //   step 3: MFMA on set 1 | read next tile's step 0 -> set 0
-    // A staging register is reloaded, for the tile after the next, in the very group that has just
-    // stored it: every global load then has a whole K tile of matrix work to arrive in, the loads
-    // stay spread out one or two per group of MFMAs, and they complete in the order they are used.
-    for (int kt = 0; kt < nk; ++kt) {
+    //   step 1: MFMA on set 1 | read step 2 -> set 0 | stage the first half of X tile kt+1, reload
+    //   step 2: MFMA on set 0 | read step 3 -> set 1 | stage the second half, reload
+    //   wait for this wave's W loads of tile kt+1, barrier (tile kt+1 complete in nxt; all of
+    //   this tile's fragments are in registers)
+    //   step 3: MFMA on set 1 | read next tile's step 0 -> set 0 | W tile kt+2 -> buffer cur
+    // An X register is reloaded, for tile kt+2, in the very group that has just stored it: every
+    // global load then has a whole K tile of matrix work to arrive in, and the loads stay spread
+    // out one or two per group of MFMAs.
+    auto iteration = [&](auto chk, int kt) {
         const int cur = kt & 1, nxt = cur ^ 1;
 #pragma unroll
         for (int i = 0; i < 4; ++i) { read_frag(1, cur, 1, i); mfma_row(0, i); RL_SB(); }
@@ -219,21 +287,33 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
         for (int i = 0; i < 4; ++i) {
             read_frag(0, cur, 2, i);
             mfma_row(1, i);
-            for_pieces(i, [&](int p) { stage(nxt, p); load_piece((kt + 2) * BK, p); });
+            for_pieces(NJ / 2, i, [&](int p) { stage(nxt, p); load_x(chk, (kt + 2) * BK, p); });
             RL_SB();
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             read_frag(1, cur, 3, i);
             mfma_row(0, i);
-            for_pieces(i, [&](int p) { stage(nxt, NJ / 2 + p); load_piece((kt + 2) * BK, NJ / 2 + p); });
+            for_pieces(NJ / 2, i, [&](int p) { stage(nxt, NJ / 2 + p); load_x(chk, (kt + 2) * BK, NJ / 2 + p); });
             RL_SB();
         }
+        // the W loads of tile kt+1 are older than this iteration's NJ + 1 reloads (the g chunk rides with X chunk 0)
+        RL_WAIT_VM(FUSED ? NJ + 1 : NJ);
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { read_frag(0, nxt, 0, i); mfma_row(1, i); RL_SB(); }
-    }
+        for (int i = 0; i < 4; ++i) {
+            read_frag(0, nxt, 0, i);
+            mfma_row(1, i);
+            for_pieces(NP, i, [&](int p) { load_w(chk, cur, (kt + 2) * BK, p); });
+            RL_SB();
+        }
+    };
+    // iterations whose prefetches (tile kt+2) lie wholly inside K take the unchecked loads
+    const int n_fast = max(0, a.K / BK - 2);
+    for (int kt = 0; kt < n_fast; ++kt) iteration(unchecked_c, kt);
+    for (int kt = n_fast; kt < nk; ++kt) iteration(checked_c, kt);
 #undef RL_SB
+    RL_WAIT_VM(0);                                       // nothing may still be writing LDS past this point
 
     // ---- A_i: the 8 threads that share a row (tid & 7) add their shares
     if (FUSED) {
