@@ -189,6 +189,8 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
             for (int e = 0; e < 4; ++e) { gf[2 * e] = Elem<T>::lo(gv[e]); gf[2 * e + 1] = Elem<T>::hi(gv[e]); }
         }
     };
+    // (three-operand dot products against a masked g, which need no unpacking, were tried for
+    // the products: fewer instructions, same time)
     auto stage = [&](int buf, int j) {
         uint4_t o = xa[j];
         if (FUSED) {
