@@ -122,8 +122,6 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
 
     const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<u16*>(a.X + size_t(m0) * a.K), 0, rows_here * a.K * 2, kTileFlags);
-    const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<u16*>(a.W), 0, a.K * a.N * 2, kTileFlags);
     const __amdgpu_buffer_rsrc_t grs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<u16*>(FUSED ? a.g : a.X), 0, a.K * 2, kTileFlags);
 
@@ -173,8 +171,10 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
             so = 0;
         }
         const uint4_t desc = wdesc;          // (operands of an asm inside a generic lambda must be its own locals)
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                     :: "s"(dst), "v"(v), "s"(desc), "s"(so) : "memory", "m0");
+        uint32_t keep;                       // M0 carries the LDS address; whatever it held is put back
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                     "buffer_load_dwordx4 %2, %3, %4 offen lds\n\ts_mov_b32 m0, %0"
+                     : "=&s"(keep) : "s"(dst), "v"(v), "s"(desc), "s"(so) : "memory");
     };
 
     float ssq[NJ];
