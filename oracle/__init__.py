@@ -45,6 +45,8 @@ def _load():
                                               ctypes.c_int, ctypes.c_double, ctypes.c_long,
                                               ctypes.c_long, ctypes.c_long, ctypes.c_void_p,
                                               ctypes.c_long, ctypes.c_void_p]
+        lib.oracle_silu_mul_f64.restype = None
+        lib.oracle_silu_mul_f64.argtypes = [ctypes.c_void_p, ctypes.c_long, ctypes.c_long, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -131,3 +133,22 @@ def rmsnorm(X, g, dtype: str, eps: float) -> np.ndarray:
 def matmul(A, W, dtype: str) -> np.ndarray:
     """Plain product on storage-typed inputs; float64 [M,N] (unfused A/B leg)."""
     return matmul_f64(decode(A, dtype), decode(W, dtype))
+
+
+def silu_mul_f64(z) -> np.ndarray:
+    """Gate of the GatedMLP block on float64: z [R, 2H] read as [gate | up] -> SiLU(gate) * up, [R, H]."""
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    R, N = z.shape
+    if N % 2:
+        raise ValueError("the gated block needs an even number of columns")
+    y = np.empty((R, N // 2), dtype=np.float64)
+    _load().oracle_silu_mul_f64(z.ctypes.data, R, N // 2, y.ctypes.data)
+    return y
+
+
+def rmsnorm_gated_mlp(X, g, W, dtype: str, eps: float, rows=None) -> np.ndarray:
+    """RMSNorm, the two products (W = [gate | up], [K, 2H]), SiLU(gate) * up; float64 [len(rows), H].
+
+    The block's fp64 output is not rounded before the gate.
+    """
+    return silu_mul_f64(rmsnorm_linear(X, g, W, dtype, eps, rows=rows))

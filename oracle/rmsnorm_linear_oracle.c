@@ -26,10 +26,17 @@
  * time; rows are independent and are spread over OpenMP threads.  No
  * blocking, no reordering, no BLAS.
  *
+ * Gated MLP (the paper's GatedMLP benchmark: two products of the same input,
+ * SiLU on one, elementwise product with the other): with the block's output
+ * Z [rows][2H] read as [gate | up],  Y[i][h] = SiLU(Z[i][h]) * Z[i][H + h],
+ * SiLU(v) = v / (1 + exp(-v)).  oracle_silu_mul_f64 is that definition on
+ * doubles, applied to the block's unrounded fp64 output.
+ *
  * Parity pins (tests/test_oracle_*.py): printed-by-hand 2x3 cases, the
  * eps-placement case, exact rational brute force, scale invariance, unit-RMS
- * rows, linearity, and a library float64 product.  No function here is
- * "parity unpinned".
+ * rows, linearity, and a library float64 product; for the gate: closed forms
+ * at v = 0, +-ln 3, the identity SiLU(v) - SiLU(-v) = v, linearity in the up
+ * half, library float64 sigmoids.  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stddef.h>
@@ -212,4 +219,21 @@ int oracle_rmsnorm_linear(const void *X, const void *G, const void *W, int dtype
     free(gd);
     free(wd);
     return failed ? -1 : 0;
+}
+
+/*
+ * Gate of the GatedMLP block on doubles: z is [rows][2H], columns [0, H) the gate half and
+ * [H, 2H) the up half; y is [rows][H]:  y[i][h] = SiLU(z[i][h]) * z[i][H + h].
+ */
+void oracle_silu_mul_f64(const double *z, long rows, long H, double *y)
+{
+#pragma omp parallel for schedule(static)
+    for (long i = 0; i < rows; ++i) {
+        const double *zi = z + (size_t)i * 2 * (size_t)H;
+        for (long h = 0; h < H; ++h) {
+            double v = zi[h];
+            double silu = v / (1.0 + exp(-v));
+            y[(size_t)i * H + h] = silu * zi[(size_t)H + h];
+        }
+    }
 }
