@@ -50,26 +50,31 @@ def _time_region(fn_enqueue, torch):
     return start.elapsed_time(end), wall
 
 
-def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=True):
+def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=True, gated=False):
     import workloads
-    from tests.util import compare, to_device, to_host_f64
+    from tests.util import compare, compare_gated, to_device, to_host_f64
 
     w = workloads.config(name)
     tdt = {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}[w.dtype]
     abytes = w.algorithmic_bytes
+    NY = w.N // 2 if gated else w.N              # gated block: W = [gate | up], Y has H = N/2 columns
+    if gated:
+        abytes -= 2 * w.M * (w.N - NY)
     copies = max(1, min(steps, -(-ROTATE_BYTES // abytes)))
     if name == "prefill":
         copies = 2
     X0, g0, W0 = to_device(w.X, w.dtype), to_device(w.g, w.dtype), to_device(w.W, w.dtype)
-    Xs, gs, Ws, Ys = [X0], [g0], [W0], [torch.empty((w.M, w.N), dtype=tdt, device="cuda")]
+    Xs, gs, Ws, Ys = [X0], [g0], [W0], [torch.empty((w.M, NY), dtype=tdt, device="cuda")]
     for _ in range(copies - 1):
         Xs.append(X0.clone()); gs.append(g0.clone()); Ws.append(W0.clone()); Ys.append(torch.empty_like(Ys[0]))
 
     rl.rl_set_variant(variant)
 
+    fused_call = rl.rmsnorm_gated_mlp if gated else rl.rmsnorm_linear
+
     def step(i):
         j = i % copies
-        rl.rmsnorm_linear(Xs[j], gs[j], Ws[j], w.eps, Ys[j])
+        fused_call(Xs[j], gs[j], Ws[j], w.eps, Ys[j])
 
     for i in range(max(warmup, 1)):
         step(i)
@@ -89,16 +94,22 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
 
     cold = make_runner(step)
     ev_ms, wall_ms = min((_time_region(cold, torch) for _ in range(3)), key=lambda t: t[0])
-    warm = make_runner(lambda i: rl.rmsnorm_linear(Xs[0], gs[0], Ws[0], w.eps, Ys[0]))
+    warm = make_runner(lambda i: fused_call(Xs[0], gs[0], Ws[0], w.eps, Ys[0]))
     warm_ms, _ = min((_time_region(warm, torch) for _ in range(3)), key=lambda t: t[0])
 
     # the unfused pair from the same library, same rotation, for the fusion gain on this hardware
+    # (gated block: the fused norm + products followed by the separate activation kernel)
     Xn = [torch.empty_like(x) for x in Xs]
+    Zs = [torch.empty((w.M, w.N), dtype=tdt, device="cuda") for _ in range(copies)] if gated else None
 
     def pair(i):
         j = i % copies
-        rl.rmsnorm(Xs[j], gs[j], w.eps, Xn[j])
-        rl.matmul(Xn[j], Ws[j], Ys[j])
+        if gated:
+            rl.rmsnorm_linear(Xs[j], gs[j], Ws[j], w.eps, Zs[j])
+            rl.silu_mul(Zs[j], Ys[j])
+        else:
+            rl.rmsnorm(Xs[j], gs[j], w.eps, Xn[j])
+            rl.matmul(Xn[j], Ws[j], Ys[j])
 
     pair(0)
     torch.cuda.synchronize()
@@ -112,13 +123,16 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
         rows = torch.from_numpy(w.check_rows).cuda()
         Y = to_host_f64(Ys[0][rows], w.dtype)
         Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps, rows=w.check_rows)
-        parity, _ = compare(Y, Z, w.dtype, name)
+        if gated:
+            parity = compare_gated(Y, Z, w.dtype, name)      # largest err / bound (<= 1)
+        else:
+            parity, _ = compare(Y, Z, w.dtype, name)
     rl.rl_set_variant("auto")
 
     per_step_ms = ev_ms / steps
     mem_bound = w.M <= 64
     res = {
-        "workload": name, "M": w.M, "K": w.K, "N": w.N, "dtype": w.dtype, "variant": used,
+        "workload": name + ("+gate" if gated else ""), "M": w.M, "K": w.K, "N": w.N, "dtype": w.dtype, "variant": used,
         "copies_rotated": copies, "us_per_step": per_step_ms * 1e3,
         "us_per_step_warm": warm_ms / steps * 1e3, "us_per_step_unfused_pair": pair_ms / steps * 1e3,
         "wall_us_per_step": wall_ms / steps * 1e3,
@@ -169,6 +183,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="enqueue the timed steps one by one")
     ap.add_argument("--others", action="store_true", help="also time the other four configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
+    ap.add_argument("--gated", action="store_true",
+                    help="time the gated block (SiLU(gate) * up epilogue, W read as [gate | up]) on the workload")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="MiB",
                     help="only run the plain copy kernel on MiB of data ten times (memory-counter calibration)")
     args = ap.parse_args()
@@ -196,7 +212,8 @@ def main():
 
     name = args.workload
     steps = args.steps if args.steps is not None else (20 if name == "prefill" else 200)
-    res, w = run_workload(rl, torch, name, steps, args.warmup, args.variant, use_graph=not args.no_graph)
+    res, w = run_workload(rl, torch, name, steps, args.warmup, args.variant, use_graph=not args.no_graph,
+                          gated=args.gated)
     mem_bound = w.M <= 64
     if mem_bound:
         metric, unit, value = "fused RMSNorm+MatMul TB/s", "TB/s", res["TBps"]
@@ -205,7 +222,7 @@ def main():
         metric, unit, value = "fused RMSNorm+MatMul TFLOP/s", "TFLOP/s", res["TFLOPs"]
         roof = {"bound": "mfma", "achieved": res["TFLOPs"], "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(name) if args.variant == "auto" else None
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(name) if args.variant == "auto" and not args.gated else None
     roof["kernel"] = res["variant"]
     roof["us_per_launch"] = res["us_per_step"]
 
@@ -213,7 +230,8 @@ def main():
         "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": steps, "warmup": args.warmup,
         "ms_per_step": res["us_per_step"] / 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": f"{name}: X {w.M}x{w.K}, W {w.K}x{w.N}, {w.dtype}", "variant": res["variant"],
+        "config": {"workload": f"{name}{' + gate' if args.gated else ''}: X {w.M}x{w.K}, W {w.K}x{w.N}, {w.dtype}",
+                   "variant": res["variant"],
                    "copies_rotated": res["copies_rotated"], "graph": not args.no_graph},
         "roofline": roof,
         "detail": res,

@@ -76,6 +76,24 @@ rl_status matmul(const void* A, const void* W, void* Y,
                  int64_t M, int64_t K, int64_t N, rl_dtype dt, void* stream);
 
 /*
+ * Gated MLP on top of the fused block (the paper's GatedMLP benchmark: two products of the same
+ * input run side by side in one kernel, SiLU and the elementwise product applied as its epilogue;
+ * here stacked on the RMSNorm prologue, so the normalised input, the two products and the gate
+ * never touch device memory):
+ *
+ *     W [K][2H] = [gate | up], columns [0, H) the gate half, [H, 2H) the up half, row-major
+ *     Z = the block above on all 2H columns (not materialised)
+ *     Y[i][h] = SiLU(Z[i][h]) * Z[i][H + h],   SiLU(v) = v / (1 + exp(-v)),   Y [M][H]
+ *
+ * Same pointer, alignment, eps and workspace rules as rmsnorm_linear; H % 8 == 0 for the fast
+ * variants (the GEMV variant does not implement it).  silu_mul is the separate activation kernel
+ * of the unfused baseline: it reads a materialised Z [M][2H] and writes Y [M][H].
+ */
+rl_status rmsnorm_gated_mlp(const void* X, const void* g, const void* W, float eps, void* Y,
+                            int64_t M, int64_t K, int64_t H, rl_dtype dt, void* stream);
+rl_status silu_mul(const void* Z, void* Y, int64_t M, int64_t H, rl_dtype dt, void* stream);
+
+/*
  * Variant control (process-wide).  RL_AUTO is the default; the environment variable
  * RL_VARIANT (auto|gemv|skinny|tile|naive) sets the initial value.  A forced variant that
  * cannot run a shape makes the call return RL_ERR_UNSUPPORTED instead of falling back.

@@ -33,6 +33,11 @@ EXPORTS = {
                                ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]),
     "matmul": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
                               ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]),
+    "rmsnorm_gated_mlp": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
+                                         ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                         ctypes.c_int, ctypes.c_void_p]),
+    "silu_mul": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                ctypes.c_int, ctypes.c_void_p]),
     "rl_set_variant": (ctypes.c_int, [ctypes.c_int]),
     "rl_get_variant": (ctypes.c_int, []),
     "rl_last_variant": (ctypes.c_int, []),
@@ -132,6 +137,32 @@ def matmul(A: torch.Tensor, W: torch.Tensor, Y: Optional[torch.Tensor] = None, s
         Y = torch.empty((M, N), dtype=A.dtype, device=A.device)
     _check(lib().matmul(_dev(A, "A"), _dev(W, "W"), _dev(Y, "Y"), M, K, N, _DTYPES[A.dtype],
                         _stream(stream)))
+    return Y
+
+
+def rmsnorm_gated_mlp(X: torch.Tensor, g: torch.Tensor, W: torch.Tensor, eps: float,
+                      Y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    M, K = X.shape
+    K2, N = W.shape
+    if K2 != K or N % 2 or g.shape != (K,) or X.dtype != W.dtype or X.dtype != g.dtype:
+        raise ValueError("shape or dtype mismatch")
+    H = N // 2
+    if Y is None:
+        Y = torch.empty((M, H), dtype=X.dtype, device=X.device)
+    elif Y.shape != (M, H) or Y.dtype != X.dtype:
+        raise ValueError("Y has the wrong shape or dtype")
+    _check(lib().rmsnorm_gated_mlp(_dev(X, "X"), _dev(g, "g"), _dev(W, "W"), float(eps), _dev(Y, "Y"),
+                                   M, K, H, _DTYPES[X.dtype], _stream(stream)))
+    return Y
+
+
+def silu_mul(Z: torch.Tensor, Y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    M, N = Z.shape
+    if N % 2:
+        raise ValueError("Z needs an even number of columns")
+    if Y is None:
+        Y = torch.empty((M, N // 2), dtype=Z.dtype, device=Z.device)
+    _check(lib().silu_mul(_dev(Z, "Z"), _dev(Y, "Y"), M, N // 2, _DTYPES[Z.dtype], _stream(stream)))
     return Y
 
 

@@ -99,6 +99,7 @@ rl_variant choose_auto(const Problem& p)
 {
     if (p.dt == F32) return RL_NAIVE;
     if (p.N % 8 != 0 || p.K % 8 != 0) return RL_NAIVE;
+    if (p.gated) return (p.N % 16 != 0) ? RL_NAIVE : p.M <= 64 ? RL_MFMA_SKINNY : RL_MFMA_TILE;
     if (p.M <= 4) return RL_GEMV_SPLITK;
     if (p.M <= 64) return RL_MFMA_SKINNY;
     return RL_MFMA_TILE;
@@ -175,6 +176,34 @@ rl_status rmsnorm_linear(const void* X, const void* g, const void* W, float eps,
     p.M = int(M); p.K = int(K); p.N = int(N);
     p.eps = eps; p.fused = 1; p.dt = DType(dt);
     return run(p, stream);
+}
+
+rl_status rmsnorm_gated_mlp(const void* X, const void* g, const void* W, float eps, void* Y,
+                            int64_t M, int64_t K, int64_t H, rl_dtype dt, void* stream)
+{
+    if (!X || !g || !W || !Y) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (H < 1 || H >= (int64_t(1) << 30)) return fail(RL_ERR_INVALID_ARG, "H must be in [1, 2^30)");
+    if (rl_status st = check_dims(M, K, 2 * H, dt)) return st;
+    if (!std::isfinite(eps) || eps < 0.f) return fail(RL_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    if (!aligned16(X) || !aligned16(g) || !aligned16(W) || !aligned16(Y))
+        return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    Problem p{};
+    p.X = X; p.g = g; p.W = W; p.Y = Y;
+    p.M = int(M); p.K = int(K); p.N = int(2 * H);
+    p.eps = eps; p.fused = 1; p.gated = 1; p.dt = DType(dt);
+    return run(p, stream);
+}
+
+rl_status silu_mul(const void* Z, void* Y, int64_t M, int64_t H, rl_dtype dt, void* stream)
+{
+    if (!Z || !Y) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (H < 1 || H >= (int64_t(1) << 30)) return fail(RL_ERR_INVALID_ARG, "H must be in [1, 2^30)");
+    if (rl_status st = check_dims(M, 1, 2 * H, dt)) return st;
+    if (M > 65535) return fail(RL_ERR_UNSUPPORTED, "silu_mul supports M <= 65535");
+    if (!aligned16(Z) || !aligned16(Y)) return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    hipError_t e = launch_silu_mul(Z, Y, int(M), int(H), DType(dt), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+    return RL_OK;
 }
 
 rl_status matmul(const void* A, const void* W, void* Y, int64_t M, int64_t K, int64_t N, rl_dtype dt,

@@ -20,6 +20,7 @@ struct Problem {
     int M, K, N;
     float eps;
     int fused;            // 1: RMSNorm prologue + row scaling, 0: plain product
+    int gated;            // 1: W is [K][N] = [gate | up] with N = 2H, Y is [M][H] = SiLU(Z_gate) * Z_up
     DType dt;
     // split-K workspace (may be null when the chosen launch needs none)
     float* ws_partial;    // [S][M][N] partial B
@@ -46,6 +47,8 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why);
 // bytes of partial-B workspace the launch of this problem would use (0 = no split)
 size_t gemv_workspace_bytes(const Problem& p);
 size_t skinny_workspace_bytes(const Problem& p);
+
+hipError_t launch_silu_mul(const void* Z, void* Y, int M, int H, DType dt, hipStream_t s);
 
 hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t s);
@@ -120,6 +123,9 @@ template <> struct Elem<float> {
 __device__ __forceinline__ float row_scale(float sumsq, float inv_K, float eps) {
     return 1.0f / __fsqrt_rn(__fmaf_rn(sumsq, inv_K, eps));
 }
+
+// SiLU(v) = v / (1 + exp(-v)) in fp32 (the activation of the paper's GatedMLP block)
+__device__ __forceinline__ float silu(float v) { return v / (1.0f + __expf(-v)); }
 
 // sum over the 64 lanes of a wave, result in every lane
 __device__ __forceinline__ float wave_sum(float v) {

@@ -237,7 +237,7 @@ __global__ __launch_bounds__(64 * gemv_waves(MT)) void gemv_splitk_kernel(GemvAr
     __syncthreads();
 
     trace_stamp(a.trace, a.trace_groups, 3);         // workgroup partial in LDS
-    TailArgs ta{a.Y, a.M, a.N, N_TILE, a.eps, a.inv_K, a.S, a.ws_partial, a.ws_sumsq, a.counter, a.trace, a.trace_groups};
+    TailArgs ta{a.Y, a.M, a.N, N_TILE, 0, 0, a.eps, a.inv_K, a.S, a.ws_partial, a.ws_sumsq, a.counter, a.trace, a.trace_groups};
     splitk_tail<T, MT, N_TILE, FUSED, NW>(ta, red, &s_sumsq[0][0], s_rinv, &s_last, tile, slab, n0);
 }
 
@@ -249,6 +249,7 @@ static GemvPlan gemv_plan(const Problem& p)
     GemvPlan pl{};
     pl.ok = false;
     if (p.dt == F32) { pl.why = "gemv variant handles 16-bit types only"; return pl; }
+    if (p.gated) { pl.why = "gemv variant does not implement the gated block"; return pl; }
     if (p.M > 16) { pl.why = "gemv variant needs M <= 16"; return pl; }
     if (p.N % 8 != 0 || p.K % 8 != 0) { pl.why = "gemv variant needs N % 8 == 0 and K % 8 == 0"; return pl; }
     if (int64_t(p.M) * p.K * 2 >= (int64_t(1) << 31)) { pl.why = "gemv variant needs M*K < 2^30"; return pl; }

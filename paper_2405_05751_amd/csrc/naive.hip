@@ -10,21 +10,23 @@ namespace rmsnl {
 // waves (k = wave, wave+4, ...), so every thread carries two running sums -- A_i and B_in, the two
 // accumulators of the fused kernel -- and the four partials meet in LDS.  Works for every M, K, N.
 // ---------------------------------------------------------------------------------------------
-template <typename T, bool FUSED>
+template <typename T, bool FUSED, bool GATED>
 __global__ __launch_bounds__(256) void naive_kernel(const typename Elem<T>::store_t* __restrict__ X,
                                                     const typename Elem<T>::store_t* __restrict__ g,
                                                     const typename Elem<T>::store_t* __restrict__ W,
                                                     typename Elem<T>::store_t* __restrict__ Y,
                                                     int M, int K, int N, float eps, float inv_K)
 {
+    // GATED: N = 2H; output column n < H needs W columns n (gate) and H + n (up)
+    const int NO = GATED ? N / 2 : N;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int i = blockIdx.y;
     const int n = blockIdx.x * 64 + lane;
-    const bool live = n < N;
+    const bool live = n < NO;
     const size_t xrow = size_t(i) * K;
 
-    float B = 0.f, A = 0.f;
+    float B = 0.f, U = 0.f, A = 0.f;
     for (int k = wave; k < K; k += 4) {
         float x = Elem<T>::to_f32(X[xrow + k]);
         float xg = x;
@@ -34,33 +36,74 @@ __global__ __launch_bounds__(256) void naive_kernel(const typename Elem<T>::stor
         }
         float w = live ? Elem<T>::to_f32(W[size_t(k) * N + n]) : 0.f;
         B = __fmaf_rn(xg, w, B);
+        if (GATED) {
+            float wu = live ? Elem<T>::to_f32(W[size_t(k) * N + NO + n]) : 0.f;
+            U = __fmaf_rn(xg, wu, U);
+        }
     }
     __shared__ float sB[4][64];
+    __shared__ float sU[4][64];
     __shared__ float sA[4];
     sB[wave][lane] = B;
+    if (GATED) sU[wave][lane] = U;
     if (lane == 0) sA[wave] = A;
     __syncthreads();
     if (wave == 0 && live) {
         float b = (sB[0][lane] + sB[1][lane]) + (sB[2][lane] + sB[3][lane]);
+        float u = GATED ? (sU[0][lane] + sU[1][lane]) + (sU[2][lane] + sU[3][lane]) : 0.f;
         if (FUSED) {
             float a = (sA[0] + sA[1]) + (sA[2] + sA[3]);
-            b *= row_scale(a, inv_K, eps);
+            const float ri = row_scale(a, inv_K, eps);
+            b *= ri;
+            u *= ri;
         }
-        Y[size_t(i) * N + n] = Elem<T>::from_f32(b);
+        if (GATED) b = silu(b) * u;
+        Y[size_t(i) * NO + n] = Elem<T>::from_f32(b);
     }
+}
+
+template <typename T, bool GATED>
+static hipError_t launch_naive_g(const Problem& p, hipStream_t s)
+{
+    typedef typename Elem<T>::store_t S;
+    dim3 grid(((GATED ? p.N / 2 : p.N) + 63) / 64, p.M);
+    if (p.fused)
+        naive_kernel<T, true, GATED><<<grid, 256, 0, s>>>((const S*)p.X, (const S*)p.g, (const S*)p.W, (S*)p.Y,
+                                                          p.M, p.K, p.N, p.eps, 1.0f / float(p.K));
+    else
+        naive_kernel<T, false, GATED><<<grid, 256, 0, s>>>((const S*)p.X, nullptr, (const S*)p.W, (S*)p.Y,
+                                                           p.M, p.K, p.N, 0.f, 0.f);
+    return hipGetLastError();
 }
 
 template <typename T>
 static hipError_t launch_naive_t(const Problem& p, hipStream_t s)
 {
-    typedef typename Elem<T>::store_t S;
-    dim3 grid((p.N + 63) / 64, p.M);
-    if (p.fused)
-        naive_kernel<T, true><<<grid, 256, 0, s>>>((const S*)p.X, (const S*)p.g, (const S*)p.W, (S*)p.Y,
-                                                   p.M, p.K, p.N, p.eps, 1.0f / float(p.K));
-    else
-        naive_kernel<T, false><<<grid, 256, 0, s>>>((const S*)p.X, nullptr, (const S*)p.W, (S*)p.Y,
-                                                    p.M, p.K, p.N, 0.f, 0.f);
+    return p.gated ? launch_naive_g<T, true>(p, s) : launch_naive_g<T, false>(p, s);
+}
+
+// Y[i][h] = SiLU(Z[i][h]) * Z[i][H + h]: the separate activation kernel of the unfused GatedMLP
+template <typename T>
+__global__ __launch_bounds__(256) void silu_mul_kernel(const typename Elem<T>::store_t* __restrict__ Z,
+                                                       typename Elem<T>::store_t* __restrict__ Y, int H)
+{
+    const size_t i = blockIdx.y;
+    const int h = blockIdx.x * 256 + threadIdx.x;
+    if (h < H) {
+        const float gt = Elem<T>::to_f32(Z[i * 2 * H + h]), up = Elem<T>::to_f32(Z[i * 2 * H + H + h]);
+        Y[i * H + h] = Elem<T>::from_f32(silu(gt) * up);
+    }
+}
+
+hipError_t launch_silu_mul(const void* Z, void* Y, int M, int H, DType dt, hipStream_t s)
+{
+    if (M > 65535) return hipErrorInvalidValue;
+    dim3 grid((H + 255) / 256, M);
+    switch (dt) {
+    case F16:  silu_mul_kernel<Fp16><<<grid, 256, 0, s>>>((const u16*)Z, (u16*)Y, H); break;
+    case BF16: silu_mul_kernel<Bf16><<<grid, 256, 0, s>>>((const u16*)Z, (u16*)Y, H); break;
+    default:   silu_mul_kernel<float><<<grid, 256, 0, s>>>((const float*)Z, (float*)Y, H); break;
+    }
     return hipGetLastError();
 }
 

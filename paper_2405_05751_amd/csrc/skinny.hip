@@ -29,6 +29,7 @@ struct SkinnyArgs {
     int S;
     int n_tiles;
     int n_tile;      // live columns per workgroup: a multiple of 8, at most kSkinnyTile
+    int H;           // gated block: N = 2H, a tile is n_tile/2 gate columns and the same up columns; else 0
     float* ws_partial; float* ws_sumsq; unsigned* counter;
     unsigned long long* trace; int trace_groups;
 };
@@ -56,7 +57,7 @@ template <> struct Mfma16<Fp16> {
 constexpr int skinny_depth(int MB) { return MB == 1 ? 4 : 3; }
 constexpr int skinny_waves(int MB) { return 4; }    // 8 (two waves per SIMD, MB <= 2 only) measured no faster
 
-template <typename T, int MB, bool FUSED>
+template <typename T, int MB, bool FUSED, bool GATED>
 __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArgs a)
 {
     constexpr int NW = skinny_waves(MB);
@@ -76,7 +77,11 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
     const int total = a.n_tiles * a.S;
     if ((total & 7) == 0) b = (b & 7) * (total >> 3) + (b >> 3);   // slabs of a tile share an XCD (hint)
     const int tile = b / a.S, slab = b % a.S;
-    const int n0 = tile * a.n_tile;
+    // plain: the tile's W columns start at n0.  Gated: the tile is half = n_tile/2 gate columns from
+    // hn0 and the up columns of the same outputs, H further on; lane chunk i is one or the other.
+    const int half = a.n_tile >> 1;
+    const int n0 = GATED ? tile * half : tile * a.n_tile;
+    const int ccol = GATED ? (i * 8 < half ? n0 + i * 8 : a.H + n0 + (i * 8 - half)) : n0 + i * 8;
     const bool live = i * 8 < a.n_tile;      // narrower tiles leave the last column chunks idle
     const int k0 = slab * a.k_slab;
     const int klen = min(a.k_slab, a.K - k0);
@@ -94,7 +99,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
     // groups of a wave then read, over the two steps, whole 128-byte lines of every X row, and no
     // other wave touches those lines.
     // idle lanes start at 2^31: their offsets stay beyond every resource (sizes are below 2^31) and read zero
-    const unsigned woff0 = live ? unsigned(((wave * 64 + q * 16) * a.N + n0 + i * 8) * 2) : 0x80000000u;
+    const unsigned woff0 = live ? unsigned(((wave * 64 + q * 16) * a.N + ccol) * 2) : 0x80000000u;
     const int wpair = 64 * NW * a.N * 2;     // bytes of W between two pairs of steps
     const int xrow0 = i * a.K * 2;           // row i of X (row 16*mb + i adds mb * 16 rows)
 
@@ -193,8 +198,9 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
     __syncthreads();
     trace_stamp(a.trace, a.trace_groups, 3);
 
-    TailArgs ta{a.Y, a.M, a.N, a.n_tile, a.eps, a.inv_K, a.S, a.ws_partial, a.ws_sumsq, a.counter, a.trace, a.trace_groups};
-    splitk_tail<T, MT, N_TILE, FUSED, NW>(ta, red, &s_sumsq[0][0], s_rinv, &s_last, tile, slab, n0);
+    TailArgs ta{a.Y, a.M, a.N, a.n_tile, GATED ? half : 0, a.H, a.eps, a.inv_K, a.S, a.ws_partial, a.ws_sumsq, a.counter,
+                a.trace, a.trace_groups};
+    splitk_tail<T, MT, N_TILE, FUSED, NW, GATED>(ta, red, &s_sumsq[0][0], s_rinv, &s_last, tile, slab, n0);
 }
 
 // ------------------------------------------------------------------------------------------- host
@@ -210,6 +216,10 @@ static SkinnyPlan skinny_plan(const Problem& p)
     if (int64_t(p.M) * p.K * 2 >= (int64_t(1) << 31)) { pl.why = "skinny variant needs M*K < 2^30"; return pl; }
     if (p.n_tile != 0 && (p.n_tile % 8 != 0 || p.n_tile < 8 || p.n_tile > kSkinnyTile)) {
         pl.why = "skinny n_tile must be a multiple of 8 in [8, 128]";
+        return pl;
+    }
+    if (p.gated && (p.N % 16 != 0 || p.n_tile % 16 != 0 || !p.fused)) {
+        pl.why = "gated block: skinny variant needs H % 8 == 0 and n_tile % 16 == 0";
         return pl;
     }
     pl.MB = (p.M + 15) / 16;
@@ -242,7 +252,7 @@ static SkinnyPlan skinny_plan(const Problem& p)
         S = best_s;
     }
     pl.n_tile = n_tile;
-    pl.n_tiles = (p.N + n_tile - 1) / n_tile;
+    pl.n_tiles = p.gated ? (p.N / 2 + n_tile / 2 - 1) / (n_tile / 2) : (p.N + n_tile - 1) / n_tile;
     int k_slab = (p.K + S - 1) / S;
     k_slab = (k_slab + gran - 1) / gran * gran;
     while (int64_t(k_slab) * p.N * 2 >= (int64_t(1) << 31)) k_slab = (k_slab / 2 + gran - 1) / gran * gran;
@@ -265,32 +275,34 @@ size_t skinny_workspace_bytes(const Problem& p)
 }
 
 template <typename T, int MB>
-static hipError_t skinny_go(const SkinnyArgs& a, bool fused, const SkinnyPlan& pl, hipStream_t s)
+static hipError_t skinny_go(const SkinnyArgs& a, bool fused, bool gated, const SkinnyPlan& pl, hipStream_t s)
 {
     dim3 grid(pl.n_tiles * pl.S);
     static bool lds_raised = false;          // 128 KiB of dynamic LDS at MB = 4
     if (!lds_raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)skinny_kernel<T, MB, true>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)skinny_kernel<T, MB, false>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
-        if (e != hipSuccess) return e;
+        const void* fns[3] = {(const void*)skinny_kernel<T, MB, true, false>, (const void*)skinny_kernel<T, MB, false, false>,
+                              (const void*)skinny_kernel<T, MB, true, true>};
+        for (const void* f : fns) {
+            hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+            if (e != hipSuccess) return e;
+        }
         lds_raised = true;
     }
-    if (fused) skinny_kernel<T, MB, true><<<grid, 64 * skinny_waves(MB), pl.lds, s>>>(a);
-    else       skinny_kernel<T, MB, false><<<grid, 64 * skinny_waves(MB), pl.lds, s>>>(a);
+    const int nt = 64 * skinny_waves(MB);
+    if (gated)      skinny_kernel<T, MB, true, true><<<grid, nt, pl.lds, s>>>(a);
+    else if (fused) skinny_kernel<T, MB, true, false><<<grid, nt, pl.lds, s>>>(a);
+    else            skinny_kernel<T, MB, false, false><<<grid, nt, pl.lds, s>>>(a);
     return hipGetLastError();
 }
 
 template <typename T>
-static hipError_t skinny_mb(const SkinnyArgs& a, bool fused, const SkinnyPlan& pl, hipStream_t s)
+static hipError_t skinny_mb(const SkinnyArgs& a, bool fused, bool gated, const SkinnyPlan& pl, hipStream_t s)
 {
     switch (pl.MB) {
-    case 1:  return skinny_go<T, 1>(a, fused, pl, s);
-    case 2:  return skinny_go<T, 2>(a, fused, pl, s);
-    case 3:  return skinny_go<T, 3>(a, fused, pl, s);
-    default: return skinny_go<T, 4>(a, fused, pl, s);
+    case 1:  return skinny_go<T, 1>(a, fused, gated, pl, s);
+    case 2:  return skinny_go<T, 2>(a, fused, gated, pl, s);
+    case 3:  return skinny_go<T, 3>(a, fused, gated, pl, s);
+    default: return skinny_go<T, 4>(a, fused, gated, pl, s);
     }
 }
 
@@ -306,9 +318,11 @@ hipError_t launch_skinny(const Problem& p, hipStream_t s, const char** why)
     a.X = (const u16*)p.X; a.g = (const u16*)p.g; a.W = (const uint4_t*)p.W; a.Y = (u16*)p.Y;
     a.M = p.M; a.K = p.K; a.N = p.N; a.eps = p.eps; a.inv_K = 1.0f / float(p.K);
     a.k_slab = pl.k_slab; a.S = pl.S; a.n_tiles = pl.n_tiles; a.n_tile = pl.n_tile;
+    a.H = p.gated ? p.N / 2 : 0;
     a.ws_partial = p.ws_partial; a.ws_sumsq = p.ws_sumsq; a.counter = p.ws_counter;
     a.trace = p.trace; a.trace_groups = p.trace_groups;
-    return p.dt == F16 ? skinny_mb<Fp16>(a, p.fused != 0, pl, s) : skinny_mb<Bf16>(a, p.fused != 0, pl, s);
+    const bool fused = p.fused != 0, gated = p.gated != 0;
+    return p.dt == F16 ? skinny_mb<Fp16>(a, fused, gated, pl, s) : skinny_mb<Bf16>(a, fused, gated, pl, s);
 }
 
 }  // namespace rmsnl

@@ -15,8 +15,10 @@ constexpr int kSumsqStride = 64;     // floats per (tile, slab) in ws_sumsq: roo
 
 struct TailArgs {
     u16* Y;
-    int M, N;
+    int M, N;        // N: columns of W (= row length of the partial workspace, and of Y unless gated)
     int n_live;      // columns of the tile that belong to it (<= N_TILE)
+    int half;        // gated block: the tile's first `half` columns are gate columns hn0.., the next `half` the
+    int H;           //   up columns H + hn0.. of W, and Y [M][H] gets SiLU(gate) * up; half = 0: plain block
     float eps, inv_K;
     int S;
     float* ws_partial; float* ws_sumsq; unsigned* counter;
@@ -26,10 +28,11 @@ struct TailArgs {
 // NW waves per workgroup (4 or 8).  red: [NW][MT][N_TILE] fp32 in LDS (one copy per wave), complete
 // and visible (barrier passed); s_sumsq: [NW][MT] per-wave partial sums of squares; s_rinv: [MT]
 // scratch; s_last: 1 int scratch.
-template <typename T, int MT, int N_TILE, bool FUSED, int NW = 4>
+template <typename T, int MT, int N_TILE, bool FUSED, int NW = 4, bool GATED = false>
 __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red, const float* s_sumsq,
                                             float* s_rinv, int* s_last_p, int tile, int slab, int n0)
 {
+    // n0: first W column of the tile (plain), or first column hn0 of the tile inside each half (gated)
     const int tid = threadIdx.x;
     constexpr int NT = 64 * NW;              // threads
     constexpr int QUADS = MT * N_TILE / 4;   // groups of 4 columns in the tile, the threads share them
@@ -50,10 +53,25 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
         if (NW == 8) v += (q[4 * WSTR] + q[5 * WSTR]) + (q[6 * WSTR] + q[7 * WSTR]);
         return v;
     };
-    auto store_y = [&](int m, int c, float4_t v, float ri) {
-        uint2_t o = {Elem<T>::pack(v[0] * ri, v[1] * ri), Elem<T>::pack(v[2] * ri, v[3] * ri)};
-        *(uint2_t*)(a.Y + size_t(m) * a.N + n0 + c) = o;
+    // tile-local quad (m, c): is it inside the problem, and where are its columns in W
+    auto live = [&](int m, int c) {
+        if (GATED) return m < a.M && c < 2 * a.half && n0 + (c < a.half ? c : c - a.half) < a.H;
+        return m < a.M && c < a.n_live && n0 + c < a.N;
     };
+    auto wcol = [&](int c) {
+        if (GATED) return c < a.half ? n0 + c : a.H + n0 + (c - a.half);
+        return n0 + c;
+    };
+    // plain block: Y = B * rinv.  Gated block: the quad is a gate quad, u the up quad of the same
+    // outputs; Y = SiLU(gate * rinv) * (up * rinv), Y's rows are H long.
+    auto store_y = [&](int m, int c, float4_t v, float4_t u, float ri) {
+        float y[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] = GATED ? silu(v[e] * ri) * (u[e] * ri) : v[e] * ri;
+        uint2_t o = {Elem<T>::pack(y[0], y[1]), Elem<T>::pack(y[2], y[3])};
+        *(uint2_t*)(a.Y + size_t(m) * (GATED ? a.H : a.N) + n0 + c) = o;
+    };
+    const float4_t kZero4 = {0.f, 0.f, 0.f, 0.f};
 
     if (a.S == 1) {
         if (tid < MT) s_rinv[tid] = FUSED ? row_scale(asum, a.inv_K, a.eps) : 1.f;
@@ -62,7 +80,8 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
         for (int qi = 0; qi < QPT; ++qi) {
             const int p = tid + qi * NT;
             const int m = p / (N_TILE / 4), c = (p % (N_TILE / 4)) * 4;
-            if (p < QUADS && m < a.M && c < a.n_live && n0 + c < a.N) store_y(m, c, wg_sum(m, c), s_rinv[m]);
+            if (p < QUADS && live(m, c) && (!GATED || c < a.half))
+                store_y(m, c, wg_sum(m, c), GATED ? wg_sum(m, c + a.half) : kZero4, s_rinv[m]);
         }
         return;
     }
@@ -78,10 +97,10 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
     for (int qi = 0; qi < QPT; ++qi) {
         const int p = tid + qi * NT;
         const int m = p / (N_TILE / 4), c = (p % (N_TILE / 4)) * 4;
-        if (p < QUADS && m < a.M && c < a.n_live && n0 + c < a.N) {
+        if (p < QUADS && live(m, c)) {
             const float4_t v = wg_sum(m, c);
             __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uint4_t, v), prs,
-                                                   slab * slab_bytes + (m * a.N + n0 + c) * 4, 0, kDev);
+                                                   slab * slab_bytes + (m * a.N + wcol(c)) * 4, 0, kDev);
         }
     }
     __builtin_amdgcn_s_waitcnt(0);           // this wave's stores have been acknowledged
@@ -99,34 +118,41 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
     // ---- last arriver: device-scope loads see what the other slabs wrote through.  A round trip
     // to the memory side of the fabric costs microseconds here, so every thread asks for all the
     // slabs' shares of its quads, and of its rows' sums of squares, before it uses any of them, and
-    // adds them in slab order once they are in.  No barrier, no LDS in this part.
-    constexpr int SB = QPT >= 8 ? 4 : QPT >= 4 ? 8 : 16;       // slabs per batch: QPT * SB <= 32 loads of each kind in flight
+    // adds them in slab order once they are in.  No barrier, no LDS in this part.  (Gated block: a
+    // thread whose quad is a gate quad also fetches the up quad of the same outputs; threads on
+    // up quads have nothing to store.)
+    constexpr int NQ = GATED ? 2 : 1;
+    constexpr int SB = (QPT >= 8 ? 4 : QPT >= 4 ? 8 : 16) / NQ;   // slabs per batch: QPT * NQ * SB <= 32 loads of each kind in flight
     const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(
         a.ws_sumsq + size_t(tile) * a.S * kSumsqStride, 0, a.S * kSumsqStride * 4, 0x00020000);
     constexpr int kNowhere = 0x7ffffff0;     // beyond either resource: reads as zero
-    float4_t yv[QPT];
+    float4_t yv[QPT][NQ];
     float asq[QPT];
-    int poff[QPT], soff[QPT];                // byte offsets; kNowhere plus any slab offset stays out of range (sizes < 2^31)
+    int poff[QPT][NQ], soff[QPT];            // byte offsets; kNowhere plus any slab offset stays out of range (sizes < 2^31)
 #pragma unroll
     for (int qi = 0; qi < QPT; ++qi) {
         const int p = tid + qi * NT;
         const int m = p / (N_TILE / 4), c = (p % (N_TILE / 4)) * 4;
-        const bool ok = p < QUADS && m < a.M && c < a.n_live && n0 + c < a.N;
-        poff[qi] = ok ? (m * a.N + n0 + c) * 4 : kNowhere;
+        const bool ok = p < QUADS && live(m, c) && (!GATED || c < a.half);
+        poff[qi][0] = ok ? (m * a.N + wcol(c)) * 4 : kNowhere;
+        if (GATED) poff[qi][1] = ok ? (m * a.N + wcol(c + a.half)) * 4 : kNowhere;
         soff[qi] = ok ? m * 4 : kNowhere;
-        yv[qi] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int h = 0; h < NQ; ++h) yv[qi][h] = kZero4;
         asq[qi] = 0.f;
     }
     for (int s0 = 0; s0 < a.S; s0 += SB) {   // slabs at or beyond S are out of range: zero
-        uint4_t q[QPT][SB];
+        uint4_t q[QPT][NQ][SB];
         float u[QPT][SB];
 #pragma unroll
         for (int qi = 0; qi < QPT; ++qi)
 #pragma unroll
             for (int j = 0; j < SB; ++j) {
                 // the whole offset goes through the range check (a scalar offset would not)
-                q[qi][j] = __builtin_amdgcn_raw_buffer_load_b128(
-                    prs, int(unsigned(poff[qi]) + unsigned((s0 + j) * slab_bytes)), 0, kDev);
+#pragma unroll
+                for (int h = 0; h < NQ; ++h)
+                    q[qi][h][j] = __builtin_amdgcn_raw_buffer_load_b128(
+                        prs, int(unsigned(poff[qi][h]) + unsigned((s0 + j) * slab_bytes)), 0, kDev);
                 if (FUSED)
                     u[qi][j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
                         srs, int(unsigned(soff[qi]) + unsigned((s0 + j) * kSumsqStride * 4)), 0, kDev));
@@ -135,7 +161,8 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
         for (int qi = 0; qi < QPT; ++qi)
 #pragma unroll
             for (int j = 0; j < SB; ++j) {
-                yv[qi] += __builtin_bit_cast(float4_t, q[qi][j]);
+#pragma unroll
+                for (int h = 0; h < NQ; ++h) yv[qi][h] += __builtin_bit_cast(float4_t, q[qi][h][j]);
                 if (FUSED) asq[qi] += u[qi][j];
             }
     }
@@ -144,7 +171,8 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
     for (int qi = 0; qi < QPT; ++qi) {
         const int p = tid + qi * NT;
         const int m = p / (N_TILE / 4), c = (p % (N_TILE / 4)) * 4;
-        if (poff[qi] != kNowhere) store_y(m, c, yv[qi], FUSED ? row_scale(asq[qi], a.inv_K, a.eps) : 1.f);
+        if (poff[qi][0] != kNowhere)
+            store_y(m, c, yv[qi][0], yv[qi][NQ - 1], FUSED ? row_scale(asq[qi], a.inv_K, a.eps) : 1.f);
     }
     trace_stamp(a.trace, a.trace_groups, 7);         // Y stored
     if (tid == 0)                            // ready for the next call on this stream

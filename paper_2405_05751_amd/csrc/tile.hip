@@ -27,6 +27,7 @@ struct TileArgs {
     int M, K, N;
     float eps, inv_K;
     int tiles_m, tiles_n;
+    int H;           // gated block: N = 2H, a tile is 128 gate columns and the up columns of the same outputs; else 0
 };
 
 constexpr int BM = 256, BN = 256, BK = 64;
@@ -80,7 +81,11 @@ template <> struct SqPair<Fp16> {
 
 // NW waves per workgroup: 4 (2x2, 128x128 per wave, one wave per SIMD) or 8 (2x4, 128x64 per
 // wave, two waves per SIMD that cover each other's stalls).
-template <typename T, bool FUSED, int NW>
+//
+// GATED (the GatedMLP block on top): the tile's 256 columns are 128 outputs' gate and up columns,
+// laid out so that MFMA tiles j and j + TN/2 of a wave are gate and up of the same 32 outputs; the
+// epilogue then forms SiLU(gate) * up in registers.  Only the column a lane fetches changes.
+template <typename T, bool FUSED, int NW, bool GATED>
 __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
 {
     constexpr int NT = 64 * NW;                  // threads
@@ -117,7 +122,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
             tm = b / a.tiles_n; tn = b % a.tiles_n;
         }
     }
-    const int m0 = tm * BM, n0 = tn * BN;
+    const int m0 = tm * BM, n0 = GATED ? tn * (BN / 2) : tn * BN;   // gated: first output column of the tile
     const int rows_here = min(BM, a.M - m0);
 
     const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(
@@ -139,7 +144,17 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
     // (2 NW p is a multiple of 4, so r & 3 does not depend on p.)
     const int wrow = 2 * wave + (lane >> 5);
     const int wchunk = (lane & 31) ^ (4 * (wrow & 3));
-    const int woff = n0 + 8 * wchunk < a.N ? (wrow * a.N + n0 + 8 * wchunk) * 2 : kTileOut;
+    int wcol = n0 + 8 * wchunk;
+    bool wcol_ok = wcol < a.N;
+    if (GATED) {
+        // tile column 8 wchunk belongs to wave column wc, MFMA tile jn, lane column jj of it
+        const int wc = (8 * wchunk) / (BN / WN), within = (8 * wchunk) % (BN / WN);
+        const int jn = within / 32, jj = within % 32;
+        const int hc = wc * (BN / WN / 2) + (jn % (TN / 2)) * 32 + jj;       // output column inside the tile
+        wcol = (jn >= TN / 2 ? a.H : 0) + n0 + hc;
+        wcol_ok = n0 + hc < a.H;
+    }
+    const int woff = wcol_ok ? (wrow * a.N + wcol) * 2 : kTileOut;
 
     uint4_t xa[NJ], gv;
     // Global loads of tile k0.  Unchecked form (the whole tile lies inside K): per-thread offsets
@@ -341,34 +356,43 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
             const int row = wm * 128 + i * 32 + 8 * (r >> 2) + rowq + (r & 3);
             const float ri = FUSED ? s_rinv[row] : 1.f;
             if (m0 + row < a.M) {
-                const int c0 = n0 + wn * (BN / WN) + col_l;
-                u16* yrow = a.Y + size_t(m0 + row) * a.N + c0;
+                if (GATED) {
+                    const int c0 = n0 + wn * (BN / WN / 2) + col_l;
+                    u16* yrow = a.Y + size_t(m0 + row) * a.H + c0;
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    if (c0 + j * 32 < a.N) yrow[j * 32] = Elem<T>::from_f32(acc[i][j][r] * ri);
+                    for (int j = 0; j < TN / 2; ++j)
+                        if (c0 + j * 32 < a.H)
+                            yrow[j * 32] = Elem<T>::from_f32(silu(acc[i][j][r] * ri) * (acc[i][j + TN / 2][r] * ri));
+                } else {
+                    const int c0 = n0 + wn * (BN / WN) + col_l;
+                    u16* yrow = a.Y + size_t(m0 + row) * a.N + c0;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        if (c0 + j * 32 < a.N) yrow[j * 32] = Elem<T>::from_f32(acc[i][j][r] * ri);
+                }
             }
         }
 }
 
 // ------------------------------------------------------------------------------------------- host
-template <typename T, bool FUSED, int NW>
+template <typename T, bool FUSED, int NW, bool GATED>
 static hipError_t tile_go(const TileArgs& a, dim3 grid, hipStream_t s)
 {
     static bool lds_raised = false;
     if (!lds_raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)tile_kernel<T, FUSED, NW>,
+        hipError_t e = hipFuncSetAttribute((const void*)tile_kernel<T, FUSED, NW, GATED>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(kTileLds));
         if (e != hipSuccess) return e;
         lds_raised = true;
     }
-    tile_kernel<T, FUSED, NW><<<grid, 64 * NW, kTileLds, s>>>(a);
+    tile_kernel<T, FUSED, NW, GATED><<<grid, 64 * NW, kTileLds, s>>>(a);
     return hipGetLastError();
 }
 
-template <typename T, bool FUSED>
+template <typename T, bool FUSED, bool GATED>
 static hipError_t tile_nw(const TileArgs& a, dim3 grid, int nw, hipStream_t s)
 {
-    return nw == 8 ? tile_go<T, FUSED, 8>(a, grid, s) : tile_go<T, FUSED, 4>(a, grid, s);
+    return nw == 8 ? tile_go<T, FUSED, 8, GATED>(a, grid, s) : tile_go<T, FUSED, 4, GATED>(a, grid, s);
 }
 
 hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
@@ -391,17 +415,24 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
     TileArgs a;
     a.X = (const u16*)p.X; a.g = (const u16*)p.g; a.W = (const u16*)p.W; a.Y = (u16*)p.Y;
     a.M = p.M; a.K = p.K; a.N = p.N; a.eps = p.eps; a.inv_K = 1.0f / float(p.K);
+    if (p.gated && (p.N % 16 != 0 || !p.fused)) {
+        if (why) *why = "gated block: tile variant needs H % 8 == 0";
+        return hipErrorInvalidValue;
+    }
+    a.H = p.gated ? p.N / 2 : 0;
     a.tiles_m = (p.M + BM - 1) / BM;
-    a.tiles_n = (p.N + BN - 1) / BN;
+    a.tiles_n = p.gated ? (a.H + BN / 2 - 1) / (BN / 2) : (p.N + BN - 1) / BN;
     if (int64_t(a.tiles_m) * a.tiles_n >= (int64_t(1) << 31)) {
         if (why) *why = "too many tiles";
         return hipErrorInvalidValue;
     }
     dim3 grid(a.tiles_m * a.tiles_n);
     const bool fused = p.fused != 0;
+    if (p.gated)
+        return p.dt == F16 ? tile_nw<Fp16, true, true>(a, grid, nw, s) : tile_nw<Bf16, true, true>(a, grid, nw, s);
     if (p.dt == F16)
-        return fused ? tile_nw<Fp16, true>(a, grid, nw, s) : tile_nw<Fp16, false>(a, grid, nw, s);
-    return fused ? tile_nw<Bf16, true>(a, grid, nw, s) : tile_nw<Bf16, false>(a, grid, nw, s);
+        return fused ? tile_nw<Fp16, true, false>(a, grid, nw, s) : tile_nw<Fp16, false, false>(a, grid, nw, s);
+    return fused ? tile_nw<Bf16, true, false>(a, grid, nw, s) : tile_nw<Bf16, false, false>(a, grid, nw, s);
 }
 
 }  // namespace rmsnl

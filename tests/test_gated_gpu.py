@@ -1,0 +1,160 @@
+"""Parity of the gated block (RMSNorm, the two products, SiLU(gate) * up in one kernel) against the
+fp64 oracle, through the C ABI.  Needs an MI355X.
+
+Bar: see util.compare_gated (the plain block's tolerance propagated through the gate, plus the
+output rounding).  Inputs are seeded and synthetic; W is [K][2H] = [gate | up].
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from util import compare, compare_gated, to_device, to_host_f64, upload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rl():
+    import torch
+    import paper_2405_05751_amd as pkg
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    yield pkg
+    pkg.rl_set_variant("auto")
+    pkg.rl_set_tuning(0, 0)
+
+
+def _run(rl, w, variant="auto", tuning=(0, 0), rows=None):
+    import torch
+    rl.rl_set_variant(variant)
+    rl.rl_set_tuning(*tuning)
+    try:
+        X, g, W = upload(w)
+        Y = rl.rmsnorm_gated_mlp(X, g, W, w.eps)
+        torch.cuda.synchronize()
+        used = rl.rl_last_variant()
+    finally:
+        rl.rl_set_variant("auto")
+        rl.rl_set_tuning(0, 0)
+    if rows is not None:
+        Y = Y[torch.from_numpy(np.asarray(rows)).cuda()]
+    return to_host_f64(Y, w.dtype), used
+
+
+def test_gateup_config(rl):
+    """Config 4 read as the gated MLP it comes from: X 64x4096, W 4096x(2*14336)."""
+    w = workloads.config("gateup")
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps, rows=w.check_rows)
+    Y, used = _run(rl, w, rows=w.check_rows)
+    assert used == "skinny"
+    worst = compare_gated(Y, Z, w.dtype, "gateup gated")
+    print(f"gateup gated: variant {used}, worst err/bound {worst:.3f}")
+
+
+SHAPES = [
+    # M, K, H
+    (1, 64, 8), (2, 72, 136), (5, 264, 40), (8, 512, 256), (16, 1024, 2048), (17, 520, 200),
+    (33, 1032, 392), (64, 264, 584), (65, 256, 128), (100, 520, 392), (130, 1544, 264),
+    (257, 264, 136), (300, 776, 648), (512, 512, 512),
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("variant", ["auto", "skinny", "tile", "naive"])
+@pytest.mark.parametrize("M,K,H", SHAPES)
+def test_gated_shapes(rl, M, K, H, variant, dtype):
+    if variant == "skinny" and M > 64:
+        pytest.skip("skinny needs M <= 64")
+    w = workloads.make(M, K, 2 * H, dtype, 1e-5, 7000 + M * 3 + K + H, outlier_frac=0.1 if M > 8 else 0.0)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used = _run(rl, w, variant)
+    if variant != "auto":
+        assert used == variant
+    compare_gated(Y, Z, dtype, f"gated {M}x{K}x2*{H} {dtype}/{variant}->{used}")
+
+
+@pytest.mark.parametrize("n_tile,k_split", [(128, 2), (128, 4), (64, 3), (32, 8), (16, 2)])
+def test_gated_split_k(rl, n_tile, k_split):
+    """The cross-workgroup exchange with the gated epilogue in the last arriver."""
+    w = workloads.make(16, 4096, 2 * 1096, "bf16", 1e-5, 7100 + n_tile + k_split)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used = _run(rl, w, "skinny", tuning=(n_tile, k_split))
+    assert used == "skinny"
+    compare_gated(Y, Z, "bf16", f"gated split n_tile={n_tile} k_split={k_split}")
+
+
+@pytest.mark.parametrize("M,K,H", [(1, 1, 1), (3, 100, 7), (4, 513, 33), (9, 130, 12), (70, 77, 50)])
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_gated_any_shape_falls_back(rl, M, K, H, dtype):
+    w = workloads.make(M, K, 2 * H, dtype, 1e-5, 7200 + M + K + H)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used = _run(rl, w, "auto")
+    compare_gated(Y, Z, dtype, f"gated odd {M}x{K}x2*{H} {dtype}->{used}")
+
+
+def test_gated_prefill_sized_tile(rl):
+    """A tile-kernel shape with several tiles each way and ragged edges, on sampled rows."""
+    w = workloads.make(1000, 2048, 2 * 1160, "bf16", 1e-5, 7300)
+    rows = np.arange(0, 1000, 37)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps, rows=rows)
+    Y, used = _run(rl, w, rows=rows)
+    assert used == "tile"
+    compare_gated(Y, Z, "bf16", "gated 1000x2048x2*1160")
+
+
+def test_gated_hand_case(rl, golden_hand_cases):
+    """H1's inputs through the gated block (G2 of the golden file); tiny, so it runs on the fallback."""
+    w = workloads.Workload("H1", 2, 3, 2, "f32", 0.0,
+                           workloads.to_storage(np.array([[3, 4, 0], [1, 2, 2]], np.float32), "f32"),
+                           workloads.to_storage(np.array([1, 2, 0.5], np.float32), "f32"),
+                           workloads.to_storage(np.array([[1, 0], [0, 1], [2, -2]], np.float32), "f32"),
+                           np.arange(2), np.zeros(0, np.int64))
+    Y, _ = _run(rl, w)
+    for (i, j), v in golden_hand_cases["G2"].items():
+        assert Y[i, j] == pytest.approx(v, rel=2e-6)
+
+
+def test_gated_matches_unfused_pair(rl):
+    """A/B: the library's own rmsnorm_linear followed by silu_mul agrees with the fused call."""
+    import torch
+    w = workloads.make(32, 1024, 2 * 512, "bf16", 1e-5, 7400)
+    X, g, W = upload(w)
+    Zg = rl.rmsnorm_linear(X, g, W, w.eps)
+    Yp = rl.silu_mul(Zg)
+    Yf = rl.rmsnorm_gated_mlp(X, g, W, w.eps)
+    torch.cuda.synchronize()
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    compare_gated(to_host_f64(Yf, "bf16"), Z, "bf16", "fused")
+    # the pair rounds Z to bf16 before the gate: one more rounding of each factor
+    H = 512
+    Zr = to_host_f64(Zg, "bf16")
+    want = Zr[:, :H] / (1.0 + np.exp(-Zr[:, :H])) * Zr[:, H:]
+    np.testing.assert_allclose(to_host_f64(Yp, "bf16"), want, rtol=2.0 ** -7, atol=1e-6)
+
+
+def test_gated_zero_row_and_canaries(rl):
+    import torch
+    w = workloads.make(6, 256, 2 * 136, "bf16", 0.0, 7500)
+    w.X[3] = 0
+    with np.errstate(all="ignore"):
+        Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, 0.0)
+    X, g, W = upload(w)
+    pad, H = 1024, 136
+    buf = torch.full((pad + 6 * H + pad,), 123.0, dtype=torch.bfloat16, device="cuda")
+    Y = buf[pad:pad + 6 * H].view(6, H)
+    for variant in ("skinny", "naive"):
+        Y.fill_(7.0)
+        rl.rl_set_variant(variant)
+        try:
+            rl.rmsnorm_gated_mlp(X, g, W, 0.0, Y)
+            torch.cuda.synchronize()
+        finally:
+            rl.rl_set_variant("auto")
+        assert torch.all(buf[:pad] == 123.0) and torch.all(buf[pad + 6 * H:] == 123.0)
+        compare_gated(to_host_f64(Y, "bf16"), Z, "bf16", f"gated zero row/{variant}")
+
+
+def test_gemv_refuses_the_gated_block(rl):
+    w = workloads.make(1, 256, 2 * 128, "bf16", 1e-5, 7600)
+    with pytest.raises(rl.RmsnlError):
+        _run(rl, w, "gemv")

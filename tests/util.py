@@ -50,3 +50,34 @@ def compare(Y_gpu: np.ndarray, Z_oracle: np.ndarray, dtype: str, what: str = "")
     g_ratio = float(err.max() / max(glob_rms, tiny))
     assert g_ratio <= tol, f"{what}: max|err|/rms(Y) = {g_ratio:.3e} > {tol}"
     return g_ratio, glob_rms
+
+
+def compare_gated(Y_gpu: np.ndarray, Z_oracle: np.ndarray, dtype: str, what: str = ""):
+    """Bar for the gated block Y = SiLU(G) * U with [G | U] = Z, the plain block's fp64 output.
+
+    The plain block is allowed |dG|, |dU| <= tol * rms(Z).  Propagated through the gate
+    (|SiLU'| <= 1.1) and followed by one rounding to the storage type (2^-8 |Y| covers bf16's
+    2^-9 with margin; fp32: 1e-6):
+        |err| <= tol * rms(Z) * (1.1 |U| + |SiLU(G)|) + r |Y|
+    checked elementwise; NaN positions must agree.  Returns the largest err / bound.
+    """
+    tol = TOL[dtype]
+    r = 1e-6 if dtype == "f32" else 2.0 ** -8
+    H = Z_oracle.shape[1] // 2
+    assert Y_gpu.shape == (Z_oracle.shape[0], H), (what, Y_gpu.shape, Z_oracle.shape)
+    import oracle
+    G, U = Z_oracle[:, :H], Z_oracle[:, H:]
+    with np.errstate(all="ignore"):
+        Y = oracle.silu_mul_f64(Z_oracle)                                   # SiLU(G) * U
+        S = oracle.silu_mul_f64(np.concatenate([G, np.ones_like(G)], 1))    # SiLU(G)
+    nan_o, nan_g = np.isnan(Y), np.isnan(Y_gpu)
+    assert np.array_equal(nan_o, nan_g), f"{what}: NaN positions differ"
+    ok = ~nan_o
+    if not ok.any():
+        return 0.0
+    rmsZ = float(np.sqrt(np.nanmean(np.where(np.isnan(Z_oracle), np.nan, Z_oracle) ** 2)))
+    bound = tol * rmsZ * (1.1 * np.abs(U) + np.abs(S)) + r * np.abs(Y) + np.finfo(np.float64).tiny
+    ratio = np.abs(Y_gpu - Y)[ok] / bound[ok]
+    worst = float(ratio.max())
+    assert worst <= 1.0, f"{what}: |err| / bound = {worst:.3f} > 1 (tol {tol})"
+    return worst
