@@ -50,7 +50,7 @@ def _time_region(fn_enqueue, torch):
     return start.elapsed_time(end), wall
 
 
-def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=True, gated=False):
+def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=True, gated=False, autotune=False):
     import workloads
     from tests.util import compare, compare_gated, to_device, to_host_f64
 
@@ -69,6 +69,10 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
         Xs.append(X0.clone()); gs.append(g0.clone()); Ws.append(W0.clone()); Ys.append(torch.empty_like(Ys[0]))
 
     rl.rl_set_variant(variant)
+    tuned = None
+    if autotune:
+        rl.rl_autotune(X0, g0, W0, w.eps, Ys[0], gated=gated, reps=20)
+        tuned = rl.rl_autotune_get(w.M, w.K, w.N, tdt, gated)
 
     fused_call = rl.rmsnorm_gated_mlp if gated else rl.rmsnorm_linear
 
@@ -139,8 +143,9 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
         "TBps": abytes / (per_step_ms * 1e-3) / 1e12, "TBps_warm": abytes / (warm_ms / steps * 1e-3) / 1e12,
         "TFLOPs": w.flops / (per_step_ms * 1e-3) / 1e12,
         "algorithmic_bytes": abytes, "flops": w.flops,
-        "max_err_over_rmsY": parity,
+        "max_err_over_rmsY": parity, "autotuned": tuned,
     }
+    rl.rl_autotune_clear()
     if mem_bound:
         res["roofline_frac"] = res["TBps"] * 1e3 / HBM_PEAK_GBS
     else:
@@ -183,6 +188,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="enqueue the timed steps one by one")
     ap.add_argument("--others", action="store_true", help="also time the other four configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
+    ap.add_argument("--autotune", action="store_true",
+                    help="let the library's launch-shape tuner pick the shape for this workload first")
     ap.add_argument("--gated", action="store_true",
                     help="time the gated block (SiLU(gate) * up epilogue, W read as [gate | up]) on the workload")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="MiB",
@@ -213,7 +220,7 @@ def main():
     name = args.workload
     steps = args.steps if args.steps is not None else (20 if name == "prefill" else 200)
     res, w = run_workload(rl, torch, name, steps, args.warmup, args.variant, use_graph=not args.no_graph,
-                          gated=args.gated)
+                          gated=args.gated, autotune=args.autotune)
     mem_bound = w.M <= 64
     if mem_bound:
         metric, unit, value = "fused RMSNorm+MatMul TB/s", "TB/s", res["TBps"]

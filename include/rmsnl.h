@@ -111,6 +111,30 @@ rl_variant rl_last_variant(void);
 rl_status rl_set_tuning(int n_tile, int k_split);
 
 /*
+ * Launch-shape tuner: the schedule half of the paper's search (grid dimensions, and here the K
+ * split that stands in for its for-loop dimension), restricted to this library's kernel family;
+ * the paper reports that the choice of grid dimensions alone is worth part of its gain.
+ *
+ * rl_autotune runs every launch shape the library has for the call (variant x columns per
+ * workgroup x K slabs, or waves per workgroup for the tile variant) on the caller's own device
+ * buffers: two warm-up launches, then `reps` (1..1000) timed ones between HIP events on `stream`.
+ * The fastest is remembered for (M, K, N, dt, gated) and used by later RL_AUTO calls of exactly
+ * that shape; forced variants are not affected.  `gated` != 0 tunes rmsnorm_gated_mlp (N = 2H, Y is
+ * [M][H]), else rmsnorm_linear.  Y is overwritten by every candidate (all compute the same block).
+ * This is the one entry point that synchronises with the stream (it waits on its events); it
+ * times on the buffers as they are, so a W that fits the 256 MB last-level cache is timed warm.
+ * *best_us (may be NULL) receives the winner's time per launch in microseconds.
+ * rl_autotune_get reports the remembered choice (variant RL_AUTO if there is none);
+ * rl_autotune_clear forgets everything.
+ */
+rl_status rl_autotune(const void* X, const void* g, const void* W, float eps, void* Y,
+                      int64_t M, int64_t K, int64_t N, rl_dtype dt, int gated, int reps,
+                      void* stream, float* best_us);
+rl_status rl_autotune_get(int64_t M, int64_t K, int64_t N, rl_dtype dt, int gated,
+                          rl_variant* variant, int* n_tile, int* k_split);
+void rl_autotune_clear(void);
+
+/*
  * Split-K workspace (fp32 partial sums + arrival counters).  By default the library
  * allocates rl_workspace_default_bytes() once per device on first need and keeps it until
  * the process ends.  rl_set_workspace lends a caller-owned DEVICE buffer instead (for the

@@ -38,6 +38,13 @@ EXPORTS = {
                                          ctypes.c_int, ctypes.c_void_p]),
     "silu_mul": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                 ctypes.c_int, ctypes.c_void_p]),
+    "rl_autotune": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
+                                   ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                   ctypes.c_int, ctypes.c_void_p, ctypes.POINTER(ctypes.c_float)]),
+    "rl_autotune_get": (ctypes.c_int, [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                       ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int),
+                                       ctypes.POINTER(ctypes.c_int)]),
+    "rl_autotune_clear": (None, []),
     "rl_set_variant": (ctypes.c_int, [ctypes.c_int]),
     "rl_get_variant": (ctypes.c_int, []),
     "rl_last_variant": (ctypes.c_int, []),
@@ -164,6 +171,31 @@ def silu_mul(Z: torch.Tensor, Y: Optional[torch.Tensor] = None, stream=None) -> 
         Y = torch.empty((M, N // 2), dtype=Z.dtype, device=Z.device)
     _check(lib().silu_mul(_dev(Z, "Z"), _dev(Y, "Y"), M, N // 2, _DTYPES[Z.dtype], _stream(stream)))
     return Y
+
+
+def rl_autotune(X: torch.Tensor, g: torch.Tensor, W: torch.Tensor, eps: float, Y: torch.Tensor,
+                gated: bool = False, reps: int = 20, stream=None) -> float:
+    """Time every launch shape for this call and remember the fastest; returns its microseconds per launch."""
+    M, K = X.shape
+    K2, N = W.shape
+    if K2 != K or g.shape != (K,) or Y.shape != (M, N // 2 if gated else N):
+        raise ValueError("shape mismatch")
+    best = ctypes.c_float(0.0)
+    _check(lib().rl_autotune(_dev(X, "X"), _dev(g, "g"), _dev(W, "W"), float(eps), _dev(Y, "Y"), M, K, N,
+                             _DTYPES[X.dtype], int(bool(gated)), int(reps), _stream(stream), ctypes.byref(best)))
+    return float(best.value)
+
+
+def rl_autotune_get(M: int, K: int, N: int, dtype: torch.dtype, gated: bool = False):
+    """(variant name, n_tile, k_split) remembered for the shape; variant "auto" if none."""
+    v, nt, ks = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().rl_autotune_get(M, K, N, _DTYPES[dtype], int(bool(gated)), ctypes.byref(v), ctypes.byref(nt),
+                                 ctypes.byref(ks)))
+    return VARIANT_NAMES[v.value], nt.value, ks.value
+
+
+def rl_autotune_clear() -> None:
+    lib().rl_autotune_clear()
 
 
 def rl_set_variant(v) -> None:

@@ -7,7 +7,10 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <map>
 #include <mutex>
+#include <tuple>
+#include <vector>
 
 using namespace rmsnl;
 
@@ -28,6 +31,11 @@ int g_trace_groups = 0;
 struct Workspace { void* ptr; size_t bytes; bool owned; };
 Workspace g_ws[kMaxDevices] = {};
 Workspace g_lent[kMaxDevices] = {};
+
+// launch shapes found by rl_autotune, by (M, K, N, dtype, gated)
+struct Tuned { rl_variant variant; int n_tile, k_split; };
+typedef std::tuple<int, int, int, int, int> TuneKey;
+std::map<TuneKey, Tuned> g_tuned;
 
 rl_status fail(rl_status st, const char* fmt, const char* a = "", const char* b = "")
 {
@@ -105,9 +113,33 @@ rl_variant choose_auto(const Problem& p)
     return RL_MFMA_TILE;
 }
 
+// one attempt at one variant; hipErrorInvalidValue = the variant cannot run the shape
+hipError_t launch_variant(rl_variant v, Problem& p, hipStream_t s, const char** why, rl_status* ws_status)
+{
+    *ws_status = RL_OK;
+    size_t need = 0;
+    if (v == RL_GEMV_SPLITK) need = gemv_workspace_bytes(p);
+    else if (v == RL_MFMA_SKINNY) need = skinny_workspace_bytes(p);
+    p.ws_partial = nullptr; p.ws_sumsq = nullptr; p.ws_counter = nullptr;
+    if (need) {
+        Workspace ws;
+        *ws_status = get_workspace(need, &ws);
+        if (*ws_status != RL_OK) return hipErrorUnknown;
+        carve(ws, p);
+    }
+    switch (v) {
+    case RL_GEMV_SPLITK: return launch_gemv(p, s, why);
+    case RL_MFMA_SKINNY: return launch_skinny(p, s, why);
+    case RL_MFMA_TILE:   return launch_tile(p, s, why);
+    case RL_NAIVE:       return launch_naive(p, s, why);
+    default:             return hipErrorInvalidValue;
+    }
+}
+
 rl_status run(Problem& p, void* stream)
 {
     rl_variant forced;
+    Tuned tuned{RL_AUTO, 0, 0};
     {
         std::lock_guard<std::mutex> lk(g_mu);
         read_env_locked();
@@ -116,15 +148,20 @@ rl_status run(Problem& p, void* stream)
         p.k_split = g_k_split;
         p.trace = g_trace;
         p.trace_groups = g_trace_groups;
+        if (forced == RL_AUTO) {
+            auto it = g_tuned.find(TuneKey(p.M, p.K, p.N, int(p.dt), p.gated));
+            if (it != g_tuned.end() && p.fused) tuned = it->second;
+        }
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    rl_variant order[4];
+    rl_variant order[5];
     int n_order = 0;
     if (forced != RL_AUTO) {
         order[n_order++] = forced;
     } else {
         p.n_tile = 0;                      // tuning overrides apply to a forced variant only
         p.k_split = 0;
+        if (tuned.variant != RL_AUTO) order[n_order++] = tuned.variant;    // with its launch shape, see below
         rl_variant first = choose_auto(p);
         order[n_order++] = first;
         if (first == RL_MFMA_TILE) order[n_order++] = RL_MFMA_SKINNY;
@@ -133,25 +170,15 @@ rl_status run(Problem& p, void* stream)
     const char* why = "variant cannot run this shape";
     for (int i = 0; i < n_order; ++i) {
         rl_variant v = order[i];
-        hipError_t e = hipErrorInvalidValue;
         why = "variant cannot run this shape";
-        size_t need = 0;
-        if (v == RL_GEMV_SPLITK) need = gemv_workspace_bytes(p);
-        else if (v == RL_MFMA_SKINNY) need = skinny_workspace_bytes(p);
-        p.ws_partial = nullptr; p.ws_sumsq = nullptr; p.ws_counter = nullptr;
-        if (need) {
-            Workspace ws;
-            rl_status st = get_workspace(need, &ws);
-            if (st != RL_OK) return st;
-            carve(ws, p);
+        if (forced == RL_AUTO) {
+            const bool use_tuned = (i == 0 && tuned.variant != RL_AUTO);
+            p.n_tile = use_tuned ? tuned.n_tile : 0;
+            p.k_split = use_tuned ? tuned.k_split : 0;
         }
-        switch (v) {
-        case RL_GEMV_SPLITK: e = launch_gemv(p, s, &why); break;
-        case RL_MFMA_SKINNY: e = launch_skinny(p, s, &why); break;
-        case RL_MFMA_TILE:   e = launch_tile(p, s, &why); break;
-        case RL_NAIVE:       e = launch_naive(p, s, &why); break;
-        default: return fail(RL_ERR_INVALID_ARG, "unknown variant");
-        }
+        rl_status ws_status;
+        hipError_t e = launch_variant(v, p, s, &why, &ws_status);
+        if (ws_status != RL_OK) return ws_status;
         if (e == hipSuccess) { tl_last_variant = v; return RL_OK; }
         if (e != hipErrorInvalidValue) return fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
         (void)hipGetLastError();
@@ -231,6 +258,99 @@ rl_status rmsnorm(const void* X, const void* g, float eps, void* Xn, int64_t M, 
     hipError_t e = launch_rmsnorm(X, g, eps, Xn, int(M), int(K), DType(dt), static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
     return RL_OK;
+}
+
+rl_status rl_autotune(const void* X, const void* g, const void* W, float eps, void* Y,
+                      int64_t M, int64_t K, int64_t N, rl_dtype dt, int gated, int reps,
+                      void* stream, float* best_us)
+{
+    if (!X || !g || !W || !Y) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (rl_status st = check_dims(M, K, N, dt)) return st;
+    if (gated && (N % 2)) return fail(RL_ERR_INVALID_ARG, "the gated block needs an even N (= 2H)");
+    if (reps < 1 || reps > 1000) return fail(RL_ERR_INVALID_ARG, "reps must be in [1, 1000]");
+    if (!std::isfinite(eps) || eps < 0.f) return fail(RL_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    if (!aligned16(X) || !aligned16(g) || !aligned16(W) || !aligned16(Y))
+        return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    Problem base{};
+    base.X = X; base.g = g; base.W = W; base.Y = Y;
+    base.M = int(M); base.K = int(K); base.N = int(N);
+    base.eps = eps; base.fused = 1; base.gated = gated ? 1 : 0; base.dt = DType(dt);
+
+    // the launch shapes worth trying: (variant, n_tile, k_split); 0 = that kernel's own default
+    struct Cand { rl_variant v; int n_tile, k_split; };
+    std::vector<Cand> cands;
+    if (dt != RL_F32) {
+        if (!gated && M <= 16)
+            for (int nt : {128, 256, 512})
+                for (int ks : {0, 4, 8, 16, 32}) cands.push_back({RL_GEMV_SPLITK, nt, ks});
+        if (M <= 64)
+            for (int ks : {1, 2, 4, 8, 16}) cands.push_back({RL_MFMA_SKINNY, 0, ks});
+        if (M > 16)
+            for (int nw : {4, 8}) cands.push_back({RL_MFMA_TILE, 0, nw});
+    }
+    cands.push_back({RL_NAIVE, 0, 0});
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t he = hipEventCreate(&e0);
+    if (he == hipSuccess) he = hipEventCreate(&e1);
+    if (he != hipSuccess) {
+        if (e0) (void)hipEventDestroy(e0);
+        return fail(RL_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(he));
+    }
+    Tuned best{RL_AUTO, 0, 0};
+    float best_ms = 0.f;
+    rl_status result = RL_OK;
+    for (const Cand& c : cands) {
+        if (c.v == RL_NAIVE && best.variant != RL_AUTO) break;      // the fallback only if nothing else runs
+        Problem p = base;
+        p.n_tile = c.n_tile; p.k_split = c.k_split;
+        const char* why = nullptr;
+        rl_status ws_status;
+        bool ok = true;
+        for (int i = 0; i < 2 + reps && ok; ++i) {
+            if (i == 2) he = hipEventRecord(e0, s);
+            hipError_t le = launch_variant(c.v, p, s, &why, &ws_status);
+            if (ws_status != RL_OK || le == hipErrorInvalidValue) { (void)hipGetLastError(); ok = false; break; }
+            if (le != hipSuccess) { result = fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(le)); ok = false; }
+        }
+        if (result != RL_OK) break;
+        if (!ok) continue;
+        he = hipEventRecord(e1, s);
+        if (he == hipSuccess) he = hipEventSynchronize(e1);
+        float ms = 0.f;
+        if (he == hipSuccess) he = hipEventElapsedTime(&ms, e0, e1);
+        if (he != hipSuccess) { result = fail(RL_ERR_HIP, "timing: %s", hipGetErrorString(he)); break; }
+        if (best.variant == RL_AUTO || ms < best_ms) { best = Tuned{c.v, c.n_tile, c.k_split}; best_ms = ms; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (result != RL_OK) return result;
+    if (best.variant == RL_AUTO) return fail(RL_ERR_UNSUPPORTED, "no variant runs this shape");
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        g_tuned[TuneKey(base.M, base.K, base.N, int(base.dt), base.gated)] = best;
+    }
+    if (best_us) *best_us = best_ms * 1000.f / float(reps);
+    return RL_OK;
+}
+
+rl_status rl_autotune_get(int64_t M, int64_t K, int64_t N, rl_dtype dt, int gated,
+                          rl_variant* variant, int* n_tile, int* k_split)
+{
+    if (!variant || !n_tile || !k_split) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (rl_status st = check_dims(M, K, N, dt)) return st;
+    std::lock_guard<std::mutex> lk(g_mu);
+    auto it = g_tuned.find(TuneKey(int(M), int(K), int(N), int(dt), gated ? 1 : 0));
+    if (it == g_tuned.end()) { *variant = RL_AUTO; *n_tile = 0; *k_split = 0; return RL_OK; }
+    *variant = it->second.variant; *n_tile = it->second.n_tile; *k_split = it->second.k_split;
+    return RL_OK;
+}
+
+void rl_autotune_clear(void)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_tuned.clear();
 }
 
 rl_status rl_set_variant(rl_variant v)

@@ -6,6 +6,8 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
+#include <initializer_list>
 
 namespace rmsnl {
 
@@ -47,6 +49,24 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why);
 // bytes of partial-B workspace the launch of this problem would use (0 = no split)
 size_t gemv_workspace_bytes(const Problem& p);
 size_t skinny_workspace_bytes(const Problem& p);
+
+// Kernels that use more than 64 KiB of dynamic LDS have the limit raised once per device (the
+// attribute belongs to the device's copy of the kernel); one LdsOnce per group of kernels.
+struct LdsOnce { std::atomic<unsigned> devices{0}; };
+inline hipError_t raise_lds_once(LdsOnce& once, std::initializer_list<const void*> kernels, int bytes)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned bit = 1u << (dev & 31);
+    if (once.devices.load(std::memory_order_acquire) & bit) return hipSuccess;
+    for (const void* k : kernels) {
+        e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e != hipSuccess) return e;
+    }
+    once.devices.fetch_or(bit, std::memory_order_release);
+    return hipSuccess;
+}
 
 hipError_t launch_silu_mul(const void* Z, void* Y, int M, int H, DType dt, hipStream_t s);
 

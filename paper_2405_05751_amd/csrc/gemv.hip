@@ -303,16 +303,10 @@ template <typename T, int MT, int LPR>
 static hipError_t gemv_go(const GemvArgs& a, bool fused, const GemvPlan& pl, hipStream_t s)
 {
     dim3 grid(pl.n_tiles * pl.S);
-    static bool lds_raised = false;          // allow more than 64 KiB of dynamic LDS, once
-    if (!lds_raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemv_splitk_kernel<T, MT, LPR, true>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)gemv_splitk_kernel<T, MT, LPR, false>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-        if (e != hipSuccess) return e;
-        lds_raised = true;
-    }
+    static LdsOnce once;                     // allow more than 64 KiB of dynamic LDS
+    hipError_t e = raise_lds_once(once, {(const void*)gemv_splitk_kernel<T, MT, LPR, true>,
+                                         (const void*)gemv_splitk_kernel<T, MT, LPR, false>}, 96 * 1024);
+    if (e != hipSuccess) return e;
     if (fused) gemv_splitk_kernel<T, MT, LPR, true><<<grid, 64 * gemv_waves(MT), pl.lds, s>>>(a);
     else       gemv_splitk_kernel<T, MT, LPR, false><<<grid, 64 * gemv_waves(MT), pl.lds, s>>>(a);
     return hipGetLastError();

@@ -278,16 +278,11 @@ template <typename T, int MB>
 static hipError_t skinny_go(const SkinnyArgs& a, bool fused, bool gated, const SkinnyPlan& pl, hipStream_t s)
 {
     dim3 grid(pl.n_tiles * pl.S);
-    static bool lds_raised = false;          // 128 KiB of dynamic LDS at MB = 4
-    if (!lds_raised) {
-        const void* fns[3] = {(const void*)skinny_kernel<T, MB, true, false>, (const void*)skinny_kernel<T, MB, false, false>,
-                              (const void*)skinny_kernel<T, MB, true, true>};
-        for (const void* f : fns) {
-            hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
-            if (e != hipSuccess) return e;
-        }
-        lds_raised = true;
-    }
+    static LdsOnce once;                     // 128 KiB of dynamic LDS at MB = 4
+    hipError_t e = raise_lds_once(once, {(const void*)skinny_kernel<T, MB, true, false>,
+                                         (const void*)skinny_kernel<T, MB, false, false>,
+                                         (const void*)skinny_kernel<T, MB, true, true>}, 144 * 1024);
+    if (e != hipSuccess) return e;
     const int nt = 64 * skinny_waves(MB);
     if (gated)      skinny_kernel<T, MB, true, true><<<grid, nt, pl.lds, s>>>(a);
     else if (fused) skinny_kernel<T, MB, true, false><<<grid, nt, pl.lds, s>>>(a);

@@ -378,13 +378,9 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
 template <typename T, bool FUSED, int NW, bool GATED>
 static hipError_t tile_go(const TileArgs& a, dim3 grid, hipStream_t s)
 {
-    static bool lds_raised = false;
-    if (!lds_raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)tile_kernel<T, FUSED, NW, GATED>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, int(kTileLds));
-        if (e != hipSuccess) return e;
-        lds_raised = true;
-    }
+    static LdsOnce once;
+    hipError_t e = raise_lds_once(once, {(const void*)tile_kernel<T, FUSED, NW, GATED>}, int(kTileLds));
+    if (e != hipSuccess) return e;
     tile_kernel<T, FUSED, NW, GATED><<<grid, 64 * NW, kTileLds, s>>>(a);
     return hipGetLastError();
 }

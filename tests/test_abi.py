@@ -110,3 +110,18 @@ def test_product_does_not_import_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text, f
                 assert "liboracle" not in text, f
+
+
+def test_gated_and_tuner_reject_bad_arguments(rl):
+    L = rl.lib()
+    assert L.rmsnorm_gated_mlp(None, 16, 16, 0.0, 16, 1, 8, 8, 1, None) == ERR_INVALID
+    assert L.rmsnorm_gated_mlp(16, 16, 16, 0.0, 16, 1, 8, 0, 1, None) == ERR_INVALID
+    assert L.rmsnorm_gated_mlp(16, 16, 16, -1.0, 16, 1, 8, 8, 1, None) == ERR_INVALID
+    assert L.silu_mul(None, 16, 1, 8, 1, None) == ERR_INVALID
+    assert L.silu_mul(16, 24, 1, 8, 1, None) == ERR_INVALID
+    assert L.rl_autotune(None, 16, 16, 0.0, 16, 1, 8, 8, 1, 0, 5, None, None) == ERR_INVALID
+    assert L.rl_autotune(16, 16, 16, 0.0, 16, 1, 8, 7, 1, 1, 5, None, None) == ERR_INVALID      # gated needs even N
+    assert L.rl_autotune(16, 16, 16, 0.0, 16, 1, 8, 8, 1, 0, 0, None, None) == ERR_INVALID      # reps
+    import torch
+    rl.rl_autotune_clear()
+    assert rl.rl_autotune_get(4, 64, 64, torch.bfloat16) == ("auto", 0, 0)

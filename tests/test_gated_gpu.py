@@ -158,3 +158,32 @@ def test_gemv_refuses_the_gated_block(rl):
     w = workloads.make(1, 256, 2 * 128, "bf16", 1e-5, 7600)
     with pytest.raises(rl.RmsnlError):
         _run(rl, w, "gemv")
+
+
+# ------------------------------------------------------------------ the launch-shape tuner
+@pytest.mark.parametrize("M,K,N,gated", [(1, 2048, 1024, False), (16, 1024, 2048, False), (48, 512, 1024, True),
+                                         (200, 512, 768, False), (3, 100, 7, False)])
+def test_autotune_picks_a_runnable_shape_and_auto_uses_it(rl, M, K, N, gated):
+    import torch
+    w = workloads.make(M, K, N, "bf16", 1e-5, 7700 + M + K + N)
+    X, g, W = upload(w)
+    Y = torch.empty((M, N // 2 if gated else N), dtype=torch.bfloat16, device="cuda")
+    rl.rl_autotune_clear()
+    try:
+        us = rl.rl_autotune(X, g, W, w.eps, Y, gated=gated, reps=5)
+        variant, n_tile, k_split = rl.rl_autotune_get(M, K, N, torch.bfloat16, gated)
+        assert us > 0 and variant in ("gemv", "skinny", "tile", "naive")
+        print(f"{M}x{K}x{N} gated={gated}: {variant} n_tile={n_tile} k_split={k_split}, {us:.2f} us")
+        rl.rl_set_variant("auto")
+        Y.fill_(float("nan"))
+        (rl.rmsnorm_gated_mlp if gated else rl.rmsnorm_linear)(X, g, W, w.eps, Y)
+        torch.cuda.synchronize()
+        assert rl.rl_last_variant() == variant
+        Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+        if gated:
+            compare_gated(to_host_f64(Y, "bf16"), Z, "bf16", "tuned gated")
+        else:
+            compare(to_host_f64(Y, "bf16"), Z, "bf16", "tuned")
+    finally:
+        rl.rl_autotune_clear()
+    assert rl.rl_autotune_get(M, K, N, torch.bfloat16, gated) == ("auto", 0, 0)
