@@ -135,6 +135,20 @@ rl_status rl_autotune_get(int64_t M, int64_t K, int64_t N, rl_dtype dt, int gate
 void rl_autotune_clear(void);
 
 /*
+ * The block over a prime field, for the paper's way of certifying a rewrite (random tests over
+ * finite fields, Table 3: add, mul, div and sqrt as modular operations): X [M][K], g [K], W [K][N],
+ * Y [M][N] are DEVICE arrays of uint32 with entries in [0, p), p a prime in [3, 32749] that does not
+ * divide K.  reordered = 0 evaluates Eq. 1 and then the product (Fig. 2a); reordered = 1 the
+ * rewritten graph (Fig. 2b: product first, division by the root afterwards).  Equal outputs on
+ * random inputs certify the reordering with the paper's error bound.  sqrt is the canonical root
+ * (smallest y with y^2 = x; for a non-residue x the smallest y with y^2 = x n, n the least
+ * non-residue); a row whose mean square is 0 gets 0 in both forms.  Integer arithmetic only:
+ * results are exact and equal, bit for bit, to the reference evaluation.
+ */
+rl_status rl_ff_rmsnorm_linear(const void* X, const void* g, const void* W, void* Y,
+                               int64_t M, int64_t K, int64_t N, uint32_t p, int reordered, void* stream);
+
+/*
  * Split-K workspace (fp32 partial sums + arrival counters).  By default the library
  * allocates rl_workspace_default_bytes() once per device on first need and keeps it until
  * the process ends.  rl_set_workspace lends a caller-owned DEVICE buffer instead (for the

@@ -152,3 +152,48 @@ def rmsnorm_gated_mlp(X, g, W, dtype: str, eps: float, rows=None) -> np.ndarray:
     The block's fp64 output is not rounded before the gate.
     """
     return silu_mul_f64(rmsnorm_linear(X, g, W, dtype, eps, rows=rows))
+
+
+# ---------------------------------------------------------------------------------------------
+# The block over a prime field (the paper's random tests over finite fields, Table 3): the same
+# graph evaluated with modular arithmetic.  Python integers, one operation at a time.
+# ---------------------------------------------------------------------------------------------
+def ff_sqrt(x: int, p: int) -> int:
+    """Canonical square root in Z_p: the smallest y with y*y = x; for a non-residue x, the smallest
+    y with y*y = x*n, n the least non-residue (so the function is total, and non-zero for x != 0)."""
+    x %= p
+    squares = {}
+    for y in range(p):
+        squares.setdefault(y * y % p, y)
+    if x in squares:
+        return squares[x]
+    n = next(v for v in range(2, p) if v not in squares)
+    return squares[x * n % p]
+
+
+def ff_rmsnorm_linear(X, g, W, p: int, reordered: bool):
+    """Eq. 1 then the product over Z_p (reordered=False), or the rewritten form (division after the
+    product, reordered=True).  X [M][K], g [K], W [K][N] integer arrays with entries in [0, p).
+    A row whose mean square is 0 has no inverse root: its outputs are defined as 0 in both forms."""
+    X = np.asarray(X, dtype=np.int64); g = np.asarray(g, dtype=np.int64); W = np.asarray(W, dtype=np.int64)
+    M, K = X.shape
+    N = W.shape[1]
+    inv = lambda v: pow(int(v), p - 2, p)
+    Y = np.zeros((M, N), dtype=np.int64)
+    for i in range(M):
+        a = 0
+        for k in range(K):
+            a = (a + int(X[i, k]) * int(X[i, k])) % p
+        r = ff_sqrt(a * inv(K % p) % p, p)
+        if r == 0:
+            continue
+        rinv = inv(r)
+        for n in range(N):
+            acc = 0
+            for k in range(K):
+                if reordered:
+                    acc = (acc + (int(X[i, k]) * int(g[k]) % p) * int(W[k, n])) % p
+                else:
+                    acc = (acc + ((int(X[i, k]) * int(g[k]) % p) * rinv % p) * int(W[k, n])) % p
+            Y[i, n] = acc * rinv % p if reordered else acc
+    return Y

@@ -45,6 +45,9 @@ EXPORTS = {
                                        ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int),
                                        ctypes.POINTER(ctypes.c_int)]),
     "rl_autotune_clear": (None, []),
+    "rl_ff_rmsnorm_linear": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_uint32,
+                                            ctypes.c_int, ctypes.c_void_p]),
     "rl_set_variant": (ctypes.c_int, [ctypes.c_int]),
     "rl_get_variant": (ctypes.c_int, []),
     "rl_last_variant": (ctypes.c_int, []),
@@ -196,6 +199,19 @@ def rl_autotune_get(M: int, K: int, N: int, dtype: torch.dtype, gated: bool = Fa
 
 def rl_autotune_clear() -> None:
     lib().rl_autotune_clear()
+
+
+def rl_ff_rmsnorm_linear(X: torch.Tensor, g: torch.Tensor, W: torch.Tensor, p: int, reordered: bool,
+                         stream=None) -> torch.Tensor:
+    """The block over Z_p on int32/uint32 device tensors with entries in [0, p); returns Y [M, N] (int32)."""
+    M, K = X.shape
+    K2, N = W.shape
+    if K2 != K or g.shape != (K,) or any(t.dtype != torch.int32 for t in (X, g, W)):
+        raise ValueError("shape or dtype mismatch (int32 tensors expected)")
+    Y = torch.empty((M, N), dtype=torch.int32, device=X.device)
+    _check(lib().rl_ff_rmsnorm_linear(_dev(X, "X"), _dev(g, "g"), _dev(W, "W"), _dev(Y, "Y"), M, K, N, int(p),
+                                      int(bool(reordered)), _stream(stream)))
+    return Y
 
 
 def rl_set_variant(v) -> None:

@@ -353,6 +353,22 @@ void rl_autotune_clear(void)
     g_tuned.clear();
 }
 
+rl_status rl_ff_rmsnorm_linear(const void* X, const void* g, const void* W, void* Y,
+                               int64_t M, int64_t K, int64_t N, uint32_t p, int reordered, void* stream)
+{
+    if (!X || !g || !W || !Y) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (rl_status st = check_dims(M, K, N, RL_F32)) return st;
+    if (M > 65535) return fail(RL_ERR_UNSUPPORTED, "the finite-field block supports M <= 65535");
+    bool prime = p >= 3 && p <= 32749;
+    for (uint32_t d = 2; prime && d * d <= p; ++d) prime = (p % d) != 0;
+    if (!prime) return fail(RL_ERR_INVALID_ARG, "p must be a prime in [3, 32749]");
+    if (K % int64_t(p) == 0) return fail(RL_ERR_INVALID_ARG, "p must not divide K (the mean needs 1/K)");
+    hipError_t e = launch_ff_block(X, g, W, Y, int(M), int(K), int(N), p, reordered ? 1 : 0,
+                                   static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+    return RL_OK;
+}
+
 rl_status rl_set_variant(rl_variant v)
 {
     if (v < RL_AUTO || v > RL_NAIVE) return fail(RL_ERR_INVALID_ARG, "unknown variant");

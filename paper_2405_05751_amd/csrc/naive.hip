@@ -222,6 +222,68 @@ hipError_t launch_rmsnorm(const void* X, const void* g, float eps, void* Xn, int
 }
 
 // ---------------------------------------------------------------------------------------------
+// The block over Z_p (random tests over finite fields): one thread per output, modular arithmetic
+// one operation at a time, in the order of the graph it stands for.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t ff_pow(uint32_t b, uint32_t e, uint32_t p)
+{
+    uint32_t r = 1;
+    b %= p;
+    while (e) {
+        if (e & 1) r = r * b % p;
+        b = b * b % p;
+        e >>= 1;
+    }
+    return r;
+}
+
+// canonical root: the smallest y with y^2 = x, or, for a non-residue, with y^2 = x n (n the least non-residue)
+__device__ uint32_t ff_sqrt(uint32_t x, uint32_t p)
+{
+    for (uint32_t y = 0; y < p; ++y)
+        if (y * y % p == x) return y;
+    uint32_t n = 2;
+    while (ff_pow(n, (p - 1) / 2, p) == 1) ++n;      // Euler's criterion: first n that is no square
+    const uint32_t t = x * n % p;
+    for (uint32_t y = 0; y < p; ++y)
+        if (y * y % p == t) return y;
+    return 0;
+}
+
+__global__ __launch_bounds__(256) void ff_block_kernel(const uint32_t* __restrict__ X, const uint32_t* __restrict__ g,
+                                                       const uint32_t* __restrict__ W, uint32_t* __restrict__ Y,
+                                                       int M, int K, int N, uint32_t p, int reordered)
+{
+    const int n = blockIdx.x * 256 + threadIdx.x, i = blockIdx.y;
+    if (n >= N) return;
+    const uint32_t* xi = X + size_t(i) * K;
+    uint32_t a = 0;
+    for (int k = 0; k < K; ++k) a = (a + xi[k] * xi[k]) % p;
+    const uint32_t r = ff_sqrt(a * ff_pow(uint32_t(K) % p, p - 2, p) % p, p);
+    uint32_t y = 0;
+    if (r != 0) {
+        const uint32_t rinv = ff_pow(r, p - 2, p);
+        uint32_t acc = 0;
+        for (int k = 0; k < K; ++k) {
+            uint32_t t = xi[k] * g[k] % p;
+            if (!reordered) t = t * rinv % p;            // Eq. 1 first: normalise, then multiply by W
+            acc = (acc + t * W[size_t(k) * N + n]) % p;
+        }
+        y = reordered ? acc * rinv % p : acc;            // rewritten graph: divide after the product
+    }
+    Y[size_t(i) * N + n] = y;
+}
+
+hipError_t launch_ff_block(const void* X, const void* g, const void* W, void* Y, int M, int K, int N,
+                           uint32_t p, int reordered, hipStream_t s)
+{
+    dim3 grid((N + 255) / 256, M);
+    ff_block_kernel<<<grid, 256, 0, s>>>((const uint32_t*)X, (const uint32_t*)g, (const uint32_t*)W, (uint32_t*)Y,
+                                         M, K, N, p, reordered);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 // Probes
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void probe_copy_kernel(uint4_t* __restrict__ dst,
