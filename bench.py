@@ -153,6 +153,54 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
     return res, w
 
 
+def run_ntrans(rl, torch, steps, warmup, M=16384, D=2048, dtype="bf16", with_cpu=True):
+    """The nTrans chain y = Norm(x + alpha Norm(h - x)) on seeded rows of an nGPT-sized hidden state."""
+    import oracle
+    import workloads
+    from tests.util import compare, to_device, to_host_f64
+    rng = np.random.default_rng(240505751 + 11)
+    x = workloads.to_storage(rng.standard_normal((M, D), dtype=np.float32), dtype)
+    h = workloads.to_storage(rng.standard_normal((M, D), dtype=np.float32), dtype)
+    a = workloads.to_storage((rng.uniform(0.0, 1.0, D) * 0.3).astype(np.float32), dtype)
+    eps = float(np.float32(1e-6))
+    abytes = 2 * (3 * M * D + D)
+    copies = max(1, -(-ROTATE_BYTES // abytes))
+    xs = [to_device(x, dtype)]; hs = [to_device(h, dtype)]; ad = to_device(a, dtype)
+    for _ in range(copies - 1):
+        xs.append(xs[0].clone()); hs.append(hs[0].clone())
+    ys = [torch.empty_like(xs[0]) for _ in range(copies)]
+    step = lambda i: rl.rl_ntrans(xs[i % copies], hs[i % copies], ad, eps, ys[i % copies])
+    for i in range(max(warmup, 1)):
+        step(i)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for i in range(steps):
+            step(i)
+    graph.replay(); torch.cuda.synchronize()
+    ev_ms, _ = min((_time_region(graph.replay, torch) for _ in range(3)), key=lambda t: t[0])
+    rows = np.arange(0, M, max(1, M // 64))
+    Z = oracle.ntrans(x[rows], h[rows], a, dtype, eps)
+    parity, _ = compare(to_host_f64(ys[0][torch.from_numpy(rows).cuda()], dtype), Z, dtype, "ntrans")
+    us = ev_ms / steps * 1e3
+    out = {"metric": "nTrans chain TB/s", "value": abytes / us / 1e6, "unit": "TB/s", "n_gpus": 1, "steps": steps,
+           "warmup": warmup, "ms_per_step": us / 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": dtype, "data": "synthetic",
+           "config": {"workload": f"ntrans: x, h {M}x{D}, alpha {D}, {dtype}", "copies_rotated": copies},
+           "roofline": {"bound": "hbm", "achieved": abytes / us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": abytes / us / 1e3 / HBM_PEAK_GBS, "traffic": None, "kernel": "ntrans_vec_kernel",
+                        "us_per_launch": us},
+           "detail": {"us_per_step": us, "algorithmic_bytes": abytes, "max_err_over_rmsY": parity}}
+    if with_cpu:
+        n, t0, reps = min(M, 4096), time.perf_counter(), 0
+        while time.perf_counter() - t0 < 10.0 and reps < 200:
+            oracle.ntrans(x[:n], h[:n], a, dtype, eps); reps += 1
+        sec = (time.perf_counter() - t0) / reps
+        out["cpu_baseline"] = {"value": 2 * (3 * n * D + D) / sec / 1e12, "unit": "TB/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": f"{reps} run(s) of the fp64 oracle on {n} of {M} rows, {sec:.4f} s each"}
+    return out
+
+
 def cpu_baseline(w, mem_bound, budget_s=12.0):
     """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
     import oracle
@@ -218,6 +266,10 @@ def main():
         return
 
     name = args.workload
+    if name == "ntrans":
+        print(json.dumps(run_ntrans(rl, torch, args.steps if args.steps is not None else 100, args.warmup,
+                                    with_cpu=not args.no_cpu)))
+        return
     steps = args.steps if args.steps is not None else (20 if name == "prefill" else 200)
     res, w = run_workload(rl, torch, name, steps, args.warmup, args.variant, use_graph=not args.no_graph,
                           gated=args.gated, autotune=args.autotune)

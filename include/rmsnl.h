@@ -111,6 +111,19 @@ rl_variant rl_last_variant(void);
 rl_status rl_set_tuning(int n_tile, int k_split);
 
 /*
+ * Normalised-Transformer chain in one kernel (the paper's nTrans benchmark: two normalisations
+ * around an elementwise step, three kernels in existing systems):
+ *
+ *     Y[i][:] = Norm(X[i][:] + alpha (.) Norm(H[i][:] - X[i][:])),   Norm(v) = v / sqrt(mean(v^2) + eps)
+ *
+ * X, H, Y [M][D] and alpha [D] DEVICE arrays of type dt, row-major, 16-byte aligned; Y may not
+ * overlap the inputs.  "Norm" is read as Eq. 1 without a gain (the paper does not say which
+ * normalisation the benchmark uses).  fp32 arithmetic, one rounding when stored.  M < 2^31.
+ */
+rl_status rl_ntrans(const void* X, const void* H, const void* alpha, float eps, void* Y,
+                    int64_t M, int64_t D, rl_dtype dt, void* stream);
+
+/*
  * Launch-shape tuner: the schedule half of the paper's search (grid dimensions, and here the K
  * split that stands in for its for-loop dimension), restricted to this library's kernel family;
  * the paper reports that the choice of grid dimensions alone is worth part of its gain.

@@ -45,6 +45,9 @@ def _load():
                                               ctypes.c_int, ctypes.c_double, ctypes.c_long,
                                               ctypes.c_long, ctypes.c_long, ctypes.c_void_p,
                                               ctypes.c_long, ctypes.c_void_p]
+        lib.oracle_ntrans.restype = ctypes.c_int
+        lib.oracle_ntrans.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                      ctypes.c_double, ctypes.c_long, ctypes.c_long, ctypes.c_void_p]
         lib.oracle_silu_mul_f64.restype = None
         lib.oracle_silu_mul_f64.argtypes = [ctypes.c_void_p, ctypes.c_long, ctypes.c_long, ctypes.c_void_p]
         _lib = lib
@@ -152,6 +155,19 @@ def rmsnorm_gated_mlp(X, g, W, dtype: str, eps: float, rows=None) -> np.ndarray:
     The block's fp64 output is not rounded before the gate.
     """
     return silu_mul_f64(rmsnorm_linear(X, g, W, dtype, eps, rows=rows))
+
+
+def ntrans(X, Hh, alpha, dtype: str, eps: float) -> np.ndarray:
+    """nTrans chain y = Norm(x + alpha * Norm(h - x)) on storage-typed inputs; float64 [M, D]."""
+    X = _storage(X, dtype); Hh = _storage(Hh, dtype); alpha = _storage(alpha, dtype)
+    M, D = X.shape
+    if Hh.shape != (M, D) or alpha.shape != (D,):
+        raise ValueError("shape mismatch")
+    Y = np.empty((M, D), dtype=np.float64)
+    if _load().oracle_ntrans(X.ctypes.data, Hh.ctypes.data, alpha.ctypes.data, _DT[dtype], float(eps), M, D,
+                             Y.ctypes.data) != 0:
+        raise RuntimeError("oracle_ntrans rejected its arguments")
+    return Y
 
 
 # ---------------------------------------------------------------------------------------------

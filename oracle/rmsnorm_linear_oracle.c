@@ -32,6 +32,11 @@
  * SiLU(v) = v / (1 + exp(-v)).  oracle_silu_mul_f64 is that definition on
  * doubles, applied to the block's unrounded fp64 output.
  *
+ * Normalised-Transformer chain (the paper's nTrans benchmark), y = Norm(x + alpha (Norm(h - x))),
+ * x, h [M][D], alpha [D]: oracle_ntrans takes it literally, three steps per row.  Reading: the
+ * paper does not say which normalisation "Norm" is; it is taken to be the only one the paper
+ * defines, Eq. 1 without a gain (divide by the root of the mean square, eps under the root).
+ *
  * Parity pins (tests/test_oracle_*.py): printed-by-hand 2x3 cases, the
  * eps-placement case, exact rational brute force, scale invariance, unit-RMS
  * rows, linearity, and a library float64 product; for the gate: closed forms
@@ -236,4 +241,52 @@ void oracle_silu_mul_f64(const double *z, long rows, long H, double *y)
             y[(size_t)i * H + h] = silu * zi[(size_t)H + h];
         }
     }
+}
+
+/*
+ * nTrans chain on storage-typed inputs: Y[i][:] = Norm(X[i] + alpha * Norm(H[i] - X[i])), Norm(v) =
+ * v / sqrt(mean(v^2) + eps).  Y is [M][D] doubles.  Returns 0, or -1 on a bad argument.
+ */
+int oracle_ntrans(const void *X, const void *Hh, const void *A, int dtype, double eps,
+                  long M, long D, double *Y)
+{
+    if (!X || !Hh || !A || !Y || M <= 0 || D <= 0)
+        return -1;
+    if (dtype != ORACLE_F16 && dtype != ORACLE_BF16 && dtype != ORACLE_F32)
+        return -1;
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *d = (double *)malloc(sizeof(double) * (size_t)D);
+        double *u = (double *)malloc(sizeof(double) * (size_t)D);
+        if (!d || !u) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(static)
+        for (long i = 0; i < M; ++i) {
+            if (!d || !u)
+                continue;
+            /* inner Norm(h - x) */
+            double s = 0.0;
+            for (long j = 0; j < D; ++j) {
+                d[j] = load_elem(Hh, (size_t)i * D + j, dtype) - load_elem(X, (size_t)i * D + j, dtype);
+                s += d[j] * d[j];
+            }
+            double r1 = sqrt(s / (double)D + eps);
+            /* x + alpha * (that) */
+            double t = 0.0;
+            for (long j = 0; j < D; ++j) {
+                u[j] = load_elem(X, (size_t)i * D + j, dtype) + load_elem(A, (size_t)j, dtype) * (d[j] / r1);
+                t += u[j] * u[j];
+            }
+            /* outer Norm */
+            double r2 = sqrt(t / (double)D + eps);
+            for (long j = 0; j < D; ++j)
+                Y[(size_t)i * D + j] = u[j] / r2;
+        }
+        free(d);
+        free(u);
+    }
+    return failed ? -1 : 0;
 }

@@ -45,6 +45,8 @@ EXPORTS = {
                                        ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int),
                                        ctypes.POINTER(ctypes.c_int)]),
     "rl_autotune_clear": (None, []),
+    "rl_ntrans": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
+                                 ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]),
     "rl_ff_rmsnorm_linear": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                             ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_uint32,
                                             ctypes.c_int, ctypes.c_void_p]),
@@ -199,6 +201,18 @@ def rl_autotune_get(M: int, K: int, N: int, dtype: torch.dtype, gated: bool = Fa
 
 def rl_autotune_clear() -> None:
     lib().rl_autotune_clear()
+
+
+def rl_ntrans(X: torch.Tensor, Hh: torch.Tensor, alpha: torch.Tensor, eps: float,
+              Y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    M, D = X.shape
+    if Hh.shape != (M, D) or alpha.shape != (D,) or Hh.dtype != X.dtype or alpha.dtype != X.dtype:
+        raise ValueError("shape or dtype mismatch")
+    if Y is None:
+        Y = torch.empty_like(X)
+    _check(lib().rl_ntrans(_dev(X, "X"), _dev(Hh, "H"), _dev(alpha, "alpha"), float(eps), _dev(Y, "Y"), M, D,
+                           _DTYPES[X.dtype], _stream(stream)))
+    return Y
 
 
 def rl_ff_rmsnorm_linear(X: torch.Tensor, g: torch.Tensor, W: torch.Tensor, p: int, reordered: bool,

@@ -353,6 +353,19 @@ void rl_autotune_clear(void)
     g_tuned.clear();
 }
 
+rl_status rl_ntrans(const void* X, const void* H, const void* alpha, float eps, void* Y,
+                    int64_t M, int64_t D, rl_dtype dt, void* stream)
+{
+    if (!X || !H || !alpha || !Y) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (rl_status st = check_dims(M, D, 1, dt)) return st;
+    if (!std::isfinite(eps) || eps < 0.f) return fail(RL_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    if (!aligned16(X) || !aligned16(H) || !aligned16(alpha) || !aligned16(Y))
+        return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    hipError_t e = launch_ntrans(X, H, alpha, eps, Y, int(M), int(D), DType(dt), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+    return RL_OK;
+}
+
 rl_status rl_ff_rmsnorm_linear(const void* X, const void* g, const void* W, void* Y,
                                int64_t M, int64_t K, int64_t N, uint32_t p, int reordered, void* stream)
 {

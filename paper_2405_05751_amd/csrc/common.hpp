@@ -70,6 +70,8 @@ inline hipError_t raise_lds_once(LdsOnce& once, std::initializer_list<const void
 
 hipError_t launch_silu_mul(const void* Z, void* Y, int M, int H, DType dt, hipStream_t s);
 
+hipError_t launch_ntrans(const void* X, const void* Hh, const void* A, float eps, void* Y, int M, int D, DType dt,
+                         hipStream_t s);
 hipError_t launch_ff_block(const void* X, const void* g, const void* W, void* Y, int M, int K, int N,
                            uint32_t p, int reordered, hipStream_t s);
 

@@ -13,6 +13,10 @@ Case H3 (placement of eps: added to the mean square, under the root), eps = 5
     row 0: sqrt(4 + 5) = 3            -> [4,4]/3
     row 1: sqrt(2/3 + 5) = sqrt(17/3) -> [0,1]/sqrt(17/3)
     (adding eps to the root instead would give 4/7 for row 0)
+Case N1 (nTrans chain y = Norm(x + a Norm(h - x)), Norm(v) = v / sqrt(mean v^2), eps = 0)
+    x = [[1, 2, 2]], h = [[4, 6, 2]], a = [1, 1/2, 3]
+    h - x = [3, 4, 0], mean square 25/3, Norm = [3, 4, 0] * sqrt(3)/5
+    u = [1 + 3 sqrt(3)/5, 2 + 2 sqrt(3)/5, 2]; y = u / sqrt((u0^2 + u1^2 + u2^2) / 3)
 Case G1 (gate of the GatedMLP block, SiLU(v) = v / (1 + exp(-v)), Y = SiLU(gate) * up), H = 4
     Z = [[0, ln 3, -ln 3, ln 7 | 5, 2, 4, -1]]
     exp(-ln 3) = 1/3 -> SiLU = (3/4) ln 3;  exp(ln 3) = 3 -> SiLU = -(1/4) ln 3;  exp(-ln 7) = 1/7 -> (7/8) ln 7
@@ -34,13 +38,17 @@ g1 = [[Decimal(0), Decimal(3) / 2 * ln3, -ln3, -Decimal(7) / 8 * ln7]]
 silu = lambda v: v / (1 + (-v).exp())
 g2 = [[silu(h1[0][0]) * h1[0][1]], [silu(h1[1][0]) * h1[1][1]]]
 
+nu = [1 + 3 * s3 / 5, 2 + 2 * s3 / 5, Decimal(2)]
+nr = ((nu[0] ** 2 + nu[1] ** 2 + nu[2] ** 2) / 3).sqrt()
+n1 = [[v / nr for v in nu]]
+
 out = os.path.join(os.path.dirname(os.path.abspath(__file__)), "hand_cases.txt")
 with open(out, "w") as f:
     f.write("# Hand-computed cases for Eq. 1 (RMSNorm) followed by the MatMul of Fig. 2a (H1, H3)\n")
-    f.write("# and for the gate of the GatedMLP block (G1, G2).\n")
+    f.write("# for the gate of the GatedMLP block (G1, G2) and for the nTrans chain (N1).\n")
     f.write("# Closed forms are derived in make_hand_cases.py; values to 30 digits.\n")
     f.write("# format: case row col value\n")
-    for name, tab in (("H1", h1), ("H3", h3), ("G1", g1), ("G2", g2)):
+    for name, tab in (("H1", h1), ("H3", h3), ("G1", g1), ("G2", g2), ("N1", n1)):
         for i, row in enumerate(tab):
             for j, v in enumerate(row):
                 f.write(f"{name} {i} {j} {v:.30f}\n")
