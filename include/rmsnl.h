@@ -86,7 +86,7 @@ rl_status matmul(const void* A, const void* W, void* Y,
  *     Y[i][h] = SiLU(Z[i][h]) * Z[i][H + h],   SiLU(v) = v / (1 + exp(-v)),   Y [M][H]
  *
  * Same pointer, alignment, eps and workspace rules as rmsnorm_linear; H % 8 == 0 for the fast
- * variants (the GEMV variant does not implement it).  silu_mul is the separate activation kernel
+ * variants.  silu_mul is the separate activation kernel
  * of the unfused baseline: it reads a materialised Z [M][2H] and writes Y [M][H].
  */
 rl_status rmsnorm_gated_mlp(const void* X, const void* g, const void* W, float eps, void* Y,

@@ -107,7 +107,7 @@ rl_variant choose_auto(const Problem& p)
 {
     if (p.dt == F32) return RL_NAIVE;
     if (p.N % 8 != 0 || p.K % 8 != 0) return RL_NAIVE;
-    if (p.gated) return (p.N % 16 != 0) ? RL_NAIVE : p.M <= 64 ? RL_MFMA_SKINNY : RL_MFMA_TILE;
+    if (p.gated && p.N % 16 != 0) return RL_NAIVE;
     if (p.M <= 4) return RL_GEMV_SPLITK;
     if (p.M <= 64) return RL_MFMA_SKINNY;
     return RL_MFMA_TILE;
@@ -280,7 +280,7 @@ rl_status rl_autotune(const void* X, const void* g, const void* W, float eps, vo
     struct Cand { rl_variant v; int n_tile, k_split; };
     std::vector<Cand> cands;
     if (dt != RL_F32) {
-        if (!gated && M <= 16)
+        if (M <= 16)
             for (int nt : {128, 256, 512})
                 for (int ks : {0, 4, 8, 16, 32}) cands.push_back({RL_GEMV_SPLITK, nt, ks});
         if (M <= 64)

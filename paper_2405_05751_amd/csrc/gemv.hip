@@ -29,6 +29,7 @@ struct GemvArgs {
     int k_slab;      // rows of W per slab (multiple of 8 * number of lane groups)
     int S;           // number of slabs
     int n_tiles;
+    int H;           // gated block: N = 2H, a tile is N_TILE/2 gate columns and the same outputs' up columns; else 0
     float* ws_partial; float* ws_sumsq; unsigned* counter;
     unsigned long long* trace; int trace_groups;
 };
@@ -42,7 +43,7 @@ constexpr int gemv_depth(int MT) { return MT <= 2 ? 4 : 2; }
 // waves per workgroup (8, in half as many workgroups, measured 6 % slower at the decode projection)
 constexpr int gemv_waves(int MT) { return 4; }
 
-template <typename T, int MT, int LPR, bool FUSED>
+template <typename T, int MT, int LPR, bool FUSED, bool GATED>
 __global__ __launch_bounds__(64 * gemv_waves(MT)) void gemv_splitk_kernel(GemvArgs a)
 {
     constexpr int NW = gemv_waves(MT);
@@ -66,7 +67,10 @@ __global__ __launch_bounds__(64 * gemv_waves(MT)) void gemv_splitk_kernel(GemvAr
     const int total = a.n_tiles * a.S;
     if ((total & 7) == 0) b = (b & 7) * (total >> 3) + (b >> 3);
     const int tile = b / a.S, slab = b % a.S;
-    const int n0 = tile * N_TILE;
+    // plain: the tile's W columns start at n0.  Gated: the tile is N_TILE/2 gate columns from n0 and
+    // the up columns of the same outputs, H further on; lane chunk col8 is one or the other.
+    const int n0 = GATED ? tile * (N_TILE / 2) : tile * N_TILE;
+    const int ccol = GATED ? (col8 < LPR / 2 ? n0 + col8 * 8 : a.H + n0 + (col8 - LPR / 2) * 8) : n0 + col8 * 8;
     const int k0 = slab * a.k_slab;
     const int klen = min(a.k_slab, a.K - k0);
     const int R = a.k_slab / NG;             // rows per lane group, a multiple of 8
@@ -83,7 +87,7 @@ __global__ __launch_bounds__(64 * gemv_waves(MT)) void gemv_splitk_kernel(GemvAr
     const __amdgpu_buffer_rsrc_t grs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<u16*>(FUSED ? a.g : a.X), 0, a.K * 2, kRsrcFlags);
     const int wrow = a.N * 2;
-    const int voff0 = (r0 * a.N + n0 + col8 * 8) * 2;
+    const int voff0 = (r0 * a.N + ccol) * 2;
 
     uint4_t w[D][8];
     uint4_t xq[D][XLDS ? 1 : MT], gq[D];
@@ -237,8 +241,9 @@ __global__ __launch_bounds__(64 * gemv_waves(MT)) void gemv_splitk_kernel(GemvAr
     __syncthreads();
 
     trace_stamp(a.trace, a.trace_groups, 3);         // workgroup partial in LDS
-    TailArgs ta{a.Y, a.M, a.N, N_TILE, 0, 0, a.eps, a.inv_K, a.S, a.ws_partial, a.ws_sumsq, a.counter, a.trace, a.trace_groups};
-    splitk_tail<T, MT, N_TILE, FUSED, NW>(ta, red, &s_sumsq[0][0], s_rinv, &s_last, tile, slab, n0);
+    TailArgs ta{a.Y, a.M, a.N, N_TILE, GATED ? N_TILE / 2 : 0, a.H, a.eps, a.inv_K, a.S, a.ws_partial, a.ws_sumsq, a.counter,
+                a.trace, a.trace_groups};
+    splitk_tail<T, MT, N_TILE, FUSED, NW, GATED>(ta, red, &s_sumsq[0][0], s_rinv, &s_last, tile, slab, n0);
 }
 
 // ------------------------------------------------------------------------------------------- host
@@ -249,7 +254,7 @@ static GemvPlan gemv_plan(const Problem& p)
     GemvPlan pl{};
     pl.ok = false;
     if (p.dt == F32) { pl.why = "gemv variant handles 16-bit types only"; return pl; }
-    if (p.gated) { pl.why = "gemv variant does not implement the gated block"; return pl; }
+    if (p.gated && (p.N % 16 != 0 || !p.fused)) { pl.why = "gated block: gemv variant needs H % 8 == 0"; return pl; }
     if (p.M > 16) { pl.why = "gemv variant needs M <= 16"; return pl; }
     if (p.N % 8 != 0 || p.K % 8 != 0) { pl.why = "gemv variant needs N % 8 == 0 and K % 8 == 0"; return pl; }
     if (int64_t(p.M) * p.K * 2 >= (int64_t(1) << 31)) { pl.why = "gemv variant needs M*K < 2^30"; return pl; }
@@ -261,7 +266,7 @@ static GemvPlan gemv_plan(const Problem& p)
     }
     if (pl.MT * n_tile > 4096) n_tile = 4096 / pl.MT;          // cross-wave reduction buffer <= 64 KiB
     pl.LPR = n_tile / 8;
-    pl.n_tiles = (p.N + n_tile - 1) / n_tile;
+    pl.n_tiles = p.gated ? (p.N / 2 + n_tile / 2 - 1) / (n_tile / 2) : (p.N + n_tile - 1) / n_tile;
     const int nw = gemv_waves(pl.MT);
     const int gran = 8 * nw * (64 / pl.LPR);                   // 8 rows per batch and lane group
     int S = p.k_split;
@@ -300,37 +305,40 @@ size_t gemv_workspace_bytes(const Problem& p)
 }
 
 template <typename T, int MT, int LPR>
-static hipError_t gemv_go(const GemvArgs& a, bool fused, const GemvPlan& pl, hipStream_t s)
+static hipError_t gemv_go(const GemvArgs& a, bool fused, bool gated, const GemvPlan& pl, hipStream_t s)
 {
     dim3 grid(pl.n_tiles * pl.S);
     static LdsOnce once;                     // allow more than 64 KiB of dynamic LDS
-    hipError_t e = raise_lds_once(once, {(const void*)gemv_splitk_kernel<T, MT, LPR, true>,
-                                         (const void*)gemv_splitk_kernel<T, MT, LPR, false>}, 96 * 1024);
+    hipError_t e = raise_lds_once(once, {(const void*)gemv_splitk_kernel<T, MT, LPR, true, false>,
+                                         (const void*)gemv_splitk_kernel<T, MT, LPR, false, false>,
+                                         (const void*)gemv_splitk_kernel<T, MT, LPR, true, true>}, 96 * 1024);
     if (e != hipSuccess) return e;
-    if (fused) gemv_splitk_kernel<T, MT, LPR, true><<<grid, 64 * gemv_waves(MT), pl.lds, s>>>(a);
-    else       gemv_splitk_kernel<T, MT, LPR, false><<<grid, 64 * gemv_waves(MT), pl.lds, s>>>(a);
+    const int nt = 64 * gemv_waves(MT);
+    if (gated)      gemv_splitk_kernel<T, MT, LPR, true, true><<<grid, nt, pl.lds, s>>>(a);
+    else if (fused) gemv_splitk_kernel<T, MT, LPR, true, false><<<grid, nt, pl.lds, s>>>(a);
+    else            gemv_splitk_kernel<T, MT, LPR, false, false><<<grid, nt, pl.lds, s>>>(a);
     return hipGetLastError();
 }
 
 template <typename T, int MT>
-static hipError_t gemv_lpr(const GemvArgs& a, bool fused, const GemvPlan& pl, hipStream_t s)
+static hipError_t gemv_lpr(const GemvArgs& a, bool fused, bool gated, const GemvPlan& pl, hipStream_t s)
 {
-    if constexpr (MT * 512 <= 4096) { if (pl.LPR == 64) return gemv_go<T, MT, 64>(a, fused, pl, s); }
-    if constexpr (MT * 256 <= 4096) { if (pl.LPR == 32) return gemv_go<T, MT, 32>(a, fused, pl, s); }
-    if (pl.LPR == 16) return gemv_go<T, MT, 16>(a, fused, pl, s);
-    if (pl.LPR == 8) return gemv_go<T, MT, 8>(a, fused, pl, s);
+    if constexpr (MT * 512 <= 4096) { if (pl.LPR == 64) return gemv_go<T, MT, 64>(a, fused, gated, pl, s); }
+    if constexpr (MT * 256 <= 4096) { if (pl.LPR == 32) return gemv_go<T, MT, 32>(a, fused, gated, pl, s); }
+    if (pl.LPR == 16) return gemv_go<T, MT, 16>(a, fused, gated, pl, s);
+    if (pl.LPR == 8) return gemv_go<T, MT, 8>(a, fused, gated, pl, s);
     return hipErrorInvalidValue;
 }
 
 template <typename T>
-static hipError_t gemv_mt(const GemvArgs& a, bool fused, const GemvPlan& pl, hipStream_t s)
+static hipError_t gemv_mt(const GemvArgs& a, bool fused, bool gated, const GemvPlan& pl, hipStream_t s)
 {
     switch (pl.MT) {
-    case 1:  return gemv_lpr<T, 1>(a, fused, pl, s);
-    case 2:  return gemv_lpr<T, 2>(a, fused, pl, s);
-    case 4:  return gemv_lpr<T, 4>(a, fused, pl, s);
-    case 8:  return gemv_lpr<T, 8>(a, fused, pl, s);
-    default: return gemv_lpr<T, 16>(a, fused, pl, s);
+    case 1:  return gemv_lpr<T, 1>(a, fused, gated, pl, s);
+    case 2:  return gemv_lpr<T, 2>(a, fused, gated, pl, s);
+    case 4:  return gemv_lpr<T, 4>(a, fused, gated, pl, s);
+    case 8:  return gemv_lpr<T, 8>(a, fused, gated, pl, s);
+    default: return gemv_lpr<T, 16>(a, fused, gated, pl, s);
     }
 }
 
@@ -346,9 +354,11 @@ hipError_t launch_gemv(const Problem& p, hipStream_t s, const char** why)
     a.X = (const u16*)p.X; a.g = (const u16*)p.g; a.W = (const uint4_t*)p.W; a.Y = (u16*)p.Y;
     a.M = p.M; a.K = p.K; a.N = p.N; a.eps = p.eps; a.inv_K = 1.0f / float(p.K);
     a.k_slab = pl.k_slab; a.S = pl.S; a.n_tiles = pl.n_tiles;
+    a.H = p.gated ? p.N / 2 : 0;
     a.ws_partial = p.ws_partial; a.ws_sumsq = p.ws_sumsq; a.counter = p.ws_counter;
     a.trace = p.trace; a.trace_groups = p.trace_groups;
-    return p.dt == F16 ? gemv_mt<Fp16>(a, p.fused != 0, pl, s) : gemv_mt<Bf16>(a, p.fused != 0, pl, s);
+    const bool fused = p.fused != 0, gated = p.gated != 0;
+    return p.dt == F16 ? gemv_mt<Fp16>(a, fused, gated, pl, s) : gemv_mt<Bf16>(a, fused, gated, pl, s);
 }
 
 }  // namespace rmsnl

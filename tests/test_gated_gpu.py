@@ -60,11 +60,13 @@ SHAPES = [
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
-@pytest.mark.parametrize("variant", ["auto", "skinny", "tile", "naive"])
+@pytest.mark.parametrize("variant", ["auto", "gemv", "skinny", "tile", "naive"])
 @pytest.mark.parametrize("M,K,H", SHAPES)
 def test_gated_shapes(rl, M, K, H, variant, dtype):
     if variant == "skinny" and M > 64:
         pytest.skip("skinny needs M <= 64")
+    if variant == "gemv" and M > 16:
+        pytest.skip("gemv needs M <= 16")
     w = workloads.make(M, K, 2 * H, dtype, 1e-5, 7000 + M * 3 + K + H, outlier_frac=0.1 if M > 8 else 0.0)
     Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
     Y, used = _run(rl, w, variant)
@@ -154,10 +156,20 @@ def test_gated_zero_row_and_canaries(rl):
         compare_gated(to_host_f64(Y, "bf16"), Z, "bf16", f"gated zero row/{variant}")
 
 
-def test_gemv_refuses_the_gated_block(rl):
-    w = workloads.make(1, 256, 2 * 128, "bf16", 1e-5, 7600)
-    with pytest.raises(rl.RmsnlError):
-        _run(rl, w, "gemv")
+@pytest.mark.parametrize("n_tile,k_split", [(128, 1), (128, 5), (256, 2), (256, 16), (512, 4)])
+def test_gated_gemv_launch_shapes(rl, n_tile, k_split):
+    w = workloads.make(3, 2056, 2 * 776, "bf16", 1e-5, 7600 + n_tile + k_split)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used = _run(rl, w, "gemv", tuning=(n_tile, k_split))
+    assert used == "gemv"
+    compare_gated(Y, Z, "bf16", f"gated gemv n_tile={n_tile} k_split={k_split}")
+
+
+def test_fast_variants_refuse_odd_halves(rl):
+    w = workloads.make(1, 256, 2 * 12, "bf16", 1e-5, 7601)           # H % 8 != 0
+    for variant in ("gemv", "skinny", "tile"):
+        with pytest.raises(rl.RmsnlError):
+            _run(rl, w, variant)
 
 
 # ------------------------------------------------------------------ the launch-shape tuner
