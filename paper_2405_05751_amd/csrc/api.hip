@@ -286,7 +286,8 @@ rl_status rl_autotune(const void* X, const void* g, const void* W, float eps, vo
         if (M <= 64)
             for (int ks : {1, 2, 4, 8, 16}) cands.push_back({RL_MFMA_SKINNY, 0, ks});
         if (M > 16)
-            for (int nw : {4, 8}) cands.push_back({RL_MFMA_TILE, 0, nw});
+            for (int shape : {256, 512})
+                for (int nw : {4, 8}) cands.push_back({RL_MFMA_TILE, shape, nw});
     }
     cands.push_back({RL_NAIVE, 0, 0});
 

@@ -1,18 +1,20 @@
 // Matrix-core variant of the fused RMSNorm + MatMul for large M (prefill): bound by the dense
 // contraction, so the design is a 256x256 output tile per workgroup on v_mfma_f32_32x32x16.
 //
-//   * 4 waves in a 2x2 arrangement, each owning 128x128 of the tile = 4x4 MFMA tiles, 256 fp32
-//     accumulators per lane (the B accumulator of the paper's fused kernel);
+//   * 8 waves, two per SIMD, in a 2x4 arrangement, each owning 128x64 of the tile = 4x2 MFMA tiles,
+//     128 fp32 accumulators per lane (the B accumulator of the paper's fused kernel); 4 waves of
+//     128x128 and a 128x512 tile are selectable and measured slower;
 //   * K advances in steps of 64 through two LDS buffers.  X goes global -> registers -> LDS, and on
 //     the way it is multiplied by g, rounded once to the 16-bit type (X-hat), and its raw squares
 //     are added to a per-row running sum (the A accumulator): the two accumulations share the K
 //     loop and the work is done once per workgroup, at staging, not per wave on fragments;
-//   * W goes global -> registers -> LDS as it lies in memory ([k][n], n contiguous).  The matrix
-//     instruction wants 8 consecutive k of one column per lane, so the B fragments are fetched with
-//     the transposing LDS read (ds_read_b64_tr_b16): within 16 lanes, lane j supplies the address
-//     of 4 columns of row j/4 and receives the 4 rows of column j;
-//   * LDS rows are padded (X-hat rows to 144 B, W rows to 576 B) so that the 16-byte fragment reads
-//     and the transposing reads fall on distinct banks;
+//   * W goes straight from global memory into LDS as it lies in memory ([k][n], n contiguous).  The
+//     matrix instruction wants 8 consecutive k of one column per lane, so the B fragments are
+//     fetched with the transposing LDS read (ds_read_b64_tr_b16): within 16 lanes, lane j supplies
+//     the address of 4 columns of row j/4 and receives the 4 rows of column j;
+//   * LDS rows are unpadded and their 16-byte chunks swizzled (X-hat: chunk c of row r at
+//     c ^ ((r/2) & 7); W: at c ^ 4 (r & 3)), so that the 16-byte fragment reads and the transposing
+//     reads fall on distinct banks and a direct load can fill whole rows;
 //   * epilogue: rinv_i = 1/sqrt(A_i/K + eps) per row, Y = B * rinv in fp32, one rounding, store.
 //
 // Out-of-range rows of X and W read as zero through buffer resources; ragged M, N and K % 64 are
@@ -30,12 +32,19 @@ struct TileArgs {
     int H;           // gated block: N = 2H, a tile is 128 gate columns and the up columns of the same outputs; else 0
 };
 
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int LDA = BK + 8;          // elements per X-hat row in LDS (144 bytes)
+// Tile shapes: 0 = 256 rows x 256 columns (2 x NW/2 waves), 1 = 128 rows x 512 columns (1 x NW waves).
+// The second halves the X-hat staging work per matrix instruction (an X tile then meets 512
+// columns) for a quarter more traffic out of L2; at 8192^3 it measured 1-2 % slower with the
+// operands in the last-level cache and 5 % slower with them in HBM, so the first is the default.
+constexpr int BK = 64;
+constexpr int tile_bm(int shape) { return shape ? 128 : 256; }
+constexpr int tile_bn(int shape) { return shape ? 512 : 256; }
+constexpr int LDA = BK;              // X-hat rows in LDS are unpadded (128 bytes), chunks swizzled
 constexpr int kTileOut = 0x7ffffff0;
 constexpr int kTileFlags = 0x00020000;
 constexpr int kTileDefaultWaves = 8;
-constexpr size_t kTileLds = size_t(2) * (BM * LDA + BK * BN) * 2 + BM * 4 * 2;
+constexpr size_t tile_lds(int shape) { return size_t(2) * (tile_bm(shape) * LDA + BK * tile_bn(shape)) * 2; }
+constexpr int kTileDefaultShape = 0;
 
 template <typename T> struct Mfma32;
 template <> struct Mfma32<Bf16> {
@@ -79,25 +88,28 @@ template <> struct SqPair<Fp16> {
 // s_waitcnt that waits only for the vector-memory counter to drop to n (n <= 63)
 #define RL_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
-// NW waves per workgroup: 4 (2x2, 128x128 per wave, one wave per SIMD) or 8 (2x4, 128x64 per
-// wave, two waves per SIMD that cover each other's stalls).
+// NW waves per workgroup: 4 (128x128 per wave, one wave per SIMD) or 8 (128x64 per wave, two waves
+// per SIMD that cover each other's stalls); SHAPE: the tile shape, see tile_bm / tile_bn.
 //
 // GATED (the GatedMLP block on top): the tile's 256 columns are 128 outputs' gate and up columns,
 // laid out so that MFMA tiles j and j + TN/2 of a wave are gate and up of the same 32 outputs; the
 // epilogue then forms SiLU(gate) * up in registers.  Only the column a lane fetches changes.
-template <typename T, bool FUSED, int NW, bool GATED>
+template <typename T, bool FUSED, int NW, bool GATED, int SHAPE>
 __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
 {
+    constexpr int BM = tile_bm(SHAPE), BN = tile_bn(SHAPE);
     constexpr int NT = 64 * NW;                  // threads
-    constexpr int WN = NW / 2;                   // waves along N
-    constexpr int TM = 4, TN = BN / WN / 32;     // MFMA tiles per wave along M and N
-    constexpr int NJ = 2048 / NT;                // 16-byte chunks of X a thread stages per K tile
+    constexpr int WM = SHAPE ? 1 : 2;            // waves along M
+    constexpr int WN = NW / WM;                  // waves along N
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // MFMA tiles per wave along M (4) and N
+    constexpr int NJ = BM * 8 / NT;              // 16-byte chunks of X a thread stages per K tile
     constexpr int XR = NT / 8;                   // row stride between a thread's X chunks
-    constexpr int NP = 32 / NW;                  // direct-to-LDS loads of W per wave and K tile (2 rows each)
+    constexpr int RPL = 512 / BN;                // rows of the W tile in one 1 KiB direct load (2 or 1)
+    constexpr int NP = BK / RPL / NW;            // direct-to-LDS loads of W per wave and K tile
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    u16* As = (u16*)lds_raw;                             // [2][BM][LDA]
+    u16* As = (u16*)lds_raw;                             // [2][BM][LDA], chunks swizzled
     u16* Bs = As + 2 * BM * LDA;                         // [2][BK][BN], chunks swizzled
-    float* s_ss = (float*)(Bs + 2 * BK * BN);            // [BM] sums of squares
+    float* s_ss = (float*)lds_raw;                       // [BM] sums of squares: over As once the K loop is done
     float* s_rinv = s_ss + BM;                           // [BM]
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -137,13 +149,13 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
 #pragma unroll
     for (int j = 0; j < NJ; ++j) xoff[j] = ((ar + XR * j) * a.K + ac) * 2;
 
-    // ---- W role: load p of this wave brings rows 2(wave + NW p), +1 of the K tile (two rows of
-    // 256 columns = 1 KiB) straight into LDS.  A direct load writes lane l's 16 bytes at byte 16 l
-    // of that KiB, so lane l fetches the chunk that belongs there: row rsel = l / 32, and, with the
-    // swizzle "chunk c of row r sits at chunk c ^ 4 (r & 3)", chunk (l % 32) ^ 4 (r & 3).
-    // (2 NW p is a multiple of 4, so r & 3 does not depend on p.)
-    const int wrow = 2 * wave + (lane >> 5);
-    const int wchunk = (lane & 31) ^ (4 * (wrow & 3));
+    // ---- W role: load p of this wave brings RPL rows of the K tile, from row RPL (wave + NW p),
+    // = 1 KiB, straight into LDS.  A direct load writes lane l's 16 bytes at byte 16 l of that KiB,
+    // so lane l fetches the chunk that belongs there: row l / (64 / RPL), and, with the swizzle
+    // "chunk c of row r sits at chunk c ^ 4 (r & 3)", chunk (l % (64 / RPL)) ^ 4 (r & 3).
+    // (RPL NW p is a multiple of 4, so r & 3 does not depend on p.)
+    const int wrow = RPL * wave + lane / (64 / RPL);
+    const int wchunk = (lane % (64 / RPL)) ^ (4 * (wrow & 3));
     int wcol = n0 + 8 * wchunk;
     bool wcol_ok = wcol < a.N;
     if (GATED) {
@@ -176,10 +188,10 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
     // waits for these loads are therefore placed by hand (RL_WAIT_VM before the barriers).
     uint4_t wdesc = {uint32_t(uintptr_t(a.W)), uint32_t(uintptr_t(a.W) >> 32), uint32_t(a.K * a.N * 2),
                            uint32_t(kTileFlags)};
-    uint32_t bs_base = uint32_t(uintptr_t(Bs)) + uint32_t(wave) * 2 * BN * 2;   // LDS byte address of this wave's first row pair
+    uint32_t bs_base = uint32_t(uintptr_t(Bs)) + uint32_t(wave) * 1024;         // LDS byte address of this wave's first KiB
     auto load_w = [&](auto checked, int buf, int k0, int p) {
-        const uint32_t dst = bs_base + uint32_t(buf * BK * BN * 2 + NW * p * 2 * BN * 2);
-        const unsigned rowoff = unsigned(k0 + 2 * NW * p) * unsigned(a.N) * 2u;
+        const uint32_t dst = bs_base + uint32_t(buf * BK * BN * 2 + NW * p * 1024);
+        const unsigned rowoff = unsigned(k0 + RPL * NW * p) * unsigned(a.N) * 2u;
         int v = woff, so = int(rowoff);
         if constexpr (decltype(checked)::value) {
             v = woff == kTileOut ? kTileOut : int(unsigned(woff) + rowoff);
@@ -215,7 +227,8 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
                 o[e] = Elem<T>::pack(Elem<T>::lo(o[e]) * gf[2 * e], Elem<T>::hi(o[e]) * gf[2 * e + 1]);
             }
         }
-        *(uint4_t*)(As + buf * BM * LDA + (ar + XR * j) * LDA + ac) = o;
+        // chunk c of row r sits at chunk c ^ ((r / 2) & 7) of the row's 128 bytes ((XR j) / 2 is a multiple of 8)
+        *(uint4_t*)(As + buf * BM * LDA + (ar + XR * j) * LDA + (ac ^ (8 * ((ar >> 1) & 7)))) = o;
     };
 
     float16_t acc[TM][TN];
@@ -226,10 +239,14 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // fragment addresses.  A: row wm*128 + i*32 + lane%32, k chunk 8*(lane/32) of the 16-deep step.
-    // B: 16-lane block blk, lane jj in it: row 8*(blk/2) + jj/4 (+4 for the second read), columns
-    // 16*(blk%2) + 4*(jj%4) of MFMA tile i, at the swizzled place of that row.
-    const int a_off = (wm * 128 + (lane & 31)) * LDA + 8 * (lane >> 5);
+    // fragment addresses.  A: row wm*(BM/WM) + i*32 + lane%32, k chunk 2 ks + lane/32 of the K tile, at
+    // its swizzled place (32 i rows further on the swizzle is the same).  B: 16-lane block blk, lane
+    // jj in it: row 8*(blk/2) + jj/4 (+4 for the second read), columns 16*(blk%2) + 4*(jj%4) of MFMA
+    // tile i, at the swizzled place of that row.
+    const int a_row = wm * (BM / WM) + (lane & 31);
+    int a_off[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) a_off[ks] = a_row * LDA + 8 * ((2 * ks + (lane >> 5)) ^ ((a_row >> 1) & 7));
     const int blk = lane >> 4, jj = lane & 15;
     const int b_row = 8 * (blk >> 1) + (jj >> 2);
     int b_off[TN];
@@ -241,7 +258,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
     // the next step land in the other set.
     uint4_t af[2][TM], bf[2][TN];
     auto read_frag = [&](int set, int buf, int ks, int i) {      // A fragment i and B fragment i of step ks
-        const u16* Ab = As + buf * BM * LDA + a_off + ks * 16;
+        const u16* Ab = As + buf * BM * LDA + a_off[ks];
         const u16* Bb = Bs + buf * BK * BN + (ks * 16) * BN;
         af[set][i] = *(const uint4_t*)(Ab + i * 32 * LDA);
         if (i < TN) {
@@ -332,8 +349,10 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
 #undef RL_SB
     RL_WAIT_VM(0);                                       // nothing may still be writing LDS past this point
 
-    // ---- A_i: the 8 threads that share a row (tid & 7) add their shares
+    // ---- A_i: the 8 threads that share a row (tid & 7) add their shares (s_ss lies over the X-hat
+    // buffers, which nobody needs any more once every wave has left the K loop)
     if (FUSED) {
+        __syncthreads();
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
             float v = ssq[j];
@@ -353,7 +372,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int row = wm * 128 + i * 32 + 8 * (r >> 2) + rowq + (r & 3);
+            const int row = wm * (BM / WM) + i * 32 + 8 * (r >> 2) + rowq + (r & 3);
             const float ri = FUSED ? s_rinv[row] : 1.f;
             if (m0 + row < a.M) {
                 if (GATED) {
@@ -375,20 +394,21 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
 }
 
 // ------------------------------------------------------------------------------------------- host
-template <typename T, bool FUSED, int NW, bool GATED>
+template <typename T, bool FUSED, int NW, bool GATED, int SHAPE>
 static hipError_t tile_go(const TileArgs& a, dim3 grid, hipStream_t s)
 {
     static LdsOnce once;
-    hipError_t e = raise_lds_once(once, {(const void*)tile_kernel<T, FUSED, NW, GATED>}, int(kTileLds));
+    hipError_t e = raise_lds_once(once, {(const void*)tile_kernel<T, FUSED, NW, GATED, SHAPE>}, int(tile_lds(SHAPE)));
     if (e != hipSuccess) return e;
-    tile_kernel<T, FUSED, NW, GATED><<<grid, 64 * NW, kTileLds, s>>>(a);
+    tile_kernel<T, FUSED, NW, GATED, SHAPE><<<grid, 64 * NW, tile_lds(SHAPE), s>>>(a);
     return hipGetLastError();
 }
 
 template <typename T, bool FUSED, bool GATED>
-static hipError_t tile_nw(const TileArgs& a, dim3 grid, int nw, hipStream_t s)
+static hipError_t tile_nw(const TileArgs& a, dim3 grid, int nw, int shape, hipStream_t s)
 {
-    return nw == 8 ? tile_go<T, FUSED, 8, GATED>(a, grid, s) : tile_go<T, FUSED, 4, GATED>(a, grid, s);
+    if (shape) return nw == 8 ? tile_go<T, FUSED, 8, GATED, 1>(a, grid, s) : tile_go<T, FUSED, 4, GATED, 1>(a, grid, s);
+    return nw == 8 ? tile_go<T, FUSED, 8, GATED, 0>(a, grid, s) : tile_go<T, FUSED, 4, GATED, 0>(a, grid, s);
 }
 
 hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
@@ -398,7 +418,7 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
         if (why) *why = "tile variant needs N % 8 == 0 and K % 8 == 0";
         return hipErrorInvalidValue;
     }
-    if (int64_t(p.K) * p.N * 2 >= (int64_t(1) << 31) || int64_t(BM) * p.K * 2 >= (int64_t(1) << 31)) {
+    if (int64_t(p.K) * p.N * 2 >= (int64_t(1) << 31) || int64_t(256) * p.K * 2 >= (int64_t(1) << 31)) {
         if (why) *why = "tile variant needs K*N < 2^30";
         return hipErrorInvalidValue;
     }
@@ -408,6 +428,13 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
         return hipErrorInvalidValue;
     }
     const int nw = p.k_split ? p.k_split : kTileDefaultWaves;
+    // tuning: n_tile carries the tile shape for this variant (0 = default, 256 = 256x256, 512 = 128x512)
+    if (p.n_tile != 0 && p.n_tile != 256 && p.n_tile != 512) {
+        if (why) *why = "tile variant: n_tile selects 256 (256x256 tiles) or 512 (128x512 tiles)";
+        return hipErrorInvalidValue;
+    }
+    const int shape = p.n_tile ? (p.n_tile == 512) : kTileDefaultShape;
+    const int BM = tile_bm(shape), BN = tile_bn(shape);
     TileArgs a;
     a.X = (const u16*)p.X; a.g = (const u16*)p.g; a.W = (const u16*)p.W; a.Y = (u16*)p.Y;
     a.M = p.M; a.K = p.K; a.N = p.N; a.eps = p.eps; a.inv_K = 1.0f / float(p.K);
@@ -425,10 +452,10 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
     dim3 grid(a.tiles_m * a.tiles_n);
     const bool fused = p.fused != 0;
     if (p.gated)
-        return p.dt == F16 ? tile_nw<Fp16, true, true>(a, grid, nw, s) : tile_nw<Bf16, true, true>(a, grid, nw, s);
+        return p.dt == F16 ? tile_nw<Fp16, true, true>(a, grid, nw, shape, s) : tile_nw<Bf16, true, true>(a, grid, nw, shape, s);
     if (p.dt == F16)
-        return fused ? tile_nw<Fp16, true, false>(a, grid, nw, s) : tile_nw<Fp16, false, false>(a, grid, nw, s);
-    return fused ? tile_nw<Bf16, true, false>(a, grid, nw, s) : tile_nw<Bf16, false, false>(a, grid, nw, s);
+        return fused ? tile_nw<Fp16, true, false>(a, grid, nw, shape, s) : tile_nw<Fp16, false, false>(a, grid, nw, shape, s);
+    return fused ? tile_nw<Bf16, true, false>(a, grid, nw, shape, s) : tile_nw<Bf16, false, false>(a, grid, nw, shape, s);
 }
 
 }  // namespace rmsnl

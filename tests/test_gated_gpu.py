@@ -94,6 +94,15 @@ def test_gated_any_shape_falls_back(rl, M, K, H, dtype):
     compare_gated(Y, Z, dtype, f"gated odd {M}x{K}x2*{H} {dtype}->{used}")
 
 
+@pytest.mark.parametrize("n_tile,waves", [(256, 4), (512, 4), (512, 8)])
+def test_gated_tile_launch_shapes(rl, n_tile, waves):
+    w = workloads.make(300, 776, 2 * 648, "bf16", 1e-5, 7250 + n_tile + waves)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used = _run(rl, w, "tile", tuning=(n_tile, waves))
+    assert used == "tile"
+    compare_gated(Y, Z, "bf16", f"gated tile shape={n_tile} waves={waves}")
+
+
 def test_gated_prefill_sized_tile(rl):
     """A tile-kernel shape with several tiles each way and ragged edges, on sampled rows."""
     w = workloads.make(1000, 2048, 2 * 1160, "bf16", 1e-5, 7300)

@@ -150,6 +150,17 @@ def test_gemv_launch_shapes(rl, n_tile, k_split):
     compare(Y, Z, w.dtype, f"gemv n_tile={n_tile} k_split={k_split}")
 
 
+@pytest.mark.parametrize("n_tile,waves", [(256, 4), (256, 8), (512, 4), (512, 8)])
+@pytest.mark.parametrize("M,K,N", [(130, 1544, 520), (257, 264, 264), (300, 776, 1288), (512, 512, 1024)])
+def test_tile_launch_shapes(rl, M, K, N, n_tile, waves):
+    """Both tile shapes (256x256 and 128x512) and both wave counts of the tile variant."""
+    w = workloads.make(M, K, N, "bf16", 1e-5, 3500 + M + K + N, outlier_frac=0.05)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used = _run(rl, w, "tile", tuning=(n_tile, waves))
+    assert used == "tile"
+    compare(Y, Z, w.dtype, f"tile {M}x{K}x{N} shape={n_tile} waves={waves}")
+
+
 # ------------------------------------------------------------------ fp32 path
 @pytest.mark.parametrize("M,K,N", [(8, 512, 512), (3, 4096, 1000), (16, 1024, 4096)])
 def test_fp32_path(rl, M, K, N):
