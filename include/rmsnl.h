@@ -104,8 +104,12 @@ rl_variant rl_get_variant(void);
 rl_variant rl_last_variant(void);
 
 /*
- * Launch-shape overrides for tuning sweeps (process-wide, 0 = automatic):
- *   n_tile  columns of W per workgroup, k_split  number of K slabs (split-K factor).
+ * Launch-shape overrides for tuning sweeps (process-wide, 0 = automatic; they apply to a forced
+ * variant only):
+ *   n_tile  columns of W per workgroup (GEMV: 64, 128, 256, 512; skinny: a multiple of 8 up to 128;
+ *           tile: 256 = 256x256 tiles, 512 = 128x512 tiles),
+ *   k_split number of K slabs (split-K factor) of the GEMV and skinny variants; for the tile variant
+ *           the waves per workgroup (4 or 8).
  * Values a variant cannot honour give RL_ERR_UNSUPPORTED at the next call.
  */
 rl_status rl_set_tuning(int n_tile, int k_split);
