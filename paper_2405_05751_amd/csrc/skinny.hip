@@ -64,7 +64,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
     constexpr int MT = 16 * MB;
     constexpr int N_TILE = kSkinnyTile;
     constexpr int D = skinny_depth(MB);
-    extern __shared__ float smem[];          // red [NW][MT][N_TILE]
+    extern __shared__ __align__(16) float smem[];   // red [NW][MT][N_TILE]
     __shared__ float s_sumsq[NW][MT];
     __shared__ float s_rinv[MT];
     __shared__ int s_last;
@@ -85,43 +85,71 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
     const bool live = i * 8 < a.n_tile;      // narrower tiles leave the last column chunks idle
     const int k0 = slab * a.k_slab;
     const int klen = min(a.k_slab, a.K - k0);
-    const int nSteps = a.k_slab / (32 * NW); // 32-row steps per wave, an even number (uniform; rows past klen read zero)
+    const int nPairs = a.k_slab / (64 * NW); // 64-row runs per wave (uniform; rows past klen read zero)
 
     const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint4_t*>(a.W + size_t(k0) * (a.N >> 3)), 0, klen * a.N * 2, kSkFlags);
     const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<u16*>(a.X), 0, a.M * a.K * 2, kSkFlags);           // rows >= M read as zero
+        const_cast<u16*>(a.X), 0, a.M * a.K * 2, kSkFlags);
     const __amdgpu_buffer_rsrc_t grs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<u16*>(FUSED ? a.g : a.X), 0, a.K * 2, kSkFlags);
     const int wrow = a.N * 2;
-    // Steps come in pairs: steps 2t and 2t+1 of this wave cover the 64 slab rows from
-    // (NW t + wave)*64; lane (i, q) owns rows 16q + 8h .. +7 of them in step 2t + h.  The four k
-    // groups of a wave then read, over the two steps, whole 128-byte lines of every X row, and no
-    // other wave touches those lines.
+    // Run t of this wave is the 64 slab rows from (NW t + wave)*64, taken as two 32-row steps:
+    // lane (i, q) owns rows 16q + 8h .. +7 of the run in step h.
     // idle lanes start at 2^31: their offsets stay beyond every resource (sizes are below 2^31) and read zero
     const unsigned woff0 = live ? unsigned(((wave * 64 + q * 16) * a.N + ccol) * 2) : 0x80000000u;
-    const int wpair = 64 * NW * a.N * 2;     // bytes of W between two pairs of steps
-    const int xrow0 = i * a.K * 2;           // row i of X (row 16*mb + i adds mb * 16 rows)
+    const int wpair = 64 * NW * a.N * 2;     // bytes of W between two runs
 
-    uint4_t w[D][8];
-    uint4_t xq[D][MB], gq[D];
-    auto issue = [&](int s, int d) {
+    // X is fetched as whole 128-byte lines, each exactly once: load j of a run has lane (r8, c8)
+    // take 16 bytes c8 of row 8j + r8 (64 k = 128 bytes per row), the wave passes the run through
+    // its own corner of LDS, and lane (i, q) reads back chunk 2q + h of row 16mb + i, which is the
+    // A operand layout.  (Loading in operand layout touches every line in both steps, half of it
+    // each time, and by the second touch the line has left the vector cache again.)  The 16-byte
+    // chunk index is XORed with (row / 2) % 8 so that writes and reads are free of bank conflicts.
+    // g rides along as one more row.
+    const int r8 = lane >> 3, c8 = lane & 7;
+    char* stage = reinterpret_cast<char*>(smem) + wave * (MT * N_TILE * 4);   // inside this wave's part of red
+    const int st_w0 = r8 * 128 + ((c8 ^ (r8 >> 1)) << 4);            // even j (+ 1024 j)
+    const int st_w1 = r8 * 128 + ((c8 ^ (r8 >> 1) ^ 4) << 4);        // odd j
+    const int st_r0 = i * 128 + (((2 * q) ^ (i >> 1)) << 4);         // step 0 (+ 2048 mb); step 1 is ^ 16
+    const int st_g = MT * 128;
+
+    uint4_t w[D][8];                         // D steps of W in flight
+    uint4_t xr[2 * MB], gr;                  // the next run of X (and g), as lines
+    // load j of a run takes row 8j + r8 of X, if there is one (8 j < rlim)
+    const int rlim = a.M - r8;
+    const int xlane = r8 * a.K * 2;          // used only where r8 < M
+    auto issue_x = [&](int t) {
+        const int kr = (NW * t + wave) * 64 + c8 * 8;               // slab-relative k of this lane's chunk
+        const int koff = (k0 + kr) * 2;
+        const int rl = kr < klen ? rlim : 0;                        // no k, no rows
+        if (FUSED) gr = __builtin_amdgcn_raw_buffer_load_b128(grs, (r8 == 0 && kr < klen) ? koff : kSkOut, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 2 * MB; ++j)
+            xr[j] = __builtin_amdgcn_raw_buffer_load_b128(
+                xrs, 8 * j < rl ? koff + xlane + 8 * j * a.K * 2 : kSkOut, 0, 0);
+    };
+    auto issue_w = [&](int s, int d) {
         const int t = s >> 1, h = s & 1;
 #pragma unroll
         for (int j = 0; j < 8; ++j)
-            w[d][j] = __builtin_amdgcn_raw_buffer_load_b128(
-                wrs, int(woff0 + unsigned(t * wpair + (8 * h + j) * wrow)), 0, kSkAux);
-        const int kr = (NW * t + wave) * 64 + q * 16 + h * 8;     // slab-relative k of this lane's chunk
-        const int koff = kr < klen ? (k0 + kr) * 2 : kSkOut;
-        if (FUSED) gq[d] = __builtin_amdgcn_raw_buffer_load_b128(grs, koff, 0, 0);
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-            xq[d][mb] = __builtin_amdgcn_raw_buffer_load_b128(
-                xrs, kr < klen ? koff + xrow0 + mb * 16 * a.K * 2 : kSkOut, 0, 0);
+            w[d][j] = __builtin_amdgcn_raw_buffer_load_b128(     // (the uniform part is kept out of the lane's registers)
+                wrs, int(woff0 + unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(t) * unsigned(wpair) + unsigned((8 * h + j) * wrow))))), 0, kSkAux);
     };
+    // Every load below is issued whether or not its step exists (a step past the slab reads zeros
+    // through the range check): the compiler then knows exactly how many loads are younger than
+    // the one it waits for, and the waits leave the rest of the ring in flight.
+    __builtin_amdgcn_sched_barrier(0);       // (the order of issue is the order the waits count in)
+    issue_w(0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    issue_x(0);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int d = 0; d < D; ++d)
-        if (d < nSteps) issue(d, d);
+    for (int d = 1; d < D; ++d) {
+        issue_w(d, d);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    asm volatile("" ::: "memory");
     trace_stamp(a.trace, a.trace_groups, 1);
 
     float4_t acc[MB][8];
@@ -133,21 +161,23 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) ss[mb] = 0.f;
 
-    auto consume = [&](int d) {
+    auto consume = [&](int d, int h) {
         // A operands: X-hat = X (.) g rounded once to the storage type; squares of the raw X
-        uint4_t aop[MB];
+        uint4_t aop[MB], gq;
+        if (FUSED) gq = *reinterpret_cast<const uint4_t*>(stage + st_g + ((2 * q + h) << 4));
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
+            const uint4_t xq = *reinterpret_cast<const uint4_t*>(stage + ((st_r0 ^ (h << 4)) + 2048 * mb));
             if (FUSED) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float x0 = Elem<T>::lo(xq[d][mb][e]), x1 = Elem<T>::hi(xq[d][mb][e]);
+                    const float x0 = Elem<T>::lo(xq[e]), x1 = Elem<T>::hi(xq[e]);
                     ss[mb] = __fmaf_rn(x0, x0, ss[mb]);
                     ss[mb] = __fmaf_rn(x1, x1, ss[mb]);
-                    aop[mb][e] = Elem<T>::pack(x0 * Elem<T>::lo(gq[d][e]), x1 * Elem<T>::hi(gq[d][e]));
+                    aop[mb][e] = Elem<T>::pack(x0 * Elem<T>::lo(gq[e]), x1 * Elem<T>::hi(gq[e]));
                 }
             } else {
-                aop[mb] = xq[d][mb];
+                aop[mb] = xq;
             }
         }
         // B operands: column c of the lane's 8x8 block, rows paired (2t, 2t+1)
@@ -163,13 +193,34 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
         }
     };
 
-    for (int s0 = 0; s0 < nSteps; s0 += D) {
+    constexpr int PU = (D % 2 == 0) ? D / 2 : D;    // runs per trip: ring slots repeat every 2 PU steps
+    for (int t0 = 0; t0 < nPairs; t0 += PU) {
 #pragma unroll
-        for (int d = 0; d < D; ++d) {
-            const int s = s0 + d;
-            if (s < nSteps) {                // uniform over the workgroup
-                consume(d);
-                if (s + D < nSteps) issue(s + D, d);
+        for (int p = 0; p < PU; ++p) {
+            const int t = t0 + p;
+            const bool there = t < nPairs;   // uniform over the workgroup; only the arithmetic is skipped
+            if (there) {
+                // the wave's LDS operations execute in order: these writes land after the previous
+                // run's reads and before the reads below
+#pragma unroll
+                for (int j = 0; j < 2 * MB; ++j)
+                    *reinterpret_cast<uint4_t*>(stage + ((j & 1) ? st_w1 : st_w0) + 1024 * j) = xr[j];
+                if (FUSED && r8 == 0) *reinterpret_cast<uint4_t*>(stage + st_g + (c8 << 4)) = gr;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            issue_x(t + 1);
+            asm volatile("" ::: "memory");   // pins the loads here: nothing may carry them down to their first use
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if (there) consume((2 * p + h) % D, h);
+                __builtin_amdgcn_sched_barrier(0);
+                issue_w(2 * t + h + D, (2 * p + h) % D);
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
@@ -255,7 +306,10 @@ static SkinnyPlan skinny_plan(const Problem& p)
     pl.n_tiles = p.gated ? (p.N / 2 + n_tile / 2 - 1) / (n_tile / 2) : (p.N + n_tile - 1) / n_tile;
     int k_slab = (p.K + S - 1) / S;
     k_slab = (k_slab + gran - 1) / gran * gran;
-    while (int64_t(k_slab) * p.N * 2 >= (int64_t(1) << 31)) k_slab = (k_slab / 2 + gran - 1) / gran * gran;
+    // the ring runs a few steps past the slab, and those offsets must stay below 2^31 as well
+    while (k_slab > gran && int64_t(k_slab + 4 * gran) * p.N * 2 >= (int64_t(1) << 31))
+        k_slab = (k_slab / 2 + gran - 1) / gran * gran;
+    if (int64_t(k_slab + 4 * gran) * p.N * 2 >= (int64_t(1) << 31)) { pl.why = "skinny variant needs N < 2^20"; return pl; }
     S = (p.K + k_slab - 1) / k_slab;
     pl.S = S;
     pl.k_slab = k_slab;
