@@ -44,7 +44,9 @@ typedef enum {
     RL_GEMV_SPLITK = 1,   /* M <= 16, no matrix cores, K split over workgroups */
     RL_MFMA_SKINNY = 2,   /* M <= 64, matrix cores, K split over the waves of a workgroup */
     RL_MFMA_TILE = 3,     /* large M: 256x256 output tiles on matrix cores */
-    RL_NAIVE = 4          /* any shape and type, fp32 arithmetic, slow */
+    RL_NAIVE = 4,         /* any shape and type, fp32 arithmetic, slow */
+    RL_MFMA_TILE_PRE = 5  /* large M and N: X (.) g and 1/rms written once by a first kernel (workspace of
+                             2 M K + 4 M bytes), then the tile kernel as a product scaled per row */
 } rl_variant;
 
 /*
@@ -95,7 +97,7 @@ rl_status silu_mul(const void* Z, void* Y, int64_t M, int64_t H, rl_dtype dt, vo
 
 /*
  * Variant control (process-wide).  RL_AUTO is the default; the environment variable
- * RL_VARIANT (auto|gemv|skinny|tile|naive) sets the initial value.  A forced variant that
+ * RL_VARIANT (auto|gemv|skinny|tile|tile_pre|naive) sets the initial value.  A forced variant that
  * cannot run a shape makes the call return RL_ERR_UNSUPPORTED instead of falling back.
  * rl_last_variant() reports what the most recent successful call on this thread ran.
  */

@@ -52,6 +52,7 @@ void read_env_locked()
     if (!strcmp(e, "gemv")) g_variant = RL_GEMV_SPLITK;
     else if (!strcmp(e, "skinny")) g_variant = RL_MFMA_SKINNY;
     else if (!strcmp(e, "tile")) g_variant = RL_MFMA_TILE;
+    else if (!strcmp(e, "tile_pre")) g_variant = RL_MFMA_TILE_PRE;
     else if (!strcmp(e, "naive")) g_variant = RL_NAIVE;
     else g_variant = RL_AUTO;
 }
@@ -67,8 +68,12 @@ rl_status check_dims(int64_t M, int64_t K, int64_t N, rl_dtype dt)
     return RL_OK;
 }
 
-// workspace for the current device: the lent buffer if there is one, else the library's own
-rl_status get_workspace(size_t need, Workspace* out)
+constexpr size_t kMaxOwnWorkspace = size_t(4) << 30;
+
+// Workspace for the current device: the lent buffer if there is one, else the library's own.  The
+// library's own buffer grows when a call needs more (the old one is freed, which waits for the
+// device), except while `stream` is being captured into a graph: nothing may be allocated then.
+rl_status get_workspace(size_t need, hipStream_t stream, Workspace* out)
 {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -80,16 +85,27 @@ rl_status get_workspace(size_t need, Workspace* out)
         *out = g_lent[dev];
         return RL_OK;
     }
-    if (!g_ws[dev].ptr) {
+    if (!g_ws[dev].ptr || g_ws[dev].bytes < need + kHeadBytes) {
+        const size_t want = std::max(kDefaultWorkspace, (need + kHeadBytes + 0xfffff) & ~size_t(0xfffff));
+        if (want > kMaxOwnWorkspace)
+            return fail(RL_ERR_WORKSPACE, "shape needs more workspace than the library allocates; lend one with rl_set_workspace");
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        e = hipStreamIsCapturing(stream, &cap);
+        if (e != hipSuccess) return fail(RL_ERR_HIP, "hipStreamIsCapturing: %s", hipGetErrorString(e));
+        if (cap != hipStreamCaptureStatusNone)
+            return fail(RL_ERR_WORKSPACE, "the workspace cannot grow during stream capture: run the shape once before, or lend a workspace");
+        if (g_ws[dev].ptr) {
+            e = hipFree(g_ws[dev].ptr);              // waits for everything that may still use it
+            g_ws[dev] = Workspace{nullptr, 0, false};
+            if (e != hipSuccess) return fail(RL_ERR_HIP, "hipFree(workspace): %s", hipGetErrorString(e));
+        }
         void* p = nullptr;
-        e = hipMalloc(&p, kDefaultWorkspace);
+        e = hipMalloc(&p, want);
         if (e != hipSuccess) return fail(RL_ERR_HIP, "hipMalloc(workspace): %s", hipGetErrorString(e));
-        e = hipMemset(p, 0, kCounterBytes);              // synchronous, once per device
+        e = hipMemset(p, 0, kCounterBytes);              // synchronous, once per allocation
         if (e != hipSuccess) { (void)hipFree(p); return fail(RL_ERR_HIP, "hipMemset(workspace): %s", hipGetErrorString(e)); }
-        g_ws[dev] = Workspace{p, kDefaultWorkspace, true};
+        g_ws[dev] = Workspace{p, want, true};
     }
-    if (g_ws[dev].bytes < need + kHeadBytes)
-        return fail(RL_ERR_WORKSPACE, "shape needs more split-K workspace than the library holds; lend one with rl_set_workspace");
     *out = g_ws[dev];
     return RL_OK;
 }
@@ -113,6 +129,14 @@ rl_variant choose_auto(const Problem& p)
     return RL_MFMA_TILE;
 }
 
+// Large M and N: the fused tile kernel repeats the X-hat conversion in every one of its N / 256
+// workgroup columns; writing X-hat once (4 M K bytes of traffic) costs less than that from about
+// N = 4096 on, where the product is bound by the matrix cores.
+bool prefers_two_kernels(const Problem& p)
+{
+    return p.fused && p.M >= 1024 && p.N >= 4096;
+}
+
 // one attempt at one variant; hipErrorInvalidValue = the variant cannot run the shape
 hipError_t launch_variant(rl_variant v, Problem& p, hipStream_t s, const char** why, rl_status* ws_status)
 {
@@ -120,10 +144,11 @@ hipError_t launch_variant(rl_variant v, Problem& p, hipStream_t s, const char** 
     size_t need = 0;
     if (v == RL_GEMV_SPLITK) need = gemv_workspace_bytes(p);
     else if (v == RL_MFMA_SKINNY) need = skinny_workspace_bytes(p);
+    else if (v == RL_MFMA_TILE_PRE) need = tile_pre_workspace_bytes(p);
     p.ws_partial = nullptr; p.ws_sumsq = nullptr; p.ws_counter = nullptr;
     if (need) {
         Workspace ws;
-        *ws_status = get_workspace(need, &ws);
+        *ws_status = get_workspace(need, s, &ws);
         if (*ws_status != RL_OK) return hipErrorUnknown;
         carve(ws, p);
     }
@@ -131,6 +156,7 @@ hipError_t launch_variant(rl_variant v, Problem& p, hipStream_t s, const char** 
     case RL_GEMV_SPLITK: return launch_gemv(p, s, why);
     case RL_MFMA_SKINNY: return launch_skinny(p, s, why);
     case RL_MFMA_TILE:   return launch_tile(p, s, why);
+    case RL_MFMA_TILE_PRE: return launch_tile_pre(p, s, why);
     case RL_NAIVE:       return launch_naive(p, s, why);
     default:             return hipErrorInvalidValue;
     }
@@ -154,7 +180,7 @@ rl_status run(Problem& p, void* stream)
         }
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    rl_variant order[5];
+    rl_variant order[6];
     int n_order = 0;
     if (forced != RL_AUTO) {
         order[n_order++] = forced;
@@ -163,6 +189,7 @@ rl_status run(Problem& p, void* stream)
         p.k_split = 0;
         if (tuned.variant != RL_AUTO) order[n_order++] = tuned.variant;    // with its launch shape, see below
         rl_variant first = choose_auto(p);
+        if (first == RL_MFMA_TILE && prefers_two_kernels(p)) order[n_order++] = RL_MFMA_TILE_PRE;
         order[n_order++] = first;
         if (first == RL_MFMA_TILE) order[n_order++] = RL_MFMA_SKINNY;
         if (first != RL_NAIVE) order[n_order++] = RL_NAIVE;
@@ -178,7 +205,11 @@ rl_status run(Problem& p, void* stream)
         }
         rl_status ws_status;
         hipError_t e = launch_variant(v, p, s, &why, &ws_status);
-        if (ws_status != RL_OK) return ws_status;
+        if (ws_status != RL_OK) {
+            // the two-kernel form is an optimisation: without room for it the fused kernel runs
+            if (forced == RL_AUTO && v == RL_MFMA_TILE_PRE && ws_status == RL_ERR_WORKSPACE) continue;
+            return ws_status;
+        }
         if (e == hipSuccess) { tl_last_variant = v; return RL_OK; }
         if (e != hipErrorInvalidValue) return fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
         (void)hipGetLastError();
@@ -288,6 +319,7 @@ rl_status rl_autotune(const void* X, const void* g, const void* W, float eps, vo
         if (M > 16)
             for (int shape : {256, 512})
                 for (int nw : {4, 8}) cands.push_back({RL_MFMA_TILE, shape, nw});
+        if (M > 64) cands.push_back({RL_MFMA_TILE_PRE, 0, 0});
     }
     cands.push_back({RL_NAIVE, 0, 0});
 
@@ -385,7 +417,7 @@ rl_status rl_ff_rmsnorm_linear(const void* X, const void* g, const void* W, void
 
 rl_status rl_set_variant(rl_variant v)
 {
-    if (v < RL_AUTO || v > RL_NAIVE) return fail(RL_ERR_INVALID_ARG, "unknown variant");
+    if (v < RL_AUTO || v > RL_MFMA_TILE_PRE) return fail(RL_ERR_INVALID_ARG, "unknown variant");
     std::lock_guard<std::mutex> lk(g_mu);
     g_env_read = true;
     g_variant = v;
@@ -447,10 +479,14 @@ size_t rl_workspace_bytes(int64_t M, int64_t K, int64_t N, rl_dtype dt)
         v = g_variant;
         if (v != RL_AUTO) { p.n_tile = g_n_tile; p.k_split = g_k_split; }
     }
-    if (v == RL_AUTO) v = choose_auto(p);
+    if (v == RL_AUTO) {
+        v = choose_auto(p);
+        if (v == RL_MFMA_TILE && prefers_two_kernels(p)) v = RL_MFMA_TILE_PRE;   // optional: without it the fused kernel runs
+    }
     size_t need = 0;
     if (v == RL_GEMV_SPLITK) need = gemv_workspace_bytes(p);
     else if (v == RL_MFMA_SKINNY) need = skinny_workspace_bytes(p);
+    else if (v == RL_MFMA_TILE_PRE) need = tile_pre_workspace_bytes(p);
     return need ? need + kHeadBytes : 0;
 }
 

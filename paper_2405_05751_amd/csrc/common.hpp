@@ -23,6 +23,7 @@ struct Problem {
     float eps;
     int fused;            // 1: RMSNorm prologue + row scaling, 0: plain product
     int gated;            // 1: W is [K][N] = [gate | up] with N = 2H, Y is [M][H] = SiLU(Z_gate) * Z_up
+    const float* rscale;  // plain product only: Y rows scaled by rscale[i] in the epilogue, or null
     DType dt;
     // split-K workspace (may be null when the chosen launch needs none)
     float* ws_partial;    // [S][M][N] partial B
@@ -46,6 +47,10 @@ hipError_t launch_rmsnorm(const void* X, const void* g, float eps, void* Xn, int
 hipError_t launch_gemv(const Problem& p, hipStream_t s, const char** why);
 hipError_t launch_skinny(const Problem& p, hipStream_t s, const char** why);
 hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why);
+// two kernels: X-hat and 1/rms per row into the workspace (at ws_partial), then the tile kernel as a
+// plain product of X-hat scaled per row
+hipError_t launch_tile_pre(const Problem& p, hipStream_t s, const char** why);
+size_t tile_pre_workspace_bytes(const Problem& p);
 // bytes of partial-B workspace the launch of this problem would use (0 = no split)
 size_t gemv_workspace_bytes(const Problem& p);
 size_t skinny_workspace_bytes(const Problem& p);

@@ -30,6 +30,7 @@ struct TileArgs {
     float eps, inv_K;
     int tiles_m, tiles_n;
     int H;           // gated block: N = 2H, a tile is 128 gate columns and the up columns of the same outputs; else 0
+    const float* rscale;   // plain product: per-row factor applied in the epilogue, or null
 };
 
 // Tile shapes: 0 = 256 rows x 256 columns (2 x NW/2 waves), 1 = 128 rows x 512 columns (1 x NW waves).
@@ -364,7 +365,12 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
         __syncthreads();
         if (tid < BM) s_rinv[tid] = row_scale(s_ss[tid], a.inv_K, a.eps);
         __syncthreads();
+    } else if (a.rscale) {                               // uniform: the rows' factors come from the caller
+        __syncthreads();
+        if (tid < BM) s_rinv[tid] = m0 + tid < a.M ? a.rscale[m0 + tid] : 0.f;
+        __syncthreads();
     }
+    const bool scaled = FUSED || a.rscale != nullptr;
 
     // ---- epilogue: D register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its tile
     const int col_l = lane & 31, rowq = 4 * (lane >> 5);
@@ -373,7 +379,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int row = wm * (BM / WM) + i * 32 + 8 * (r >> 2) + rowq + (r & 3);
-            const float ri = FUSED ? s_rinv[row] : 1.f;
+            const float ri = scaled ? s_rinv[row] : 1.f;
             if (m0 + row < a.M) {
                 if (GATED) {
                     const int c0 = n0 + wn * (BN / WN / 2) + col_l;
@@ -438,11 +444,12 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
     TileArgs a;
     a.X = (const u16*)p.X; a.g = (const u16*)p.g; a.W = (const u16*)p.W; a.Y = (u16*)p.Y;
     a.M = p.M; a.K = p.K; a.N = p.N; a.eps = p.eps; a.inv_K = 1.0f / float(p.K);
-    if (p.gated && (p.N % 16 != 0 || !p.fused)) {
+    if (p.gated && (p.N % 16 != 0 || (!p.fused && !p.rscale))) {
         if (why) *why = "gated block: tile variant needs H % 8 == 0";
         return hipErrorInvalidValue;
     }
     a.H = p.gated ? p.N / 2 : 0;
+    a.rscale = p.fused ? nullptr : p.rscale;
     a.tiles_m = (p.M + BM - 1) / BM;
     a.tiles_n = p.gated ? (a.H + BN / 2 - 1) / (BN / 2) : (p.N + BN - 1) / BN;
     if (int64_t(a.tiles_m) * a.tiles_n >= (int64_t(1) << 31)) {
@@ -451,11 +458,110 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
     }
     dim3 grid(a.tiles_m * a.tiles_n);
     const bool fused = p.fused != 0;
+    if (p.gated && !fused)                  // gate over a product of a materialised X-hat, scaled per row
+        return p.dt == F16 ? tile_nw<Fp16, false, true>(a, grid, nw, shape, s) : tile_nw<Bf16, false, true>(a, grid, nw, shape, s);
     if (p.gated)
         return p.dt == F16 ? tile_nw<Fp16, true, true>(a, grid, nw, shape, s) : tile_nw<Bf16, true, true>(a, grid, nw, shape, s);
     if (p.dt == F16)
         return fused ? tile_nw<Fp16, true, false>(a, grid, nw, shape, s) : tile_nw<Fp16, false, false>(a, grid, nw, shape, s);
     return fused ? tile_nw<Bf16, true, false>(a, grid, nw, shape, s) : tile_nw<Bf16, false, false>(a, grid, nw, shape, s);
+}
+
+// ------------------------------------------------------------------- two-kernel form for large M
+// The fused tile kernel converts its 256 rows of X to X-hat once per workgroup, so a problem with
+// N / 256 workgroup columns repeats that conversion N / 256 times, on the same vector units that
+// have to feed the matrix cores.  For large M and N it is cheaper to write X-hat (rounded once, as in
+// the fused kernel) and 1 / rms per row to device memory in a first, memory-bound kernel and to run
+// the tile kernel as a plain product whose epilogue applies the row factors (Fig. 2b's division after
+// the product, with the normalised input materialised as in Fig. 2a).
+// One workgroup per row.  PER > 0: the row has at most 256 * PER 16-byte chunks and a thread's
+// loads are all issued before the first is used; PER = 0: any K, one chunk at a time.
+template <typename T, int PER>
+__global__ __launch_bounds__(256) void xhat_rows_kernel(const uint4_t* __restrict__ X, const uint4_t* __restrict__ g,
+                                                        uint4_t* __restrict__ Xh, float* __restrict__ rscale,
+                                                        int K8, float eps, float inv_K)
+{
+    __shared__ float part[4];
+    const size_t row = size_t(blockIdx.x) * K8;
+    float ss = 0.f;
+    auto one = [&](uint4_t xv, uint4_t gv) {
+        uint4_t o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float x0 = Elem<T>::lo(xv[e]), x1 = Elem<T>::hi(xv[e]);
+            ss = __fmaf_rn(x0, x0, ss);
+            ss = __fmaf_rn(x1, x1, ss);
+            o[e] = Elem<T>::pack(x0 * Elem<T>::lo(gv[e]), x1 * Elem<T>::hi(gv[e]));
+        }
+        return o;
+    };
+    if constexpr (PER > 0) {
+        uint4_t xv[PER], gv[PER];
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int c = threadIdx.x + j * 256;
+            xv[j] = c < K8 ? X[row + c] : uint4_t{0, 0, 0, 0};
+            gv[j] = c < K8 ? g[c] : uint4_t{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int c = threadIdx.x + j * 256;
+            const uint4_t o = one(xv[j], gv[j]);
+            if (c < K8) Xh[row + c] = o;
+        }
+    } else {
+        for (int c = threadIdx.x; c < K8; c += 256) Xh[row + c] = one(X[row + c], g[c]);
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    if (threadIdx.x == 0) rscale[blockIdx.x] = row_scale((part[0] + part[1]) + (part[2] + part[3]), inv_K, eps);
+}
+
+template <typename T>
+static void xhat_rows_go(const Problem& p, uint4_t* Xh, float* rscale, hipStream_t s)
+{
+    const int K8 = p.K / 8;
+    const float inv_K = 1.0f / float(p.K);
+    const uint4_t* X = (const uint4_t*)p.X;
+    const uint4_t* g = (const uint4_t*)p.g;
+    if (K8 <= 256)       xhat_rows_kernel<T, 1><<<p.M, 256, 0, s>>>(X, g, Xh, rscale, K8, p.eps, inv_K);
+    else if (K8 <= 512)  xhat_rows_kernel<T, 2><<<p.M, 256, 0, s>>>(X, g, Xh, rscale, K8, p.eps, inv_K);
+    else if (K8 <= 1024) xhat_rows_kernel<T, 4><<<p.M, 256, 0, s>>>(X, g, Xh, rscale, K8, p.eps, inv_K);
+    else if (K8 <= 2048) xhat_rows_kernel<T, 8><<<p.M, 256, 0, s>>>(X, g, Xh, rscale, K8, p.eps, inv_K);
+    else                 xhat_rows_kernel<T, 0><<<p.M, 256, 0, s>>>(X, g, Xh, rscale, K8, p.eps, inv_K);
+}
+
+static size_t xhat_bytes(const Problem& p) { return (size_t(p.M) * p.K * 2 + 255) / 256 * 256; }
+
+size_t tile_pre_workspace_bytes(const Problem& p) { return xhat_bytes(p) + size_t(p.M) * 4; }
+
+hipError_t launch_tile_pre(const Problem& p, hipStream_t s, const char** why)
+{
+    if (!p.fused) { if (why) *why = "two-kernel tile variant runs the fused blocks only"; return hipErrorInvalidValue; }
+    if (p.gated && p.N % 16 != 0) { if (why) *why = "gated block: tile variant needs H % 8 == 0"; return hipErrorInvalidValue; }
+    if (p.dt == F32 || p.N % 8 != 0 || p.K % 8 != 0) {
+        if (why) *why = "tile variants need a 16-bit type, N % 8 == 0 and K % 8 == 0";
+        return hipErrorInvalidValue;
+    }
+    if (!p.ws_partial) { if (why) *why = "two-kernel tile variant needs the workspace"; return hipErrorInvalidValue; }
+    uint4_t* Xh = reinterpret_cast<uint4_t*>(p.ws_partial);
+    float* rscale = reinterpret_cast<float*>(reinterpret_cast<char*>(p.ws_partial) + xhat_bytes(p));
+    Problem q = p;                           // the product of X-hat, scaled per row
+    q.X = Xh; q.g = nullptr; q.fused = 0; q.rscale = rscale;
+    const char* w2 = nullptr;
+    // check that the second kernel can run before the first is launched: both or neither
+    if (int64_t(p.K) * p.N * 2 >= (int64_t(1) << 31) || int64_t(256) * p.K * 2 >= (int64_t(1) << 31)) {
+        if (why) *why = "tile variant needs K*N < 2^30";
+        return hipErrorInvalidValue;
+    }
+    if (p.dt == F16) xhat_rows_go<Fp16>(p, Xh, rscale, s);
+    else             xhat_rows_go<Bf16>(p, Xh, rscale, s);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = launch_tile(q, s, &w2);
+    if (e != hipSuccess && why && w2) *why = w2;
+    return e;
 }
 
 }  // namespace rmsnl

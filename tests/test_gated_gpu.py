@@ -60,9 +60,11 @@ SHAPES = [
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
-@pytest.mark.parametrize("variant", ["auto", "gemv", "skinny", "tile", "naive"])
+@pytest.mark.parametrize("variant", ["auto", "gemv", "skinny", "tile", "tile_pre", "naive"])
 @pytest.mark.parametrize("M,K,H", SHAPES)
 def test_gated_shapes(rl, M, K, H, variant, dtype):
+    if variant == "tile_pre" and M <= 64:
+        pytest.skip("the two-kernel form is for large M")
     if variant == "skinny" and M > 64:
         pytest.skip("skinny needs M <= 64")
     if variant == "gemv" and M > 16:
@@ -111,6 +113,9 @@ def test_gated_prefill_sized_tile(rl):
     Y, used = _run(rl, w, rows=rows)
     assert used == "tile"
     compare_gated(Y, Z, "bf16", "gated 1000x2048x2*1160")
+    Y, used = _run(rl, w, "tile_pre", rows=rows)
+    assert used == "tile_pre"
+    compare_gated(Y, Z, "bf16", "gated 1000x2048x2*1160, two kernels")
 
 
 def test_gated_hand_case(rl, golden_hand_cases):

@@ -65,6 +65,8 @@ def _supported(variant, w):
         return w.M <= 16
     if variant == "skinny":
         return w.M <= 64
+    if variant == "tile_pre":
+        return w.M > 64
     return True
 
 
@@ -80,7 +82,7 @@ def test_config_auto(rl, name):
         assert ratio > 1e-3, "suspiciously small error: is the comparison against a rounded oracle?"
 
 
-@pytest.mark.parametrize("variant", ["naive", "gemv", "skinny", "tile"])
+@pytest.mark.parametrize("variant", ["naive", "gemv", "skinny", "tile", "tile_pre"])
 @pytest.mark.parametrize("name", workloads.CONFIG_NAMES)
 def test_config_forced_variant(rl, name, variant):
     shape = workloads.config_shape(name)
@@ -159,6 +161,49 @@ def test_tile_launch_shapes(rl, M, K, N, n_tile, waves):
     Y, used = _run(rl, w, "tile", tuning=(n_tile, waves))
     assert used == "tile"
     compare(Y, Z, w.dtype, f"tile {M}x{K}x{N} shape={n_tile} waves={waves}")
+
+
+# ------------------------------------------------------------------ two-kernel tile variant
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("M,K,N", [(65, 8, 8), (130, 1544, 520), (257, 2056, 264), (300, 4104, 1288),
+                                   (70, 16392, 264), (1100, 520, 4104)])
+def test_tile_pre_variant(rl, M, K, N, dtype):
+    """X-hat and 1/rms written by a first kernel, then the tile kernel as a scaled product: every
+    prepass form (1, 2, 4, 8 chunks per thread and the loop), ragged K and N, several tiles."""
+    w = workloads.make(M, K, N, dtype, 1e-5, 4600 + M + K + N, outlier_frac=0.05)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used = _run(rl, w, "tile_pre")
+    assert used == "tile_pre"
+    compare(Y, Z, w.dtype, f"tile_pre {M}x{K}x{N} {dtype}")
+    Yt, _ = _run(rl, w, "tile")
+    # same X-hat rounding and the same product kernel: only the order of the sum of squares differs
+    compare(Y, Yt, w.dtype, "tile_pre against tile")
+
+
+def test_tile_pre_is_the_automatic_choice_for_large_shapes(rl):
+    import torch
+    w = workloads.make(1024, 264, 4096, "bf16", 1e-5, 4700)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used = _run(rl, w, "auto")
+    assert used == "tile_pre"
+    compare(Y, Z, w.dtype, "auto -> tile_pre")
+    # a lent workspace without room for X-hat: the fused tile kernel runs instead, no error
+    small = torch.zeros(1400 * 1024 // 4, dtype=torch.float32, device="cuda")     # head fits, X-hat does not
+    try:
+        rl.rl_set_workspace(small)
+        Y, used = _run(rl, w, "auto")
+        assert used == "tile"
+        compare(Y, Z, w.dtype, "auto -> tile with a small lent workspace")
+        rl.rl_set_variant("tile_pre")
+        X, g, W = upload(w)
+        with pytest.raises(rl.RmsnlError) as ei:
+            rl.rmsnorm_linear(X, g, W, w.eps)
+        assert ei.value.status == 4
+    finally:
+        rl.rl_set_variant("auto")
+        rl.rl_set_workspace(None)
+    need = rl.rl_workspace_bytes(w.M, w.K, w.N, torch.bfloat16)
+    assert need >= 2 * w.M * w.K + 4 * w.M
 
 
 # ------------------------------------------------------------------ fp32 path
