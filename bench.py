@@ -34,7 +34,7 @@ ROTATE_BYTES = 512 << 20
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same counters
 # read for the plain copy kernel (x2.0 and x1.0): profiles/hbm_traffic_pmc.md.  Counters cannot be read from
 # inside this process, so the table is refreshed by hand when a kernel's launch shape changes.
-MEASURED_TRAFFIC_BYTES = {"decode": 34.47e6, "qkv": 55.00e6, "gateup": 243.01e6, "prefill": 1745.6e6}
+MEASURED_TRAFFIC_BYTES = {"decode": 34.46e6, "qkv": 55.01e6, "gateup": 243.11e6, "prefill": 2014.1e6}
 
 
 def _time_region(fn_enqueue, torch):
