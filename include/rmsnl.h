@@ -40,10 +40,12 @@ typedef enum {
 typedef enum { RL_F16 = 0, RL_BF16 = 1, RL_F32 = 2 } rl_dtype;
 
 typedef enum {
-    RL_AUTO = 0,          /* pick by shape */
+    RL_AUTO = 0,          /* pick by shape: M = 1 GEMV; M <= 64 skinny; above that skinny per 64 rows while the tile
+                             kernels would have too few workgroups (a cost model), else the tile kernels */
     RL_GEMV_SPLITK = 1,   /* M <= 16, no matrix cores, K split over workgroups */
-    RL_MFMA_SKINNY = 2,   /* M <= 64, matrix cores, K split over the waves of a workgroup */
-    RL_MFMA_TILE = 3,     /* large M: 256x256 output tiles on matrix cores */
+    RL_MFMA_SKINNY = 2,   /* matrix cores, 64 rows per launch (M <= 1024: one launch after the other), K split
+                             over the waves of a workgroup and over workgroups */
+    RL_MFMA_TILE = 3,     /* large M: 256x256 output tiles on matrix cores, one fused kernel */
     RL_NAIVE = 4,         /* any shape and type, fp32 arithmetic, slow */
     RL_MFMA_TILE_PRE = 5  /* large M and N: X (.) g and 1/rms written once by a first kernel (workspace of
                              2 M K + 4 M bytes), then the tile kernel as a product scaled per row */

@@ -16,6 +16,7 @@
 // A workgroup owns 128 columns and one K slab; its NW waves take alternate 64-row runs of the
 // slab, two 32-row steps each, so nothing in the K loop needs a barrier.  The waves' fp32 tiles meet in LDS, and the
 // common split-K epilogue finishes (see splitk.hpp).
+#include <algorithm>
 #include "common.hpp"
 #include "splitk.hpp"
 
@@ -262,7 +263,7 @@ static SkinnyPlan skinny_plan(const Problem& p)
     SkinnyPlan pl{};
     pl.ok = false;
     if (p.dt == F32) { pl.why = "skinny variant handles 16-bit types only"; return pl; }
-    if (p.M > 64) { pl.why = "skinny variant needs M <= 64"; return pl; }
+    if (p.M > 64) { pl.why = "skinny kernel takes at most 64 rows per launch"; return pl; }
     if (p.N % 8 != 0 || p.K % 8 != 0) { pl.why = "skinny variant needs N % 8 == 0 and K % 8 == 0"; return pl; }
     if (int64_t(p.M) * p.K * 2 >= (int64_t(1) << 31)) { pl.why = "skinny variant needs M*K < 2^30"; return pl; }
     if (p.n_tile != 0 && (p.n_tile % 8 != 0 || p.n_tile < 8 || p.n_tile > kSkinnyTile)) {
@@ -323,9 +324,16 @@ static SkinnyPlan skinny_plan(const Problem& p)
 
 size_t skinny_workspace_bytes(const Problem& p)
 {
-    SkinnyPlan pl = skinny_plan(p);
-    if (!pl.ok || pl.S <= 1) return 0;
-    return size_t(pl.S) * p.M * p.N * 4;
+    // larger M runs block after block through the same workspace: full blocks and the last one
+    size_t need = 0;
+    for (int m : {std::min(p.M, 64), p.M % 64}) {
+        if (m == 0) continue;
+        Problem q = p;
+        q.M = m;
+        SkinnyPlan pl = skinny_plan(q);
+        if (pl.ok && pl.S > 1) need = std::max(need, size_t(pl.S) * q.M * q.N * 4);
+    }
+    return need;
 }
 
 template <typename T, int MB>
@@ -355,7 +363,7 @@ static hipError_t skinny_mb(const SkinnyArgs& a, bool fused, bool gated, const S
     }
 }
 
-hipError_t launch_skinny(const Problem& p, hipStream_t s, const char** why)
+static hipError_t launch_skinny_block(const Problem& p, hipStream_t s, const char** why)
 {
     SkinnyPlan pl = skinny_plan(p);
     if (!pl.ok) { if (why) *why = pl.why; return hipErrorInvalidValue; }
@@ -372,6 +380,40 @@ hipError_t launch_skinny(const Problem& p, hipStream_t s, const char** why)
     a.trace = p.trace; a.trace_groups = p.trace_groups;
     const bool fused = p.fused != 0, gated = p.gated != 0;
     return p.dt == F16 ? skinny_mb<Fp16>(a, fused, gated, pl, s) : skinny_mb<Bf16>(a, fused, gated, pl, s);
+}
+
+// M > 64: one launch per block of 64 rows, in stream order (they share the workspace).  Every launch
+// streams W again - from the last-level cache when W fits it - which still beats a tile kernel
+// whose M/256 x N/256 workgroups would leave most of the chip idle; the caller decides when.
+constexpr int kSkinnyMaxM = 1024;
+
+static Problem skinny_rows(const Problem& p, int r0)
+{
+    Problem q = p;
+    q.M = std::min(64, p.M - r0);
+    q.X = static_cast<const char*>(p.X) + size_t(r0) * p.K * 2;
+    q.Y = static_cast<char*>(p.Y) + size_t(r0) * (p.gated ? p.N / 2 : p.N) * 2;
+    return q;
+}
+
+hipError_t launch_skinny(const Problem& p, hipStream_t s, const char** why)
+{
+    if (p.M <= 64) return launch_skinny_block(p, s, why);
+    if (p.M > kSkinnyMaxM) { if (why) *why = "skinny variant needs M <= 1024"; return hipErrorInvalidValue; }
+    if (p.dt == F32) { if (why) *why = "skinny variant handles 16-bit types only"; return hipErrorInvalidValue; }
+    for (int r0 = 0; r0 < p.M; r0 += 64) {   // all blocks can run, or none is launched
+        SkinnyPlan pl = skinny_plan(skinny_rows(p, r0));
+        if (!pl.ok) { if (why) *why = pl.why; return hipErrorInvalidValue; }
+        if (pl.S > 1 && (!p.ws_partial || !p.ws_sumsq || !p.ws_counter)) {
+            if (why) *why = "split-K needs the workspace";
+            return hipErrorInvalidValue;
+        }
+    }
+    for (int r0 = 0; r0 < p.M; r0 += 64) {
+        hipError_t e = launch_skinny_block(skinny_rows(p, r0), s, why);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace rmsnl

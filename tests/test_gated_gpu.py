@@ -65,8 +65,6 @@ SHAPES = [
 def test_gated_shapes(rl, M, K, H, variant, dtype):
     if variant == "tile_pre" and M <= 64:
         pytest.skip("the two-kernel form is for large M")
-    if variant == "skinny" and M > 64:
-        pytest.skip("skinny needs M <= 64")
     if variant == "gemv" and M > 16:
         pytest.skip("gemv needs M <= 16")
     w = workloads.make(M, K, 2 * H, dtype, 1e-5, 7000 + M * 3 + K + H, outlier_frac=0.1 if M > 8 else 0.0)
@@ -111,8 +109,11 @@ def test_gated_prefill_sized_tile(rl):
     rows = np.arange(0, 1000, 37)
     Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps, rows=rows)
     Y, used = _run(rl, w, rows=rows)
+    assert used in ("tile", "tile_pre", "skinny")
+    compare_gated(Y, Z, "bf16", f"gated 1000x2048x2*1160 auto->{used}")
+    Y, used = _run(rl, w, "tile", rows=rows)
     assert used == "tile"
-    compare_gated(Y, Z, "bf16", "gated 1000x2048x2*1160")
+    compare_gated(Y, Z, "bf16", "gated 1000x2048x2*1160, fused tile kernel")
     Y, used = _run(rl, w, "tile_pre", rows=rows)
     assert used == "tile_pre"
     compare_gated(Y, Z, "bf16", "gated 1000x2048x2*1160, two kernels")

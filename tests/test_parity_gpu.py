@@ -64,7 +64,7 @@ def _supported(variant, w):
     if variant == "gemv":
         return w.M <= 16
     if variant == "skinny":
-        return w.M <= 64
+        return w.M <= 1024
     if variant == "tile_pre":
         return w.M > 64
     return True
@@ -161,6 +161,30 @@ def test_tile_launch_shapes(rl, M, K, N, n_tile, waves):
     Y, used = _run(rl, w, "tile", tuning=(n_tile, waves))
     assert used == "tile"
     compare(Y, Z, w.dtype, f"tile {M}x{K}x{N} shape={n_tile} waves={waves}")
+
+
+# ------------------------------------------------------------------ skinny kernel, block after block
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("M,K,N", [(65, 264, 136), (128, 1032, 520), (200, 4096, 1024), (1024, 520, 264)])
+def test_skinny_runs_larger_m_in_blocks_of_64_rows(rl, M, K, N, dtype):
+    w = workloads.make(M, K, N, dtype, 1e-5, 4800 + M + K + N, outlier_frac=0.05)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used = _run(rl, w, "skinny")
+    assert used == "skinny"
+    compare(Y, Z, w.dtype, f"skinny in blocks {M}x{K}x{N} {dtype}")
+
+
+def test_mid_m_automatic_choice(rl):
+    """Few tile-kernel workgroups: the skinny kernel per 64 rows; many: the tile kernels."""
+    w = workloads.make(128, 2048, 2048, "bf16", 1e-5, 4900)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used = _run(rl, w, "auto")
+    assert used == "skinny"
+    compare(Y, Z, w.dtype, "auto -> skinny at M = 128")
+    w = workloads.make(2, 1024, 2048, "bf16", 1e-5, 4901)
+    Y, used = _run(rl, w, "auto")
+    assert used == "skinny"
+    compare(Y, oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps), w.dtype, "auto -> skinny at M = 2")
 
 
 # ------------------------------------------------------------------ two-kernel tile variant
