@@ -40,15 +40,16 @@ typedef enum {
 typedef enum { RL_F16 = 0, RL_BF16 = 1, RL_F32 = 2 } rl_dtype;
 
 typedef enum {
-    RL_AUTO = 0,          /* pick by shape: M = 1 GEMV; M <= 64 skinny; above that skinny per 64 rows while the tile
-                             kernels would have too few workgroups (a cost model), else the tile kernels */
+    RL_AUTO = 0,          /* pick by shape: M = 1 GEMV; M <= 64 skinny; above that the two-kernel tile form, or the
+                             fused tile kernel when the workspace has no room for it */
     RL_GEMV_SPLITK = 1,   /* M <= 16, no matrix cores, K split over workgroups */
     RL_MFMA_SKINNY = 2,   /* matrix cores, 64 rows per launch (M <= 1024: one launch after the other), K split
                              over the waves of a workgroup and over workgroups */
     RL_MFMA_TILE = 3,     /* large M: 256x256 output tiles on matrix cores, one fused kernel */
     RL_NAIVE = 4,         /* any shape and type, fp32 arithmetic, slow */
-    RL_MFMA_TILE_PRE = 5  /* large M and N: X (.) g and 1/rms written once by a first kernel (workspace of
-                             2 M K + 4 M bytes), then the tile kernel as a product scaled per row */
+    RL_MFMA_TILE_PRE = 5  /* M > 64: X (.) g and 1/rms written once by a first kernel (workspace of 2 M K + 4 M bytes),
+                             then the tile kernel as a product scaled per row; with few 256x256 tiles the product is
+                             split over K into fp32 partials (up to 64 MiB more) that a third kernel adds up */
 } rl_variant;
 
 /*
@@ -113,7 +114,9 @@ rl_variant rl_last_variant(void);
  *   n_tile  columns of W per workgroup (GEMV: 64, 128, 256, 512; skinny: a multiple of 8 up to 128;
  *           tile: 256 = 256x256 tiles, 512 = 128x512 tiles),
  *   k_split number of K slabs (split-K factor) of the GEMV and skinny variants; for the tile variant
- *           the waves per workgroup (4 or 8).
+ *           the waves per workgroup (4 or 8); for the two-kernel tile variant n_tile = 1 makes k_split
+ *           (1 to 16) the number of K slabs of its product (1 = no split; otherwise the library splits
+ *           when the 256x256 tiles are too few to fill the chip).
  * Values a variant cannot honour give RL_ERR_UNSUPPORTED at the next call.
  */
 rl_status rl_set_tuning(int n_tile, int k_split);

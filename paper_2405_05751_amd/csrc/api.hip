@@ -119,21 +119,6 @@ void carve(const Workspace& ws, Problem& p)
     p.ws_partial = reinterpret_cast<float*>(base + kHeadBytes);
 }
 
-// Rough times (us) of the two ways to run 64 < M <= 1024: the skinny kernel once per 64 rows, each
-// launch streaming W at about 5 TB/s plus a split-K epilogue, against the tile kernel, whose
-// workgroups each finish a 256 x 256 x K tile in K * 20 to 27 ns however few of them there are.
-bool skinny_blocks_beat_tiles(const Problem& p)
-{
-    if (p.M > 1024) return false;
-    const double passes = double((p.M + 63) / 64);
-    const double t_skinny = passes * (double(p.K) * p.N * 2.0 / 5.0e6 + 8.0);
-    const double tiles = double((p.M + 255) / 256) * double((p.N + 255) / 256);
-    const double rounds = double((int64_t(tiles) + 255) / 256);
-    const double fill = std::min(1.0, tiles / 256.0);       // a busy chip clocks lower
-    const double t_tile = rounds * double(p.K) * (0.0205 + 0.006 * fill) + 4.0 * p.M * double(p.K) / 6.0e6;
-    return t_skinny < t_tile;
-}
-
 rl_variant choose_auto(const Problem& p)
 {
     if (p.dt == F32) return RL_NAIVE;
@@ -141,14 +126,16 @@ rl_variant choose_auto(const Problem& p)
     if (p.gated && p.N % 16 != 0) return RL_NAIVE;
     if (p.M == 1) return RL_GEMV_SPLITK;     // from two rows on the matrix-core kernel is faster
     if (p.M <= 64) return RL_MFMA_SKINNY;
-    if (skinny_blocks_beat_tiles(p)) return RL_MFMA_SKINNY;
+    // (the skinny kernel can run larger M block after block; the tile kernels, split over K when
+    // their tiles are few, measured faster from M = 65 on)
     return RL_MFMA_TILE;
 }
 
 // The fused tile kernel repeats the X-hat conversion in every one of its N / 256 workgroup
-// columns; writing X-hat once (4 M K bytes of traffic) measured faster at every tile-sized shape
-// tried (M 128 to 8192, N 2048 to 28672), so the fused tile kernel is what runs when the
-// workspace has no room for X-hat.
+// columns and cannot split K; writing X-hat once (4 M K bytes of traffic) and running the product
+// on it, split over K when its tiles are few, measured faster at every tile-sized shape tried
+// (M 65 to 8192, N 2048 to 28672), so the fused tile kernel is what runs when the workspace has no
+// room for X-hat.
 bool prefers_two_kernels(const Problem& p)
 {
     return p.fused != 0;
@@ -208,7 +195,6 @@ rl_status run(Problem& p, void* stream)
         rl_variant first = choose_auto(p);
         if (first == RL_MFMA_TILE && prefers_two_kernels(p)) order[n_order++] = RL_MFMA_TILE_PRE;
         order[n_order++] = first;
-        if (first == RL_MFMA_SKINNY && p.M > 64) order[n_order++] = RL_MFMA_TILE;
         if (first != RL_NAIVE) order[n_order++] = RL_NAIVE;
     }
     const char* why = "variant cannot run this shape";
@@ -336,7 +322,8 @@ rl_status rl_autotune(const void* X, const void* g, const void* W, float eps, vo
         if (M > 16)
             for (int shape : {256, 512})
                 for (int nw : {4, 8}) cands.push_back({RL_MFMA_TILE, shape, nw});
-        if (M > 64) cands.push_back({RL_MFMA_TILE_PRE, 0, 0});
+        if (M > 64)                        // two-kernel form: the library's own K split, none, 2 to 16 slabs
+            for (int ks : {0, 1, 2, 4, 8, 16}) cands.push_back({RL_MFMA_TILE_PRE, ks ? 1 : 0, ks});
     }
     cands.push_back({RL_NAIVE, 0, 0});
 

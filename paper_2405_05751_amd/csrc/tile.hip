@@ -19,6 +19,7 @@
 //
 // Out-of-range rows of X and W read as zero through buffer resources; ragged M, N and K % 64 are
 // handled by those reads and by guarded stores (N % 8 == 0 and K % 8 == 0 are required).
+#include <algorithm>
 #include "common.hpp"
 #include <type_traits>
 
@@ -31,6 +32,10 @@ struct TileArgs {
     int tiles_m, tiles_n;
     int H;           // gated block: N = 2H, a tile is 128 gate columns and the up columns of the same outputs; else 0
     const float* rscale;   // plain product: per-row factor applied in the epilogue, or null
+    // SPLIT kernels: workgroup (tile, slab) covers k in [slab * k_slab, +k_slab) and stores its
+    // fp32 tile to part [slab][M][N]; tiles_m * tiles_n workgroups per slab
+    int k_slab;
+    float* part;
 };
 
 // Tile shapes: 0 = 256 rows x 256 columns (2 x NW/2 waves), 1 = 128 rows x 512 columns (1 x NW waves).
@@ -95,9 +100,12 @@ template <> struct SqPair<Fp16> {
 // GATED (the GatedMLP block on top): the tile's 256 columns are 128 outputs' gate and up columns,
 // laid out so that MFMA tiles j and j + TN/2 of a wave are gate and up of the same 32 outputs; the
 // epilogue then forms SiLU(gate) * up in registers.  Only the column a lane fetches changes.
-template <typename T, bool FUSED, int NW, bool GATED, int SHAPE>
+// SPLIT (plain product only): the K range is split over workgroups, which leave fp32 partial tiles
+// for tile_reduce_kernel to add up, for shapes with too few tiles to fill the chip.
+template <typename T, bool FUSED, int NW, bool GATED, int SHAPE, bool SPLIT = false>
 __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
 {
+    static_assert(!SPLIT || (!FUSED && !GATED), "split-K runs the plain product");
     constexpr int BM = tile_bm(SHAPE), BN = tile_bn(SHAPE);
     constexpr int NT = 64 * NW;                  // threads
     constexpr int WM = SHAPE ? 1 : 2;            // waves along M
@@ -121,8 +129,12 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
     // grid allows, XCD x works through a band of tile rows, four rows at a time, so the ~32 tiles
     // it runs together share few X and W panels in that L2.
     int tm, tn;
+    const int n_tiles = a.tiles_m * a.tiles_n;
+    const int slab = SPLIT ? int(blockIdx.x) / n_tiles : 0;
+    const int kb = SPLIT ? slab * a.k_slab : 0;                     // first k of this workgroup
+    const int Kend = SPLIT ? min(a.K, kb + a.k_slab) : a.K;         // k at or beyond it reads as zero
     {
-        const int b = blockIdx.x;
+        const int b = SPLIT ? int(blockIdx.x) % n_tiles : int(blockIdx.x);
         if ((a.tiles_m & 7) == 0) {
             const int band = a.tiles_m >> 3;             // tile rows per XCD
             const int x = b & 7, idx = b >> 3;           // idx in [0, band * tiles_n)
@@ -175,8 +187,9 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
     // through the vector offset, which is what the range check looks at, so that k at or beyond K
     // reads zero (ragged last tile, and the prefetches that run past the end).
     auto load_x = [&](auto checked, int k0, int j) {
+        k0 += kb;
         if constexpr (decltype(checked)::value) {
-            const bool kin = k0 + ac < a.K;
+            const bool kin = k0 + ac < Kend;
             if (FUSED && j == 0) gv = __builtin_amdgcn_raw_buffer_load_b128(grs, kin ? (k0 + ac) * 2 : kTileOut, 0, 0);
             xa[j] = __builtin_amdgcn_raw_buffer_load_b128(xrs, kin ? xoff[j] + k0 * 2 : kTileOut, 0, 0);
         } else {
@@ -187,12 +200,13 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
     // The direct load is written in assembly: as a builtin, the compiler takes every later LDS read
     // for a possible reader of the bytes in flight and waits for all outstanding loads first.  The
     // waits for these loads are therefore placed by hand (RL_WAIT_VM before the barriers).
-    uint4_t wdesc = {uint32_t(uintptr_t(a.W)), uint32_t(uintptr_t(a.W) >> 32), uint32_t(a.K * a.N * 2),
+    // (rows of W at or beyond Kend lie beyond the resource)
+    uint4_t wdesc = {uint32_t(uintptr_t(a.W)), uint32_t(uintptr_t(a.W) >> 32), uint32_t(Kend * a.N * 2),
                            uint32_t(kTileFlags)};
     uint32_t bs_base = uint32_t(uintptr_t(Bs)) + uint32_t(wave) * 1024;         // LDS byte address of this wave's first KiB
     auto load_w = [&](auto checked, int buf, int k0, int p) {
         const uint32_t dst = bs_base + uint32_t(buf * BK * BN * 2 + NW * p * 1024);
-        const unsigned rowoff = unsigned(k0 + RPL * NW * p) * unsigned(a.N) * 2u;
+        const unsigned rowoff = unsigned(kb + k0 + RPL * NW * p) * unsigned(a.N) * 2u;
         int v = woff, so = int(rowoff);
         if constexpr (decltype(checked)::value) {
             v = woff == kTileOut ? kTileOut : int(unsigned(woff) + rowoff);
@@ -283,7 +297,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
     const std::integral_constant<bool, false> unchecked_c;
 
     // ---- prologue: tile 0 into LDS buffer 0, its first fragments into set 0, tile 1 on its way
-    const int nk = (a.K + BK - 1) / BK;
+    const int nk = (Kend - kb + BK - 1) / BK;
 #pragma unroll
     for (int p = 0; p < NP; ++p) load_w(checked_c, 0, 0, p);
 #pragma unroll
@@ -344,7 +358,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
         }
     };
     // iterations whose prefetches (tile kt+2) lie wholly inside K take the unchecked loads
-    const int n_fast = max(0, a.K / BK - 2);
+    const int n_fast = max(0, (Kend - kb) / BK - 2);
     for (int kt = 0; kt < n_fast; ++kt) iteration(unchecked_c, kt);
     for (int kt = n_fast; kt < nk; ++kt) iteration(checked_c, kt);
 #undef RL_SB
@@ -374,6 +388,23 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
 
     // ---- epilogue: D register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its tile
     const int col_l = lane & 31, rowq = 4 * (lane >> 5);
+    if constexpr (SPLIT) {
+        float* base = a.part + size_t(slab) * a.M * a.N;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = wm * (BM / WM) + i * 32 + 8 * (r >> 2) + rowq + (r & 3);
+                if (m0 + row < a.M) {
+                    const int c0 = n0 + wn * (BN / WN) + col_l;
+                    float* prow = base + size_t(m0 + row) * a.N + c0;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        if (c0 + j * 32 < a.N) prow[j * 32] = acc[i][j][r];
+                }
+            }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -450,6 +481,7 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
     }
     a.H = p.gated ? p.N / 2 : 0;
     a.rscale = p.fused ? nullptr : p.rscale;
+    a.k_slab = 0; a.part = nullptr;
     a.tiles_m = (p.M + BM - 1) / BM;
     a.tiles_n = p.gated ? (a.H + BN / 2 - 1) / (BN / 2) : (p.N + BN - 1) / BN;
     if (int64_t(a.tiles_m) * a.tiles_n >= (int64_t(1) << 31)) {
@@ -465,6 +497,78 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
     if (p.dt == F16)
         return fused ? tile_nw<Fp16, true, false>(a, grid, nw, shape, s) : tile_nw<Fp16, false, false>(a, grid, nw, shape, s);
     return fused ? tile_nw<Bf16, true, false>(a, grid, nw, shape, s) : tile_nw<Bf16, false, false>(a, grid, nw, shape, s);
+}
+
+// --------------------------------------------------------- split-K product for shapes with few tiles
+// part [S][M][N] fp32 -> Y: slabs added in order, rows scaled, one rounding (and, for the gated block,
+// column h paired with column H + h).  One thread per four output columns.
+template <typename T, bool GATED>
+__global__ __launch_bounds__(256) void tile_reduce_kernel(const float* __restrict__ part, const float* __restrict__ rscale,
+                                                          u16* __restrict__ Y, int M, int N, int S)
+{
+    const int H = N / 2;
+    const int cols4 = (GATED ? H : N) / 4;               // groups of four output columns per row
+    const int64_t idx = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (idx >= int64_t(M) * cols4) return;
+    const int row = int(idx / cols4), c = int(idx % cols4) * 4;
+    const size_t slab = size_t(M) * N;
+    const float* src = part + size_t(row) * N + c;
+    float4_t v = *(const float4_t*)src, u = float4_t{0.f, 0.f, 0.f, 0.f};
+    if (GATED) u = *(const float4_t*)(src + H);
+    for (int s = 1; s < S; ++s) {
+        const float4_t t = *(const float4_t*)(src + s * slab);
+        v += t;
+        if (GATED) u += *(const float4_t*)(src + s * slab + H);
+    }
+    const float ri = rscale ? rscale[row] : 1.f;
+    float o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = GATED ? silu(v[e] * ri) * (u[e] * ri) : v[e] * ri;
+    uint2_t out = {Elem<T>::pack(o[0], o[1]), Elem<T>::pack(o[2], o[3])};
+    *(uint2_t*)(Y + size_t(row) * (GATED ? H : N) + c) = out;
+}
+
+// slabs for a plain product whose 256x256 tiles number `tiles`: enough to give every compute unit a
+// workgroup, each slab a multiple of 64 rows and at least 256 of them
+static void tile_split_plan(int K, int64_t tiles, int* S, int* k_slab)
+{
+    int s = int(std::min<int64_t>(16, 256 / std::max<int64_t>(tiles, 1)));
+    s = std::min(s, std::max(1, K / 256));
+    if (s < 2) { *S = 1; *k_slab = K; return; }
+    int ks = ((K + s - 1) / s + BK - 1) / BK * BK;
+    *S = (K + ks - 1) / ks;
+    *k_slab = ks;
+}
+
+// the product of a materialised X-hat in S slabs + the reduction; part has room for [S][M][N] fp32
+static hipError_t launch_tile_split(const Problem& q, int S, int k_slab, float* part, hipStream_t s)
+{
+    TileArgs a;
+    a.X = (const u16*)q.X; a.g = nullptr; a.W = (const u16*)q.W; a.Y = (u16*)q.Y;
+    a.M = q.M; a.K = q.K; a.N = q.N; a.eps = 0.f; a.inv_K = 0.f;
+    a.H = 0; a.rscale = nullptr; a.k_slab = k_slab; a.part = part;
+    a.tiles_m = (q.M + 255) / 256;
+    a.tiles_n = (q.N + 255) / 256;
+    dim3 grid(a.tiles_m * a.tiles_n * S);
+    static LdsOnce once;
+    hipError_t e = raise_lds_once(once, {(const void*)tile_kernel<Fp16, false, 8, false, 0, true>,
+                                         (const void*)tile_kernel<Bf16, false, 8, false, 0, true>}, int(tile_lds(0)));
+    if (e != hipSuccess) return e;
+    if (q.dt == F16) tile_kernel<Fp16, false, 8, false, 0, true><<<grid, 512, tile_lds(0), s>>>(a);
+    else             tile_kernel<Bf16, false, 8, false, 0, true><<<grid, 512, tile_lds(0), s>>>(a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t groups = int64_t(q.M) * ((q.gated ? q.N / 2 : q.N) / 4);
+    dim3 rgrid((unsigned)((groups + 255) / 256));
+    u16* Y = (u16*)q.Y;
+    if (q.dt == F16) {
+        if (q.gated) tile_reduce_kernel<Fp16, true><<<rgrid, 256, 0, s>>>(part, q.rscale, Y, q.M, q.N, S);
+        else         tile_reduce_kernel<Fp16, false><<<rgrid, 256, 0, s>>>(part, q.rscale, Y, q.M, q.N, S);
+    } else {
+        if (q.gated) tile_reduce_kernel<Bf16, true><<<rgrid, 256, 0, s>>>(part, q.rscale, Y, q.M, q.N, S);
+        else         tile_reduce_kernel<Bf16, false><<<rgrid, 256, 0, s>>>(part, q.rscale, Y, q.M, q.N, S);
+    }
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------- two-kernel form for large M
@@ -534,7 +638,29 @@ static void xhat_rows_go(const Problem& p, uint4_t* Xh, float* rscale, hipStream
 
 static size_t xhat_bytes(const Problem& p) { return (size_t(p.M) * p.K * 2 + 255) / 256 * 256; }
 
-size_t tile_pre_workspace_bytes(const Problem& p) { return xhat_bytes(p) + size_t(p.M) * 4; }
+static size_t rscale_bytes(const Problem& p) { return (size_t(p.M) * 4 + 255) / 256 * 256; }
+
+// slabs of the product (1 = no split): forced by k_split = 1..16 when n_tile is 1 (a tuning
+// override of this variant only), else from the tile count
+static void tile_pre_split(const Problem& p, int* S, int* k_slab)
+{
+    const int64_t tiles = int64_t((p.M + 255) / 256) * ((p.N + 255) / 256);
+    tile_split_plan(p.K, tiles, S, k_slab);
+    if (p.n_tile == 1 && p.k_split >= 1 && p.k_split <= 16) {
+        if (p.k_split == 1) { *S = 1; *k_slab = p.K; return; }
+        const int ks = ((p.K + p.k_split - 1) / p.k_split + BK - 1) / BK * BK;
+        *S = (p.K + ks - 1) / ks;
+        *k_slab = ks;
+    }
+    if (p.N % 8 != 0 || (p.gated && p.N % 16 != 0)) { *S = 1; *k_slab = p.K; }
+}
+
+size_t tile_pre_workspace_bytes(const Problem& p)
+{
+    int S, k_slab;
+    tile_pre_split(p, &S, &k_slab);
+    return xhat_bytes(p) + rscale_bytes(p) + (S > 1 ? size_t(S) * p.M * p.N * 4 : 0);
+}
 
 hipError_t launch_tile_pre(const Problem& p, hipStream_t s, const char** why)
 {
@@ -559,6 +685,13 @@ hipError_t launch_tile_pre(const Problem& p, hipStream_t s, const char** why)
     else             xhat_rows_go<Bf16>(p, Xh, rscale, s);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    int S, k_slab;
+    tile_pre_split(p, &S, &k_slab);
+    if (S > 1) {
+        float* part = reinterpret_cast<float*>(reinterpret_cast<char*>(rscale) + rscale_bytes(p));
+        return launch_tile_split(q, S, k_slab, part, s);
+    }
+    if (p.n_tile == 1) { q.n_tile = 0; q.k_split = 0; }   // the override was for the split only
     e = launch_tile(q, s, &w2);
     if (e != hipSuccess && why && w2) *why = w2;
     return e;

@@ -114,9 +114,10 @@ def test_gated_prefill_sized_tile(rl):
     Y, used = _run(rl, w, "tile", rows=rows)
     assert used == "tile"
     compare_gated(Y, Z, "bf16", "gated 1000x2048x2*1160, fused tile kernel")
-    Y, used = _run(rl, w, "tile_pre", rows=rows)
-    assert used == "tile_pre"
-    compare_gated(Y, Z, "bf16", "gated 1000x2048x2*1160, two kernels")
+    for tuning in ((0, 0), (1, 1), (1, 4)):          # the library's own split, none, four slabs
+        Y, used = _run(rl, w, "tile_pre", tuning=tuning, rows=rows)
+        assert used == "tile_pre"
+        compare_gated(Y, Z, "bf16", f"gated 1000x2048x2*1160, two kernels {tuning}")
 
 
 def test_gated_hand_case(rl, golden_hand_cases):
@@ -199,7 +200,7 @@ def test_autotune_picks_a_runnable_shape_and_auto_uses_it(rl, M, K, N, gated):
     try:
         us = rl.rl_autotune(X, g, W, w.eps, Y, gated=gated, reps=5)
         variant, n_tile, k_split = rl.rl_autotune_get(M, K, N, torch.bfloat16, gated)
-        assert us > 0 and variant in ("gemv", "skinny", "tile", "naive")
+        assert us > 0 and variant in ("gemv", "skinny", "tile", "tile_pre", "naive")
         print(f"{M}x{K}x{N} gated={gated}: {variant} n_tile={n_tile} k_split={k_split}, {us:.2f} us")
         rl.rl_set_variant("auto")
         Y.fill_(float("nan"))

@@ -175,12 +175,12 @@ def test_skinny_runs_larger_m_in_blocks_of_64_rows(rl, M, K, N, dtype):
 
 
 def test_mid_m_automatic_choice(rl):
-    """Few tile-kernel workgroups: the skinny kernel per 64 rows; many: the tile kernels."""
+    """Above 64 rows the tile kernels (two-kernel form, split over K); from two rows the skinny kernel."""
     w = workloads.make(128, 2048, 2048, "bf16", 1e-5, 4900)
     Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
     Y, used = _run(rl, w, "auto")
-    assert used == "skinny"
-    compare(Y, Z, w.dtype, "auto -> skinny at M = 128")
+    assert used == "tile_pre"
+    compare(Y, Z, w.dtype, "auto -> tile_pre at M = 128")
     w = workloads.make(2, 1024, 2048, "bf16", 1e-5, 4901)
     Y, used = _run(rl, w, "auto")
     assert used == "skinny"
@@ -189,16 +189,18 @@ def test_mid_m_automatic_choice(rl):
 
 # ------------------------------------------------------------------ two-kernel tile variant
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("tuning", [(0, 0), (1, 1), (1, 3), (1, 16)])
 @pytest.mark.parametrize("M,K,N", [(65, 8, 8), (130, 1544, 520), (257, 2056, 264), (300, 4104, 1288),
                                    (70, 16392, 264), (1100, 520, 4104)])
-def test_tile_pre_variant(rl, M, K, N, dtype):
+def test_tile_pre_variant(rl, M, K, N, dtype, tuning):
     """X-hat and 1/rms written by a first kernel, then the tile kernel as a scaled product: every
-    prepass form (1, 2, 4, 8 chunks per thread and the loop), ragged K and N, several tiles."""
+    prepass form (1, 2, 4, 8 chunks per thread and the loop), ragged K and N, several tiles; the
+    product unsplit (1, 1), split over K by the library's own rule (0, 0) or as told (1, slabs)."""
     w = workloads.make(M, K, N, dtype, 1e-5, 4600 + M + K + N, outlier_frac=0.05)
     Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
-    Y, used = _run(rl, w, "tile_pre")
+    Y, used = _run(rl, w, "tile_pre", tuning=tuning)
     assert used == "tile_pre"
-    compare(Y, Z, w.dtype, f"tile_pre {M}x{K}x{N} {dtype}")
+    compare(Y, Z, w.dtype, f"tile_pre {M}x{K}x{N} {dtype} {tuning}")
     Yt, _ = _run(rl, w, "tile")
     # same X-hat rounding and the same product kernel: only the order of the sum of squares differs
     compare(Y, Yt, w.dtype, "tile_pre against tile")
