@@ -50,11 +50,21 @@ def _time_region(fn_enqueue, torch):
     return start.elapsed_time(end), wall
 
 
+def _workload(name):
+    """One of the five configurations by name, or "MxKxN": a bf16 workload of that shape (same recipe)."""
+    import workloads
+    if name in workloads.CONFIG_NAMES:
+        return workloads.config(name)
+    M, K, N = (int(v) for v in name.lower().split("x"))
+    return workloads.make(M, K, N, "bf16", 1e-5, 4242 + M + K + N, name=name, outlier_frac=0.05,
+                          n_check_rows=min(M, 64))
+
+
 def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=True, gated=False, autotune=False):
     import workloads
     from tests.util import compare, compare_gated, to_device, to_host_f64
 
-    w = workloads.config(name)
+    w = _workload(name)
     tdt = {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}[w.dtype]
     abytes = w.algorithmic_bytes
     NY = w.N // 2 if gated else w.N              # gated block: W = [gate | up], Y has H = N/2 columns
@@ -231,7 +241,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="decode")
+    ap.add_argument("--workload", default="decode",
+                    help="decode, tiny, qkv, gateup, prefill, ntrans, or MxKxN (a bf16 workload of that shape)")
     ap.add_argument("--variant", default="auto")
     ap.add_argument("--no-graph", action="store_true", help="enqueue the timed steps one by one")
     ap.add_argument("--others", action="store_true", help="also time the other four configurations")
@@ -271,6 +282,9 @@ def main():
                                     with_cpu=not args.no_cpu)))
         return
     steps = args.steps if args.steps is not None else (20 if name == "prefill" else 200)
+    if args.steps is None and "x" in name and name != "prefill":
+        M, K, N = (int(v) for v in name.lower().split("x"))
+        steps = 20 if 2.0 * M * K * N > 2e11 else 100
     res, w = run_workload(rl, torch, name, steps, args.warmup, args.variant, use_graph=not args.no_graph,
                           gated=args.gated, autotune=args.autotune)
     mem_bound = w.M <= 64

@@ -138,7 +138,7 @@ rl_variant choose_auto(const Problem& p)
 // room for X-hat.
 bool prefers_two_kernels(const Problem& p)
 {
-    return p.fused != 0;
+    return p.fused != 0 || tile_pre_workspace_bytes(p) != 0;   // the plain product: only where it is split over K
 }
 
 // one attempt at one variant; hipErrorInvalidValue = the variant cannot run the shape

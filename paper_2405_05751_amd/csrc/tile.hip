@@ -659,40 +659,42 @@ size_t tile_pre_workspace_bytes(const Problem& p)
 {
     int S, k_slab;
     tile_pre_split(p, &S, &k_slab);
-    return xhat_bytes(p) + rscale_bytes(p) + (S > 1 ? size_t(S) * p.M * p.N * 4 : 0);
+    return (p.fused ? xhat_bytes(p) + rscale_bytes(p) : 0) + (S > 1 ? size_t(S) * p.M * p.N * 4 : 0);
 }
 
 hipError_t launch_tile_pre(const Problem& p, hipStream_t s, const char** why)
 {
-    if (!p.fused) { if (why) *why = "two-kernel tile variant runs the fused blocks only"; return hipErrorInvalidValue; }
-    if (p.gated && p.N % 16 != 0) { if (why) *why = "gated block: tile variant needs H % 8 == 0"; return hipErrorInvalidValue; }
+    if (p.gated && (p.N % 16 != 0 || !p.fused)) { if (why) *why = "gated block: tile variant needs H % 8 == 0"; return hipErrorInvalidValue; }
     if (p.dt == F32 || p.N % 8 != 0 || p.K % 8 != 0) {
         if (why) *why = "tile variants need a 16-bit type, N % 8 == 0 and K % 8 == 0";
         return hipErrorInvalidValue;
     }
-    if (!p.ws_partial) { if (why) *why = "two-kernel tile variant needs the workspace"; return hipErrorInvalidValue; }
-    uint4_t* Xh = reinterpret_cast<uint4_t*>(p.ws_partial);
-    float* rscale = reinterpret_cast<float*>(reinterpret_cast<char*>(p.ws_partial) + xhat_bytes(p));
-    Problem q = p;                           // the product of X-hat, scaled per row
-    q.X = Xh; q.g = nullptr; q.fused = 0; q.rscale = rscale;
-    const char* w2 = nullptr;
-    // check that the second kernel can run before the first is launched: both or neither
+    // check that the later kernels can run before the first is launched: all or none
     if (int64_t(p.K) * p.N * 2 >= (int64_t(1) << 31) || int64_t(256) * p.K * 2 >= (int64_t(1) << 31)) {
         if (why) *why = "tile variant needs K*N < 2^30";
         return hipErrorInvalidValue;
     }
-    if (p.dt == F16) xhat_rows_go<Fp16>(p, Xh, rscale, s);
-    else             xhat_rows_go<Bf16>(p, Xh, rscale, s);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
     int S, k_slab;
     tile_pre_split(p, &S, &k_slab);
-    if (S > 1) {
-        float* part = reinterpret_cast<float*>(reinterpret_cast<char*>(rscale) + rscale_bytes(p));
-        return launch_tile_split(q, S, k_slab, part, s);
+    if ((p.fused || S > 1) && !p.ws_partial) { if (why) *why = "two-kernel tile variant needs the workspace"; return hipErrorInvalidValue; }
+    Problem q = p;                           // the product, scaled per row if it is the fused block's
+    float* part = p.ws_partial;
+    if (p.fused) {
+        uint4_t* Xh = reinterpret_cast<uint4_t*>(p.ws_partial);
+        float* rscale = reinterpret_cast<float*>(reinterpret_cast<char*>(p.ws_partial) + xhat_bytes(p));
+        part = reinterpret_cast<float*>(reinterpret_cast<char*>(rscale) + rscale_bytes(p));
+        q.X = Xh; q.g = nullptr; q.fused = 0; q.rscale = rscale;
+        if (p.dt == F16) xhat_rows_go<Fp16>(p, Xh, rscale, s);
+        else             xhat_rows_go<Bf16>(p, Xh, rscale, s);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    } else {
+        q.rscale = nullptr;                  // the plain product (matmul): no first kernel, only the split
     }
+    if (S > 1) return launch_tile_split(q, S, k_slab, part, s);
     if (p.n_tile == 1) { q.n_tile = 0; q.k_split = 0; }   // the override was for the split only
-    e = launch_tile(q, s, &w2);
+    const char* w2 = nullptr;
+    hipError_t e = launch_tile(q, s, &w2);
     if (e != hipSuccess && why && w2) *why = w2;
     return e;
 }

@@ -359,6 +359,18 @@ def test_unfused_pair(rl, name):
     print(f"{name}: unfused pair max|err|/rms(Y) = {ratio:.3e}")
 
 
+@pytest.mark.parametrize("M,K,N", [(65, 1032, 264), (130, 1544, 520), (300, 4104, 1288), (1100, 520, 4104)])
+def test_plain_product_with_few_tiles_is_split_over_k(rl, M, K, N):
+    import torch
+    w = workloads.make(M, K, N, "bf16", 1e-5, 5100 + M + K + N)
+    X, _, W = upload(w)
+    Y = rl.matmul(X, W)
+    torch.cuda.synchronize()
+    tiles = -(-M // 256) * -(-N // 256)
+    assert rl.rl_last_variant() == ("tile_pre" if tiles <= 128 and K >= 512 else "tile")
+    compare(to_host_f64(Y, "bf16"), oracle.matmul(w.X, w.W, "bf16"), "bf16", f"matmul {M}x{K}x{N}")
+
+
 @pytest.mark.parametrize("M,K", [(1, 8), (3, 100), (5, 4096), (2, 16384), (4, 20000)])
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
 def test_rmsnorm_shapes(rl, M, K, dtype):
