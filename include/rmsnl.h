@@ -53,8 +53,8 @@ typedef enum {
 } rl_variant;
 
 /*
- * Fused RMSNorm + MatMul in one kernel (case-study section: Eq. 1 followed by the
- * MatMul of Fig. 2a, computed in the reordered form of Fig. 2b):
+ * Fused RMSNorm + MatMul (case-study section: Eq. 1 followed by the MatMul of Fig. 2a, computed in
+ * the reordered form of Fig. 2b; one kernel up to M = 64, see rl_variant for larger M):
  *
  *     A_i  = sum_k X[i][k]^2                      (accumulated in the same K loop as B)
  *     B_in = sum_k (X[i][k] * g[k]) * W[k][n]
@@ -63,7 +63,7 @@ typedef enum {
  * eps is added to the mean square under the root (eps = 0 gives Eq. 1 exactly).
  * An all-zero row with eps = 0 yields NaN, as the definition does.
  * May use the library workspace (see rl_set_workspace): calls that overlap in time on
- * different streams of one device must not both use the split-K variant.
+ * different streams of one device must not both use it (rl_workspace_bytes() > 0).
  */
 rl_status rmsnorm_linear(const void* X, const void* g, const void* W, float eps, void* Y,
                          int64_t M, int64_t K, int64_t N, rl_dtype dt, void* stream);
@@ -173,12 +173,15 @@ rl_status rl_ff_rmsnorm_linear(const void* X, const void* g, const void* W, void
                                int64_t M, int64_t K, int64_t N, uint32_t p, int reordered, void* stream);
 
 /*
- * Split-K workspace (fp32 partial sums + arrival counters).  By default the library
- * allocates rl_workspace_default_bytes() once per device on first need and keeps it until
- * the process ends.  rl_set_workspace lends a caller-owned DEVICE buffer instead (for the
- * current device; bytes must be >= rl_workspace_bytes() of every later call; the first
- * 256 KiB must be zero when lent); NULL returns to the library's own buffer.
- * rl_workspace_bytes gives the bytes a call of that shape needs (0 if none).
+ * Workspace (split-K partial sums + arrival counters; X (.) g, 1/rms and partial tiles of the two-kernel
+ * tile form).  By default the library allocates rl_workspace_default_bytes() per device on first need,
+ * replaces it by a larger one (up to 4 GiB) when a call needs more -- freeing the old one waits for the
+ * device, and nothing is allocated while the call's stream is being captured into a graph: run the shape
+ * once before capturing, or lend a buffer -- and keeps it until the process ends.  rl_set_workspace lends a
+ * caller-owned DEVICE buffer instead (for the current device; the first 256 KiB must be zero when lent);
+ * NULL returns to the library's own buffer.  With a lent buffer too small for a call, the split-K variants
+ * return RL_ERR_WORKSPACE; the two-kernel tile form is then skipped by RL_AUTO (the fused tile kernel runs).
+ * rl_workspace_bytes gives the bytes an rmsnorm_linear call of that shape would like (0 if none).
  */
 rl_status rl_set_workspace(void* dev_ptr, size_t bytes);
 size_t rl_workspace_bytes(int64_t M, int64_t K, int64_t N, rl_dtype dt);
