@@ -1,4 +1,5 @@
-// Matrix-core variant of the fused RMSNorm + MatMul for small M (M <= 64): still bound by streaming
+// Matrix-core variant of the fused RMSNorm + MatMul for small M (up to 64 rows per launch; more
+// rows run launch after launch): still bound by streaming
 // W once from HBM, but each W element now meets up to 64 rows of X-hat, which plain FMAs could not
 // keep up with.  One v_mfma_f32_16x16x32 per 16 rows x 16 columns x 32 k.
 //
@@ -10,12 +11,14 @@
 // rows of 256 contiguous bytes).  For each of the 8 columns c of the block, the B operand of MFMA
 // #c is the column of that register block -- four v_perm_b32 pick it out -- and MFMA #c as a whole
 // computes the 16 strided columns {n0 + 8i + c}.  The A operand of lane (m, q) is
-// X-hat[m][kb + 8q .. +7]: one 16-byte load of X, times g, rounded once to the 16-bit type;
-// the squares of the raw X feed A_i in the same pass (the paper's two accumulators in one K loop).
+// X-hat[m][kb + 8q .. +7]: X times g, rounded once to the 16-bit type; the squares of the raw X
+// feed A_i in the same pass (the paper's two accumulators in one K loop).  X itself is loaded as
+// whole 128-byte lines and turned into that layout through the wave's own piece of LDS (see the
+// kernel).
 //
 // A workgroup owns 128 columns and one K slab; its NW waves take alternate 64-row runs of the
-// slab, two 32-row steps each, so nothing in the K loop needs a barrier.  The waves' fp32 tiles meet in LDS, and the
-// common split-K epilogue finishes (see splitk.hpp).
+// slab, two 32-row steps each, so nothing in the K loop needs a barrier.  The waves' fp32 tiles
+// meet in LDS, and the common split-K epilogue finishes (see splitk.hpp).
 #include <algorithm>
 #include "common.hpp"
 #include "splitk.hpp"
@@ -54,7 +57,8 @@ template <> struct Mfma16<Fp16> {
     }
 };
 
-// steps (8 W loads per lane each) kept in flight per wave
+// steps (8 W loads per lane each) kept in flight per wave; X is fetched one run ahead (two runs
+// ahead measured 1 % slower at M <= 16)
 constexpr int skinny_depth(int MB) { return MB == 1 ? 4 : 3; }
 constexpr int skinny_waves(int MB) { return 4; }    // 8 (two waves per SIMD, MB <= 2 only) measured no faster
 

@@ -49,12 +49,7 @@ def _run(rl, w, variant="auto", tuning=(0, 0), rows=None):
     return to_host_f64(Y, w.dtype), used
 
 
-NOT_BUILT = set()                    # variants whose kernels have not landed yet
-
-
 def _supported(variant, w):
-    if variant in NOT_BUILT:
-        return False
     if variant == "auto":
         return True
     if variant == "naive":
@@ -306,10 +301,8 @@ def test_zero_row_nan_positions(rl):
 
 # ------------------------------------------------------------------ determinism and memory safety
 @pytest.mark.parametrize("name,variant", [("decode", "gemv"), ("qkv", "gemv"), ("qkv", "skinny"),
-                                          ("gateup", "skinny"), ("tiny", "tile")])
+                                          ("gateup", "skinny"), ("tiny", "tile"), ("tiny", "tile_pre")])
 def test_bit_reproducible(rl, name, variant):
-    if variant in NOT_BUILT:
-        pytest.skip(f"{variant} not built")
     w, _ = _workload(name)
     Y1, _ = _run(rl, w, variant)
     for _ in range(3):
