@@ -40,8 +40,8 @@ typedef enum {
 typedef enum { RL_F16 = 0, RL_BF16 = 1, RL_F32 = 2 } rl_dtype;
 
 typedef enum {
-    RL_AUTO = 0,          /* pick by shape: M = 1 GEMV; M <= 64 skinny; above that the two-kernel tile form, or the
-                             fused tile kernel when the workspace has no room for it */
+    RL_AUTO = 0,          /* pick by shape: M = 1 and N < 16384 GEMV; M <= 64 skinny; above that the two-kernel tile
+                             form, or the fused tile kernel when the workspace has no room for it */
     RL_GEMV_SPLITK = 1,   /* M <= 16, no matrix cores, K split over workgroups */
     RL_MFMA_SKINNY = 2,   /* matrix cores, 64 rows per launch (M <= 1024: one launch after the other), K split
                              over the waves of a workgroup and over workgroups */

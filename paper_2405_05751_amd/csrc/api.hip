@@ -124,7 +124,9 @@ rl_variant choose_auto(const Problem& p)
     if (p.dt == F32) return RL_NAIVE;
     if (p.N % 8 != 0 || p.K % 8 != 0) return RL_NAIVE;
     if (p.gated && p.N % 16 != 0) return RL_NAIVE;
-    if (p.M == 1) return RL_GEMV_SPLITK;     // from two rows on the matrix-core kernel is faster
+    // one row: the GEMV kernel is ahead by 2 to 8 % while W needs a split over K to fill the chip
+    // (N < 16384); without a split, and from two rows on, the matrix-core kernel is faster
+    if (p.M == 1 && p.N < 16384) return RL_GEMV_SPLITK;
     if (p.M <= 64) return RL_MFMA_SKINNY;
     // (the skinny kernel can run larger M block after block; the tile kernels, split over K when
     // their tiles are few, measured faster from M = 65 on)

@@ -121,18 +121,22 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
 
     uint4_t w[D][8];                         // D steps of W in flight
     uint4_t xr[2 * MB], gr;                  // the next run of X (and g), as lines
-    // load j of a run takes row 8j + r8 of X, if there is one (8 j < rlim)
+    // Load j of a run takes row 8j + r8 of X.  Where there is no such row (8 j >= rlim) it takes the
+    // last row again: an instruction whose lanes are partly out of range is slow (the 4096 x 28672
+    // shape ran 20 % slower at M = 2 and 4 than at M = 8 with zeros read there), the repeated line
+    // costs nothing, and nothing computed from those rows is ever stored.
     const int rlim = a.M - r8;
     const int xlane = r8 * a.K * 2;          // used only where r8 < M
+    const int xlast = (a.M - 1) * a.K * 2;
     auto issue_x = [&](int t) {
         const int kr = (NW * t + wave) * 64 + c8 * 8;               // slab-relative k of this lane's chunk
         const int koff = (k0 + kr) * 2;
-        const int rl = kr < klen ? rlim : 0;                        // no k, no rows
-        if (FUSED) gr = __builtin_amdgcn_raw_buffer_load_b128(grs, (r8 == 0 && kr < klen) ? koff : kSkOut, 0, 0);
+        const bool kin = kr < klen;
+        if (FUSED) gr = __builtin_amdgcn_raw_buffer_load_b128(grs, (r8 == 0 && kin) ? koff : kSkOut, 0, 0);
 #pragma unroll
         for (int j = 0; j < 2 * MB; ++j)
             xr[j] = __builtin_amdgcn_raw_buffer_load_b128(
-                xrs, 8 * j < rl ? koff + xlane + 8 * j * a.K * 2 : kSkOut, 0, 0);
+                xrs, kin ? koff + (8 * j < rlim ? xlane + 8 * j * a.K * 2 : xlast) : kSkOut, 0, 0);
     };
     auto issue_w = [&](int s, int d) {
         const int t = s >> 1, h = s & 1;
@@ -282,9 +286,12 @@ static SkinnyPlan skinny_plan(const Problem& p)
     const int gran = 64 * skinny_waves(pl.MB);
     int n_tile = p.n_tile, S = p.k_split;
     if (n_tile == 0 || S <= 0) {
-        // Pick the tile width and slab count with a small cost model: W streams at the rate a grid
-        // of that size can pull (whole rounds of 256 compute units), and every extra slab costs the
-        // split-K epilogue's latency plus a write and a read of an fp32 partial tile set.
+        // Pick the slab count with a small cost model.  W streams at the HBM rate this kernel
+        // reaches (5.7 TB/s) unless the compute units holding workgroups cannot pull their share
+        // of W plus their slab of X that fast (about 36 GB/s each in this kernel; with more
+        // workgroups than units some units hold several, one after the other as far as the
+        // stream is concerned); every extra slab costs the split-K epilogue's latency plus a
+        // write and a read of an fp32 partial tile set.
         double best = 1e30;
         int best_nt = kSkinnyTile, best_s = 1;
         // (narrower tiles measured slower: their row segments stop being whole 128-byte lines, so
@@ -295,10 +302,11 @@ static SkinnyPlan skinny_plan(const Problem& p)
                 if (s > 1 && 2 * s * gran > p.K) break;
                 if (tiles > kMaxCounters || int64_t(tiles) * s * kSumsqStride > kMaxSumsqFloats) continue;
                 if (s > 1 && int64_t(s) * p.M * p.N * 4 > (int64_t(48) << 20)) continue;   // fits the library workspace
+                const double bytes = double(p.K) * p.N * 2.0;
                 const double wgs = double(tiles) * s;
-                const double rounds = double((int64_t(wgs) + 255) / 256);
-                const double fill = wgs / (rounds * 256.0);
-                const double stream_us = double(p.K) * p.N * 2.0 / (5.0e6 * fill);          // 5 TB/s when full
+                const double wg_bytes = (double(p.K) / s) * (nt * 2.0 + p.M * 2.0);         // its W and its X
+                const double per_unit = double((int64_t(wgs) + 255) / 256) * wg_bytes / 36.0e3;
+                const double stream_us = std::max(bytes / 5.7e6, per_unit);
                 const double tail_us = s > 1 ? 3.0 + 2.0 * s * double(p.M) * p.N * 4.0 / 2.0e6 : 0.5;
                 const double t = stream_us + tail_us;
                 if (t < best) { best = t; best_nt = nt; best_s = s; }
