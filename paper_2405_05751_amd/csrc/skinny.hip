@@ -122,9 +122,9 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
     uint4_t w[D][8];                         // D steps of W in flight
     uint4_t xr[2 * MB], gr;                  // the next run of X (and g), as lines
     // Load j of a run takes row 8j + r8 of X.  Where there is no such row (8 j >= rlim) it takes the
-    // last row again: an instruction whose lanes are partly out of range is slow (the 4096 x 28672
-    // shape ran 20 % slower at M = 2 and 4 than at M = 8 with zeros read there), the repeated line
-    // costs nothing, and nothing computed from those rows is ever stored.
+    // last row again: the repeated line costs nothing, nothing computed from those rows is ever
+    // stored, and no instruction has part of its lanes out of range (measured the same as reading
+    // zeros there).
     const int rlim = a.M - r8;
     const int xlane = r8 * a.K * 2;          // used only where r8 < M
     const int xlast = (a.M - 1) * a.K * 2;
