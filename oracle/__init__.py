@@ -48,6 +48,9 @@ def _load():
         lib.oracle_ntrans.restype = ctypes.c_int
         lib.oracle_ntrans.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
                                       ctypes.c_double, ctypes.c_long, ctypes.c_long, ctypes.c_void_p]
+        lib.oracle_qknorm_attention.restype = ctypes.c_int
+        lib.oracle_qknorm_attention.argtypes = [ctypes.c_void_p] * 7 + [ctypes.c_int, ctypes.c_double] + \
+            [ctypes.c_long] * 4 + [ctypes.c_void_p]
         lib.oracle_silu_mul_f64.restype = None
         lib.oracle_silu_mul_f64.argtypes = [ctypes.c_void_p, ctypes.c_long, ctypes.c_long, ctypes.c_void_p]
         _lib = lib
@@ -168,6 +171,23 @@ def ntrans(X, Hh, alpha, dtype: str, eps: float) -> np.ndarray:
                              Y.ctypes.data) != 0:
         raise RuntimeError("oracle_ntrans rejected its arguments")
     return Y
+
+
+def qknorm_attention(Q, K, V, gq, bq, gk, bk, dtype: str, eps: float) -> np.ndarray:
+    """LayerNorm of the query and of every key, then attention, one query per (sample, head), on
+    storage-typed inputs: Q [B, H, D], K and V [B, H, S, D], gains and biases [D]; float64 [B, H, D]."""
+    Q = _storage(Q, dtype); K = _storage(K, dtype); V = _storage(V, dtype)
+    gq = _storage(gq, dtype); bq = _storage(bq, dtype); gk = _storage(gk, dtype); bk = _storage(bk, dtype)
+    B, H, D = Q.shape
+    S = K.shape[2]
+    if K.shape != (B, H, S, D) or V.shape != (B, H, S, D) or any(v.shape != (D,) for v in (gq, bq, gk, bk)):
+        raise ValueError("shape mismatch")
+    O = np.empty((B, H, D), dtype=np.float64)
+    if _load().oracle_qknorm_attention(Q.ctypes.data, K.ctypes.data, V.ctypes.data, gq.ctypes.data, bq.ctypes.data,
+                                       gk.ctypes.data, bk.ctypes.data, _DT[dtype], float(eps), B, H, S, D,
+                                       O.ctypes.data) != 0:
+        raise RuntimeError("oracle_qknorm_attention rejected its arguments")
+    return O
 
 
 # ---------------------------------------------------------------------------------------------

@@ -37,6 +37,15 @@
  * paper does not say which normalisation "Norm" is; it is taken to be the only one the paper
  * defines, Eq. 1 without a gain (divide by the root of the mean square, eps under the root).
  *
+ * QKNorm in front of attention (the paper's QKNorm benchmark: layer normalisation of the query and
+ * key vectors before attention), decode form, one query per head: oracle_qknorm_attention takes it
+ * literally -- LayerNorm of q, LayerNorm of every key, scores, softmax, weighted sum of V.
+ * Readings: "layer normalization" is the usual one (subtract the mean, divide by the root of the
+ * population variance plus eps, times a gain, plus a bias; gain and bias of length D, shared by the
+ * heads); scores are scaled by 1/sqrt(D); the paper gives no eps.
+ * Pins (tests/test_qknorm_pins.py): a D = 2 closed form, shift and scale invariance, uniform
+ * attention for equal keys and for a zero key gain, library layer_norm + attention in float64.
+ *
  * Parity pins (tests/test_oracle_*.py): printed-by-hand 2x3 cases, the
  * eps-placement case, exact rational brute force, scale invariance, unit-RMS
  * rows, linearity, and a library float64 product; for the gate: closed forms
@@ -287,6 +296,88 @@ int oracle_ntrans(const void *X, const void *Hh, const void *A, int dtype, doubl
         }
         free(d);
         free(u);
+    }
+    return failed ? -1 : 0;
+}
+
+/* v[0..D) -> (v - mean) / sqrt(var + eps) * gain + bias, population variance. */
+static void layer_norm_row(const double *v, const void *gain, const void *bias, int dtype, double eps,
+                           long D, double *out)
+{
+    double mean = 0.0;
+    for (long j = 0; j < D; ++j)
+        mean += v[j];
+    mean /= (double)D;
+    double var = 0.0;
+    for (long j = 0; j < D; ++j)
+        var += (v[j] - mean) * (v[j] - mean);
+    var /= (double)D;
+    double r = sqrt(var + eps);
+    for (long j = 0; j < D; ++j)
+        out[j] = (v[j] - mean) / r * load_elem(gain, (size_t)j, dtype) + load_elem(bias, (size_t)j, dtype);
+}
+
+/*
+ * QKNorm + attention, one query per (sample, head): Q [B][H][D], K and V [B][H][S][D], gains and
+ * biases [D], O [B][H][D] doubles:
+ *   qn = LayerNorm(q; gq, bq), kn_t = LayerNorm(k_t; gk, bk), s_t = qn . kn_t / sqrt(D),
+ *   p = softmax_t(s), o = sum_t p_t v_t.
+ * Returns 0, or -1 on a bad argument.
+ */
+int oracle_qknorm_attention(const void *Q, const void *K, const void *V, const void *gq, const void *bq,
+                            const void *gk, const void *bk, int dtype, double eps,
+                            long B, long H, long S, long D, double *O)
+{
+    if (!Q || !K || !V || !gq || !bq || !gk || !bk || !O || B <= 0 || H <= 0 || S <= 0 || D <= 0)
+        return -1;
+    if (dtype != ORACLE_F16 && dtype != ORACLE_BF16 && dtype != ORACLE_F32)
+        return -1;
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *raw = (double *)malloc(sizeof(double) * (size_t)D);
+        double *qn = (double *)malloc(sizeof(double) * (size_t)D);
+        double *kn = (double *)malloc(sizeof(double) * (size_t)D);
+        double *sc = (double *)malloc(sizeof(double) * (size_t)S);
+        if (!raw || !qn || !kn || !sc) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(static)
+        for (long bh = 0; bh < B * H; ++bh) {
+            if (!raw || !qn || !kn || !sc)
+                continue;
+            for (long j = 0; j < D; ++j)
+                raw[j] = load_elem(Q, (size_t)bh * D + j, dtype);
+            layer_norm_row(raw, gq, bq, dtype, eps, D, qn);
+            double top = -INFINITY;
+            for (long t = 0; t < S; ++t) {
+                for (long j = 0; j < D; ++j)
+                    raw[j] = load_elem(K, ((size_t)bh * S + t) * D + j, dtype);
+                layer_norm_row(raw, gk, bk, dtype, eps, D, kn);
+                double dot = 0.0;
+                for (long j = 0; j < D; ++j)
+                    dot += qn[j] * kn[j];
+                sc[t] = dot / sqrt((double)D);
+                if (sc[t] > top)
+                    top = sc[t];
+            }
+            double denom = 0.0;
+            for (long t = 0; t < S; ++t) {
+                sc[t] = exp(sc[t] - top);
+                denom += sc[t];
+            }
+            for (long j = 0; j < D; ++j) {
+                double acc = 0.0;
+                for (long t = 0; t < S; ++t)
+                    acc += sc[t] / denom * load_elem(V, ((size_t)bh * S + t) * D + j, dtype);
+                O[(size_t)bh * D + j] = acc;
+            }
+        }
+        free(raw);
+        free(qn);
+        free(kn);
+        free(sc);
     }
     return failed ? -1 : 0;
 }

@@ -139,3 +139,27 @@ def config_shape(name_or_index):
     """(name, M, K, N, dtype, eps) without drawing anything."""
     idx = CONFIG_NAMES.index(name_or_index) if isinstance(name_or_index, str) else int(name_or_index)
     return _CONFIGS[idx][:6]
+
+
+def make_attention(B: int, H: int, S: int, D: int, dtype: str, seed: int):
+    """Inputs of the QKNorm-before-attention workload, one query per (sample, head): Q [B, H, D],
+    K and V [B, H, S, D] (a key-value cache of S positions), LayerNorm gains ~ U(0.5, 1.5) and
+    biases ~ N(0, 0.1) of length D for queries and keys.  Keys and queries get a per-vector offset
+    and scale (N(0, 1) and U(0.5, 2)), so that the normalisation has something to remove.
+    Returns a dict of storage-typed arrays; draws in the order Q, K, V, gq, bq, gk, bk."""
+    rng = np.random.default_rng(seed)
+    def vectors(*shape):
+        v = rng.standard_normal(shape + (D,), dtype=np.float32)
+        v *= rng.uniform(0.5, 2.0, shape + (1,)).astype(np.float32)
+        v += rng.standard_normal(shape + (1,), dtype=np.float32)
+        return v
+    Q = vectors(B, H)
+    K = vectors(B, H, S)
+    V = rng.standard_normal((B, H, S, D), dtype=np.float32)
+    gq = rng.uniform(0.5, 1.5, D).astype(np.float32)
+    bq = (rng.standard_normal(D, dtype=np.float32) * np.float32(0.1))
+    gk = rng.uniform(0.5, 1.5, D).astype(np.float32)
+    bk = (rng.standard_normal(D, dtype=np.float32) * np.float32(0.1))
+    arrays = dict(Q=Q, K=K, V=V, gq=gq, bq=bq, gk=gk, bk=bk)
+    return {k: to_storage(v, dtype) for k, v in arrays.items()}
+
