@@ -159,6 +159,26 @@ rl_status rl_autotune_get(int64_t M, int64_t K, int64_t N, rl_dtype dt, int gate
 void rl_autotune_clear(void);
 
 /*
+ * QKNorm in front of attention (the paper's QKNorm benchmark: layer normalisation of the query and key
+ * vectors before attention, in one kernel with the attention), decode form: one query per (sample,
+ * head) against S cached positions.  DEVICE arrays, row-major: Q [B][H][D], K and V [B][H][S][D],
+ * gq, bq, gk, bk [D] (gain and bias of the two layer normalisations, shared by the heads), O [B][H][D]:
+ *
+ *     LayerNorm(v; g, b)_d = (v_d - mean(v)) / sqrt(var(v) + eps) * g_d + b_d      (population variance)
+ *     qn = LayerNorm(q; gq, bq),  kn_t = LayerNorm(k_t; gk, bk),  s_t = qn . kn_t / sqrt(D)
+ *     O = sum_t softmax(s)_t v_t
+ *
+ * The paper names the operation but not its constants: the usual layer normalisation, the usual
+ * 1/sqrt(D), eps as given.  Fast path: D = 128 and a 16-bit type (keys read once, their mean, variance
+ * and dot product from the same registers, online softmax, the sequence split over workgroups); any
+ * other D (<= 4096) or type runs a slow plain kernel.  May use the library workspace like
+ * rmsnorm_linear.  Pointers 16-byte aligned; O must not overlap the inputs.
+ */
+rl_status rl_qknorm_attention(const void* Q, const void* K, const void* V, const void* gq, const void* bq,
+                              const void* gk, const void* bk, float eps, void* O,
+                              int64_t B, int64_t H, int64_t S, int64_t D, rl_dtype dt, void* stream);
+
+/*
  * The block over a prime field, for the paper's way of certifying a rewrite (random tests over
  * finite fields, Table 3: add, mul, div and sqrt as modular operations): X [M][K], g [K], W [K][N],
  * Y [M][N] are DEVICE arrays of uint32 with entries in [0, p), p a prime in [3, 32749] that does not

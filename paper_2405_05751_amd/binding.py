@@ -36,6 +36,8 @@ EXPORTS = {
     "rmsnorm_gated_mlp": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
                                          ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                          ctypes.c_int, ctypes.c_void_p]),
+    "rl_qknorm_attention": (ctypes.c_int, [ctypes.c_void_p] * 7 + [ctypes.c_float, ctypes.c_void_p] +
+                            [ctypes.c_int64] * 4 + [ctypes.c_int, ctypes.c_void_p]),
     "silu_mul": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                 ctypes.c_int, ctypes.c_void_p]),
     "rl_autotune": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
@@ -213,6 +215,23 @@ def rl_ntrans(X: torch.Tensor, Hh: torch.Tensor, alpha: torch.Tensor, eps: float
     _check(lib().rl_ntrans(_dev(X, "X"), _dev(Hh, "H"), _dev(alpha, "alpha"), float(eps), _dev(Y, "Y"), M, D,
                            _DTYPES[X.dtype], _stream(stream)))
     return Y
+
+
+def rl_qknorm_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, gq: torch.Tensor, bq: torch.Tensor,
+                        gk: torch.Tensor, bk: torch.Tensor, eps: float, O: Optional[torch.Tensor] = None,
+                        stream=None) -> torch.Tensor:
+    """LayerNorm of the query and of every key, then attention: Q [B, H, D], K and V [B, H, S, D] -> O [B, H, D]."""
+    B, H, D = Q.shape
+    S = K.shape[2]
+    if K.shape != (B, H, S, D) or V.shape != (B, H, S, D) or any(t.shape != (D,) for t in (gq, bq, gk, bk)) \
+            or any(t.dtype != Q.dtype for t in (K, V, gq, bq, gk, bk)):
+        raise ValueError("shape or dtype mismatch")
+    if O is None:
+        O = torch.empty_like(Q)
+    _check(lib().rl_qknorm_attention(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(gq, "gq"), _dev(bq, "bq"),
+                                     _dev(gk, "gk"), _dev(bk, "bk"), float(eps), _dev(O, "O"), B, H, S, D,
+                                     _DTYPES[Q.dtype], _stream(stream)))
+    return O
 
 
 def rl_ff_rmsnorm_linear(X: torch.Tensor, g: torch.Tensor, W: torch.Tensor, p: int, reordered: bool,

@@ -405,6 +405,30 @@ rl_status rl_ntrans(const void* X, const void* H, const void* alpha, float eps, 
     return RL_OK;
 }
 
+rl_status rl_qknorm_attention(const void* Q, const void* K, const void* V, const void* gq, const void* bq,
+                              const void* gk, const void* bk, float eps, void* O,
+                              int64_t B, int64_t H, int64_t S, int64_t D, rl_dtype dt, void* stream)
+{
+    if (!Q || !K || !V || !gq || !bq || !gk || !bk || !O) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (dt != RL_F16 && dt != RL_BF16 && dt != RL_F32) return fail(RL_ERR_INVALID_ARG, "unknown dtype");
+    if (B < 1 || H < 1 || S < 1 || D < 1 || B * H > (int64_t(1) << 24) || S > (int64_t(1) << 22) || D > 4096)
+        return fail(RL_ERR_INVALID_ARG, "need 1 <= B*H <= 2^24, 1 <= S <= 2^22, 1 <= D <= 4096");
+    if (!std::isfinite(eps) || eps < 0.f) return fail(RL_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    for (const void* ptr : {Q, K, V, gq, bq, gk, bk, (const void*)O})
+        if (!aligned16(ptr)) return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float* ws = nullptr;
+    const size_t need = qkattn_workspace_bytes(B, H, S, D, DType(dt));
+    if (need) {
+        Workspace w;
+        if (rl_status st = get_workspace(need, s, &w)) return st;
+        ws = reinterpret_cast<float*>(static_cast<char*>(w.ptr) + kHeadBytes);
+    }
+    hipError_t e = launch_qkattn(Q, K, V, gq, bq, gk, bk, eps, O, B, H, S, D, DType(dt), ws, s);
+    if (e != hipSuccess) return fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+    return RL_OK;
+}
+
 rl_status rl_ff_rmsnorm_linear(const void* X, const void* g, const void* W, void* Y,
                                int64_t M, int64_t K, int64_t N, uint32_t p, int reordered, void* stream)
 {
