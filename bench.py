@@ -211,6 +211,68 @@ def run_ntrans(rl, torch, steps, warmup, M=16384, D=2048, dtype="bf16", with_cpu
     return out
 
 
+def run_qknorm(rl, torch, steps, warmup, B=8, H=32, S=4096, D=128, dtype="bf16", with_cpu=True):
+    """QKNorm in front of attention, decode form, on a seeded key-value cache: 32 heads of 128, 4K
+    context (the paper's QKNorm setting: Chameleon-7B's attention shape and context length)."""
+    import oracle
+    import workloads
+    from tests.util import to_device, to_host_f64
+    c = workloads.make_attention(B, H, S, D, dtype, 240505751 + 13)
+    eps = float(np.float32(1e-5))
+    abytes = 2 * (2 * B * H * S * D + 2 * B * H * D + 4 * D)
+    copies = max(2, -(-(2 * ROTATE_BYTES) // abytes))   # at least 1 GiB of keys and values in rotation
+    dev = {k: to_device(v, dtype) for k, v in c.items()}
+    Ks = [dev["K"]] + [dev["K"].clone() for _ in range(copies - 1)]
+    Vs = [dev["V"]] + [dev["V"].clone() for _ in range(copies - 1)]
+    Os = [torch.empty_like(dev["Q"]) for _ in range(copies)]
+    step = lambda i: rl.rl_qknorm_attention(dev["Q"], Ks[i % copies], Vs[i % copies], dev["gq"], dev["bq"],
+                                            dev["gk"], dev["bk"], eps, Os[i % copies])
+    for i in range(max(warmup, 1)):
+        step(i)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for i in range(steps):
+            step(i)
+    graph.replay(); torch.cuda.synchronize()
+    ev_ms, _ = min((_time_region(graph.replay, torch) for _ in range(3)), key=lambda t: t[0])
+    us = ev_ms / steps * 1e3
+    nb = min(B, 2)                                   # parity on the first samples
+    want = oracle.qknorm_attention(c["Q"][:nb], c["K"][:nb], c["V"][:nb], c["gq"], c["bq"], c["gk"], c["bk"], dtype, eps)
+    got = to_host_f64(Os[0][:nb].contiguous(), dtype)
+    parity = float((np.abs(got - want).max(-1) / np.sqrt((want ** 2).mean(-1))).max())
+    assert parity <= 2e-2, f"qknorm attention: max|err|/rms = {parity:.3e}"
+    # the unfused baseline the paper describes (normalisation kernels, then an attention kernel), from the
+    # vendor stack behind torch: for context only
+    import torch.nn.functional as F
+    def unfused():
+        qn = F.layer_norm(dev["Q"], (D,), dev["gq"], dev["bq"], eps)
+        kn = F.layer_norm(dev["K"], (D,), dev["gk"], dev["bk"], eps)
+        return F.scaled_dot_product_attention(qn.unsqueeze(2), kn, dev["V"])
+    for _ in range(3):
+        unfused()
+    torch.cuda.synchronize()
+    t_ms, _ = min((_time_region(lambda: [unfused() for _ in range(10)], torch) for _ in range(3)), key=lambda t: t[0])
+    out = {"metric": "QKNorm + attention TB/s", "value": abytes / us / 1e6, "unit": "TB/s", "n_gpus": 1, "steps": steps,
+           "warmup": warmup, "ms_per_step": us / 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": dtype, "data": "synthetic",
+           "config": {"workload": f"qknorm: Q {B}x{H}x{D}, K and V {B}x{H}x{S}x{D}, {dtype}", "copies_rotated": copies},
+           "roofline": {"bound": "hbm", "achieved": abytes / us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": abytes / us / 1e3 / HBM_PEAK_GBS, "traffic": None, "kernel": "qkattn_kernel",
+                        "us_per_launch": us},
+           "detail": {"us_per_step": us, "algorithmic_bytes": abytes, "max_err_over_rms": parity,
+                      "us_per_step_torch_unfused_one_buffer": t_ms / 10 * 1e3}}
+    if with_cpu:
+        t0, reps = time.perf_counter(), 0
+        while time.perf_counter() - t0 < 10.0 and reps < 200:
+            oracle.qknorm_attention(c["Q"][:1], c["K"][:1], c["V"][:1], c["gq"], c["bq"], c["gk"], c["bk"], dtype, eps)
+            reps += 1
+        sec = (time.perf_counter() - t0) / reps
+        out["cpu_baseline"] = {"value": abytes / B / sec / 1e12, "unit": "TB/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": f"{reps} run(s) of the fp64 oracle on 1 of {B} samples, {sec:.4f} s each"}
+    return out
+
+
 def cpu_baseline(w, mem_bound, budget_s=12.0):
     """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
     import oracle
@@ -242,7 +304,8 @@ def main():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="decode",
-                    help="decode, tiny, qkv, gateup, prefill, ntrans, or MxKxN (a bf16 workload of that shape)")
+                    help="decode, tiny, qkv, gateup, prefill, ntrans, qknorm (batch 8; qknorm1, qknorm16), "
+                         "or MxKxN (a bf16 workload of that shape)")
     ap.add_argument("--variant", default="auto")
     ap.add_argument("--no-graph", action="store_true", help="enqueue the timed steps one by one")
     ap.add_argument("--others", action="store_true", help="also time the other four configurations")
@@ -279,6 +342,11 @@ def main():
     name = args.workload
     if name == "ntrans":
         print(json.dumps(run_ntrans(rl, torch, args.steps if args.steps is not None else 100, args.warmup,
+                                    with_cpu=not args.no_cpu)))
+        return
+    if name in ("qknorm", "qknorm1", "qknorm16"):
+        B = {"qknorm": 8, "qknorm1": 1, "qknorm16": 16}[name]
+        print(json.dumps(run_qknorm(rl, torch, args.steps if args.steps is not None else 100, args.warmup, B=B,
                                     with_cpu=not args.no_cpu)))
         return
     steps = args.steps if args.steps is not None else (20 if name == "prefill" else 200)

@@ -117,6 +117,7 @@ rl_variant rl_last_variant(void);
  *           the waves per workgroup (4 or 8); for the two-kernel tile variant n_tile = 1 makes k_split
  *           (1 to 16) the number of K slabs of its product (1 = no split; otherwise the library splits
  *           when the 256x256 tiles are too few to fill the chip).
+ *           For rl_qknorm_attention k_split is the number of splits of the sequence (at least 64 positions each).
  * Values a variant cannot honour give RL_ERR_UNSUPPORTED at the next call.
  */
 rl_status rl_set_tuning(int n_tile, int k_split);

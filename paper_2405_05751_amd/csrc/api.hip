@@ -418,13 +418,20 @@ rl_status rl_qknorm_attention(const void* Q, const void* K, const void* V, const
         if (!aligned16(ptr)) return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
     hipStream_t s = static_cast<hipStream_t>(stream);
     float* ws = nullptr;
+    unsigned* counters = nullptr;
     const size_t need = qkattn_workspace_bytes(B, H, S, D, DType(dt));
     if (need) {
         Workspace w;
         if (rl_status st = get_workspace(need, s, &w)) return st;
+        counters = static_cast<unsigned*>(w.ptr);
         ws = reinterpret_cast<float*>(static_cast<char*>(w.ptr) + kHeadBytes);
     }
-    hipError_t e = launch_qkattn(Q, K, V, gq, bq, gk, bk, eps, O, B, H, S, D, DType(dt), ws, s);
+    int splits;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        splits = g_k_split;                  // rl_set_tuning(., k_split): sequence splits of this kernel
+    }
+    hipError_t e = launch_qkattn(Q, K, V, gq, bq, gk, bk, eps, O, B, H, S, D, DType(dt), ws, counters, splits, s);
     if (e != hipSuccess) return fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
     return RL_OK;
 }

@@ -73,10 +73,12 @@ inline hipError_t raise_lds_once(LdsOnce& once, std::initializer_list<const void
     return hipSuccess;
 }
 
-// QKNorm in front of attention, one query per (sample, head); ws: qkattn_workspace_bytes() of device memory or null
+// QKNorm in front of attention, one query per (sample, head); ws: qkattn_workspace_bytes() of device memory;
+// splits > 0 forces the number of sequence splits (tuning), 0 = automatic
 hipError_t launch_qkattn(const void* Q, const void* K, const void* V, const void* gq, const void* bq,
                          const void* gk, const void* bk, float eps, void* O,
-                         int64_t B, int64_t H, int64_t S, int64_t D, DType dt, float* ws, hipStream_t s);
+                         int64_t B, int64_t H, int64_t S, int64_t D, DType dt, float* ws, unsigned* counters,
+                         int splits, hipStream_t s);
 size_t qkattn_workspace_bytes(int64_t B, int64_t H, int64_t S, int64_t D, DType dt);
 hipError_t launch_silu_mul(const void* Z, void* Y, int M, int H, DType dt, hipStream_t s);
 

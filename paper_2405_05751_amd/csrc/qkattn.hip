@@ -13,8 +13,9 @@
 // Fast path (D = 128, 16-bit types): 16 lanes share a key (8 elements each; a wave-wide load is four
 // consecutive keys, 1 KiB contiguous), the three sums over D are rotations inside a 16-lane row
 // (DPP, no LDS), every group of 16 lanes keeps its own running maximum, denominator and 8 output
-// sums (online softmax), and the groups, the waves and - through the workspace and a second kernel -
-// the splits of the sequence are merged at the end.  Any other D or type: a slow plain kernel.
+// sums (online softmax), and the groups, the waves and
+// the splits of the sequence (by the last of them to arrive, through the workspace) are merged at
+// the end.  Any other D or type: a slow plain kernel.
 #include <algorithm>
 #include "common.hpp"
 
@@ -31,6 +32,8 @@ struct QkArgs {
     const u16* gq; const u16* bq; const u16* gk; const u16* bk;
     u16* O;
     float* part;                     // [B*H][SP][D + 2] when SP > 1
+    unsigned* counter;               // one arrival counter per (sample, head), zero between calls; or null:
+                                     // then a second kernel merges the splits
     float eps, scale_log2e;          // scores are kept in units of log2: s * log2(e) / sqrt(D)
     int S, SP, chunk;                // positions, splits, positions per split (a multiple of 16)
 };
@@ -60,6 +63,7 @@ __global__ __launch_bounds__(256) void qkattn_kernel(QkArgs a)
     constexpr int D = kQkD, R = kQkRing;
     __shared__ float s_m[4], s_l[4];
     __shared__ float s_acc[4][D];
+    __shared__ int s_last;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kq = lane >> 4, c = lane & 15;
     const int bh = blockIdx.x / a.SP, sp = blockIdx.x % a.SP;
@@ -188,12 +192,51 @@ __global__ __launch_bounds__(256) void qkattn_kernel(QkArgs a)
         }
         if (a.SP == 1) {
             a.O[size_t(bh) * D + tid] = Elem<T>::from_f32(o / ll);
-        } else {
+        } else {                             // written through: another workgroup will read them
             float* dst = a.part + (size_t(bh) * a.SP + sp) * (D + 2);
-            dst[tid] = o;
-            if (tid == 0) { dst[D] = mm; dst[D + 1] = ll; }
+            st_dev(dst + tid, o);
+            if (tid == 0) { st_dev(dst + D, mm); st_dev(dst + D + 1, ll); }
         }
     }
+    if (a.SP == 1 || !a.counter) return;     // uniform
+
+    // ---- the last split of this (sample, head) to arrive merges them all
+    __builtin_amdgcn_s_waitcnt(0);           // this wave's stores have been acknowledged
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned prev = __hip_atomic_fetch_add(a.counter + bh * kCounterStride, 1u, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+        s_last = (prev == unsigned(a.SP - 1));
+    }
+    __syncthreads();
+    if (!s_last) return;
+    if (tid < D) {
+        const float* src = a.part + size_t(bh) * a.SP * (D + 2);
+        float mm = -1.0e30f, o = 0.f, ll = 0.f;
+        for (int s0 = 0; s0 < a.SP; s0 += 16) {      // 16 splits per round trip, all loads before any use
+            float pm[16], pl[16], po[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const float* e = src + size_t(min(s0 + j, a.SP - 1)) * (D + 2);
+                pm[j] = ld_dev(e + D); pl[j] = ld_dev(e + D + 1); po[j] = ld_dev(e + tid);
+            }
+            float bm = mm;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) if (s0 + j < a.SP) bm = fmaxf(bm, pm[j]);
+            const float w0 = __builtin_amdgcn_exp2f(mm - bm);
+            o *= w0; ll *= w0;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const float ws = s0 + j < a.SP ? __builtin_amdgcn_exp2f(pm[j] - bm) : 0.f;
+                o = __fmaf_rn(po[j], ws, o);
+                ll = __fmaf_rn(pl[j], ws, ll);
+            }
+            mm = bm;
+        }
+        a.O[size_t(bh) * D + tid] = Elem<T>::from_f32(o / ll);
+    }
+    if (tid == 0)                            // ready for the next call on this stream
+        __hip_atomic_store(a.counter + bh * kCounterStride, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // splits of one (sample, head) -> O; thread j owns output dimension j
@@ -282,11 +325,14 @@ __global__ __launch_bounds__(256) void qkattn_plain_kernel(const typename Elem<T
 }
 
 // ------------------------------------------------------------------------------------------- host
-static void qk_plan(int64_t BH, int S, int* SP, int* chunk)
+static void qk_plan(int64_t BH, int S, int force, int* SP, int* chunk)
 {
-    // about two workgroups per compute unit, at least 64 positions each
-    int64_t sp = std::max<int64_t>(1, (512 + BH - 1) / BH);
-    sp = std::min<int64_t>(sp, std::max(1, S / 64));
+    // one workgroup per compute unit, at least 256 positions each: more splits measured slower
+    // (32 heads x 4096 positions: 8 splits 19.2 us, 16 splits 23.9 us, 32 splits 30.2 us);
+    // force > 0: that many splits, at least 64 positions each
+    int64_t sp = std::max<int64_t>(1, (256 + BH - 1) / BH);
+    sp = std::min<int64_t>(sp, std::max(1, S / 256));
+    if (force > 0) sp = std::min<int64_t>(force, std::max(1, S / 64));
     sp = std::min<int64_t>(sp, 64);
     int ch = int(((S + sp - 1) / sp + 15) / 16 * 16);
     *chunk = ch;
@@ -296,9 +342,7 @@ static void qk_plan(int64_t BH, int S, int* SP, int* chunk)
 size_t qkattn_workspace_bytes(int64_t B, int64_t H, int64_t S, int64_t D, DType dt)
 {
     if (dt == F32 || D != kQkD) return size_t(B) * H * S * 4;       // the plain kernel's scores
-    int SP, chunk;
-    qk_plan(B * H, int(S), &SP, &chunk);
-    return SP > 1 ? size_t(B) * H * SP * (kQkD + 2) * 4 : 0;
+    return size_t(B) * H * 64 * (kQkD + 2) * 4;                      // room for the most splits there can be
 }
 
 template <typename T>
@@ -314,7 +358,8 @@ static hipError_t qk_plain_go(const void* Q, const void* K, const void* V, const
 
 hipError_t launch_qkattn(const void* Q, const void* K, const void* V, const void* gq, const void* bq,
                          const void* gk, const void* bk, float eps, void* O,
-                         int64_t B, int64_t H, int64_t S, int64_t D, DType dt, float* ws, hipStream_t s)
+                         int64_t B, int64_t H, int64_t S, int64_t D, DType dt, float* ws, unsigned* counters,
+                         int splits, hipStream_t s)
 {
     const int64_t BH = B * H;
     if (dt == F32 || D != kQkD) {
@@ -328,12 +373,13 @@ hipError_t launch_qkattn(const void* Q, const void* K, const void* V, const void
     a.O = (u16*)O; a.part = ws; a.eps = eps;
     a.scale_log2e = kLog2e / sqrtf(float(kQkD));
     a.S = int(S);
-    qk_plan(BH, int(S), &a.SP, &a.chunk);
+    qk_plan(BH, int(S), splits, &a.SP, &a.chunk);
+    a.counter = (BH <= kMaxCounters) ? counters : nullptr;
     dim3 grid((unsigned)(BH * a.SP));
     if (dt == F16) qkattn_kernel<Fp16><<<grid, 256, 0, s>>>(a);
     else           qkattn_kernel<Bf16><<<grid, 256, 0, s>>>(a);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || a.SP == 1) return e;
+    if (e != hipSuccess || a.SP == 1 || a.counter) return e;
     if (dt == F16) qkattn_combine_kernel<Fp16><<<dim3((unsigned)BH), kQkD, 0, s>>>(ws, (u16*)O, a.SP);
     else           qkattn_combine_kernel<Bf16><<<dim3((unsigned)BH), kQkD, 0, s>>>(ws, (u16*)O, a.SP);
     return hipGetLastError();
