@@ -195,10 +195,11 @@ rl_status rl_ff_rmsnorm_linear(const void* X, const void* g, const void* W, void
 
 /*
  * Workspace (split-K partial sums + arrival counters; X (.) g, 1/rms and partial tiles of the two-kernel
- * tile form).  By default the library allocates rl_workspace_default_bytes() per device on first need,
- * replaces it by a larger one (up to 4 GiB) when a call needs more -- freeing the old one waits for the
- * device, and nothing is allocated while the call's stream is being captured into a graph: run the shape
- * once before capturing, or lend a buffer -- and keeps it until the process ends.  rl_set_workspace lends a
+ * tile form, split merges of rl_qknorm_attention).  By default the library allocates
+ * rl_workspace_default_bytes() per device on first need and switches to a larger allocation (at least
+ * twice the size, up to 4 GiB) when a call needs more; earlier allocations stay alive until the process
+ * ends, because a graph captured before still points into them.  Nothing is allocated while the call's
+ * stream is being captured into a graph: run the shape once before capturing, or lend a buffer.  rl_set_workspace lends a
  * caller-owned DEVICE buffer instead (for the current device; the first 256 KiB must be zero when lent);
  * NULL returns to the library's own buffer.  With a lent buffer too small for a call, the split-K variants
  * return RL_ERR_WORKSPACE; the two-kernel tile form is then skipped by RL_AUTO (the fused tile kernel runs).

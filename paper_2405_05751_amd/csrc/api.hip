@@ -71,8 +71,9 @@ rl_status check_dims(int64_t M, int64_t K, int64_t N, rl_dtype dt)
 constexpr size_t kMaxOwnWorkspace = size_t(4) << 30;
 
 // Workspace for the current device: the lent buffer if there is one, else the library's own.  The
-// library's own buffer grows when a call needs more (the old one is freed, which waits for the
-// device), except while `stream` is being captured into a graph: nothing may be allocated then.
+// library's own buffer is replaced by a larger one (at least twice the size) when a call needs
+// more.  The old one is kept until the process ends: a graph captured earlier still points into
+// it.  Nothing is allocated while `stream` is being captured.
 rl_status get_workspace(size_t need, hipStream_t stream, Workspace* out)
 {
     int dev = 0;
@@ -86,25 +87,21 @@ rl_status get_workspace(size_t need, hipStream_t stream, Workspace* out)
         return RL_OK;
     }
     if (!g_ws[dev].ptr || g_ws[dev].bytes < need + kHeadBytes) {
-        const size_t want = std::max(kDefaultWorkspace, (need + kHeadBytes + 0xfffff) & ~size_t(0xfffff));
+        size_t want = std::max(kDefaultWorkspace, (need + kHeadBytes + 0xfffff) & ~size_t(0xfffff));
         if (want > kMaxOwnWorkspace)
             return fail(RL_ERR_WORKSPACE, "shape needs more workspace than the library allocates; lend one with rl_set_workspace");
+        want = std::min(kMaxOwnWorkspace, std::max(want, 2 * g_ws[dev].bytes));
         hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
         e = hipStreamIsCapturing(stream, &cap);
         if (e != hipSuccess) return fail(RL_ERR_HIP, "hipStreamIsCapturing: %s", hipGetErrorString(e));
         if (cap != hipStreamCaptureStatusNone)
             return fail(RL_ERR_WORKSPACE, "the workspace cannot grow during stream capture: run the shape once before, or lend a workspace");
-        if (g_ws[dev].ptr) {
-            e = hipFree(g_ws[dev].ptr);              // waits for everything that may still use it
-            g_ws[dev] = Workspace{nullptr, 0, false};
-            if (e != hipSuccess) return fail(RL_ERR_HIP, "hipFree(workspace): %s", hipGetErrorString(e));
-        }
         void* p = nullptr;
         e = hipMalloc(&p, want);
         if (e != hipSuccess) return fail(RL_ERR_HIP, "hipMalloc(workspace): %s", hipGetErrorString(e));
         e = hipMemset(p, 0, kCounterBytes);              // synchronous, once per allocation
         if (e != hipSuccess) { (void)hipFree(p); return fail(RL_ERR_HIP, "hipMemset(workspace): %s", hipGetErrorString(e)); }
-        g_ws[dev] = Workspace{p, want, true};
+        g_ws[dev] = Workspace{p, want, true};            // (a smaller predecessor stays allocated)
     }
     *out = g_ws[dev];
     return RL_OK;

@@ -412,6 +412,34 @@ def test_lent_workspace(rl):
         rl.rl_set_workspace(None)
 
 
+def test_workspace_growth_keeps_captured_graphs_valid(rl):
+    """A graph captured while the library workspace was small still works after a larger shape has
+    made the library switch to a bigger one (the old allocation stays alive)."""
+    import torch
+    w, Z = _workload("decode")
+    X, g, W = upload(w)
+    Y = torch.empty((w.M, w.N), dtype=torch.bfloat16, device="cuda")
+    rl.rmsnorm_linear(X, g, W, w.eps, Y)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        rl.rmsnorm_linear(X, g, W, w.eps, Y)
+    Xb = torch.randn((8192, 16384), device="cuda").to(torch.bfloat16)        # X-hat alone needs 256 MiB
+    gb = torch.ones(16384, dtype=torch.bfloat16, device="cuda")
+    Wb = torch.randn((16384, 256), device="cuda").to(torch.bfloat16)
+    rl.rmsnorm_linear(Xb, gb, Wb, 1e-5)
+    assert rl.rl_last_variant() == "tile_pre"
+    torch.cuda.synchronize()
+    for _ in range(2):
+        Y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        compare(to_host_f64(Y, w.dtype), Z, w.dtype, "replay after workspace growth")
+    Y2 = rl.rmsnorm_linear(X, g, W, w.eps)                                   # and the new workspace serves split-K too
+    torch.cuda.synchronize()
+    compare(to_host_f64(Y2, w.dtype), Z, w.dtype, "decode after workspace growth")
+
+
 def test_probes_run(rl):
     import torch
     src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
