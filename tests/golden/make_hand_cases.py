@@ -23,6 +23,10 @@ Case G1 (gate of the GatedMLP block, SiLU(v) = v / (1 + exp(-v)), Y = SiLU(gate)
     Y = [0, (3/2) ln 3, -ln 3, -(7/8) ln 7]
 Case G2 (the whole gated block on case H1's inputs, H = 1: gate = column 0, up = column 1 of H1)
     row 0: SiLU(3 sqrt(3)/5) * 8 sqrt(3)/5;  row 1: SiLU(sqrt(3)) * 2/sqrt(3)   (exp in 40-digit decimals)
+Case Q1 (QKNorm in front of attention: layer normalisation of query and keys, eps = 0, then attention), D = 2
+    q = [3, 1], gq = [1, 1], bq = [1/2, 0];  keys [2, 0] and [0, 5], gk = [1, 1], bk = [0, 0];  values [1, 0] and [0, 1]
+    a vector of two components normalises to (+1, -1) or (-1, +1): qn = [1 + 1/2, -1], kn_1 = [1, -1], kn_2 = [-1, 1]
+    scores +-(3/2 + 1) / sqrt(2); weights 1 / (1 + exp(-+5 / sqrt 2)); output = [w1, w2]
 """
 from decimal import Decimal, getcontext
 import os
@@ -42,13 +46,17 @@ nu = [1 + 3 * s3 / 5, 2 + 2 * s3 / 5, Decimal(2)]
 nr = ((nu[0] ** 2 + nu[1] ** 2 + nu[2] ** 2) / 3).sqrt()
 n1 = [[v / nr for v in nu]]
 
+x = Decimal(5) / Decimal(2).sqrt()
+q1 = [[1 / (1 + (-x).exp()), 1 / (1 + x.exp())]]
+
 out = os.path.join(os.path.dirname(os.path.abspath(__file__)), "hand_cases.txt")
 with open(out, "w") as f:
     f.write("# Hand-computed cases for Eq. 1 (RMSNorm) followed by the MatMul of Fig. 2a (H1, H3)\n")
-    f.write("# for the gate of the GatedMLP block (G1, G2) and for the nTrans chain (N1).\n")
+    f.write("# for the gate of the GatedMLP block (G1, G2), for the nTrans chain (N1) and for QKNorm in\n")
+    f.write("# front of attention (Q1).\n")
     f.write("# Closed forms are derived in make_hand_cases.py; values to 30 digits.\n")
     f.write("# format: case row col value\n")
-    for name, tab in (("H1", h1), ("H3", h3), ("G1", g1), ("G2", g2), ("N1", n1)):
+    for name, tab in (("H1", h1), ("H3", h3), ("G1", g1), ("G2", g2), ("N1", n1), ("Q1", q1)):
         for i, row in enumerate(tab):
             for j, v in enumerate(row):
                 f.write(f"{name} {i} {j} {v:.30f}\n")

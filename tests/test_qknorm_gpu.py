@@ -84,6 +84,21 @@ def test_output_canaries_and_reuse(rl):
     _check(rl, c2, "bf16", 1e-5, "second, smaller call")
 
 
+def test_hand_case_q1_on_gpu(rl, golden_hand_cases):
+    """The D = 2 closed form through the plain kernel, in all three types."""
+    import torch
+    w = lambda a: np.asarray(a, dtype=np.float32)
+    arrs = (w([[[3.0, 1.0]]]), w([[[[2.0, 0.0], [0.0, 5.0]]]]), w([[[[1.0, 0.0], [0.0, 1.0]]]]),
+            w([1, 1]), w([0.5, 0.0]), w([1, 1]), w([0, 0]))
+    want = np.array([golden_hand_cases["Q1"][(0, j)] for j in range(2)])
+    for dtype, tol in (("f32", 1e-6), ("f16", 2e-3), ("bf16", 1e-2)):
+        # 16-byte alignment: every operand in its own allocation
+        dev = [to_device(workloads.to_storage(a, dtype), dtype) for a in arrs]
+        O = rl.rl_qknorm_attention(*dev, 0.0)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(to_host_f64(O, dtype)[0, 0], want, rtol=tol)
+
+
 def test_argument_checks(rl):
     import torch
     c = workloads.make_attention(1, 2, 32, 128, "bf16", 9700)

@@ -37,6 +37,18 @@ def test_closed_form_d2():
     np.testing.assert_allclose(oq, [[[pq, 1.0 - pq]]], rtol=1e-14)
 
 
+def test_hand_case_q1(golden_hand_cases):
+    """Golden case Q1 (closed form, 40-digit decimals): a query bias makes qn = (3/2, -1)."""
+    q = _w([[[3.0, 1.0]]])
+    k = _w([[[[2.0, 0.0], [0.0, 5.0]]]])
+    v = _w([[[[1.0, 0.0], [0.0, 1.0]]]])
+    for dtype in ("f32", "f16", "bf16"):                 # every value is exact in all three types
+        args = [workloads.to_storage(a, dtype) for a in (q, k, v, ONE2, _w([0.5, 0.0]), ONE2, ZERO2)]
+        o = oracle.qknorm_attention(*args, dtype, 0.0)
+        want = [golden_hand_cases["Q1"][(0, j)] for j in range(2)]
+        np.testing.assert_allclose(o[0, 0], want, rtol=1e-14)
+
+
 def _case(dtype="bf16", B=2, H=3, S=37, D=16, seed=5):
     return workloads.make_attention(B, H, S, D, dtype, seed)
 
