@@ -129,6 +129,15 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
     torch.cuda.synchronize()
     pair_ms, _ = min((_time_region(make_runner(pair), torch) for _ in range(3)), key=lambda t: t[0])
 
+    # where the automatic choice is the two-kernel tile form, the one fused kernel is timed beside it
+    one_kernel_ms = None
+    if used == "tile_pre" and variant == "auto":
+        rl.rl_set_variant("tile")
+        step(0)
+        torch.cuda.synchronize()
+        one_kernel_ms, _ = min((_time_region(make_runner(step), torch) for _ in range(3)), key=lambda t: t[0])
+        rl.rl_set_variant("auto")
+
     parity = None
     if check:
         import oracle
@@ -150,6 +159,7 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
         "copies_rotated": copies, "us_per_step": per_step_ms * 1e3,
         "us_per_step_warm": warm_ms / steps * 1e3, "us_per_step_unfused_pair": pair_ms / steps * 1e3,
         "wall_us_per_step": wall_ms / steps * 1e3,
+        "us_per_step_one_fused_kernel": None if one_kernel_ms is None else one_kernel_ms / steps * 1e3,
         "TBps": abytes / (per_step_ms * 1e-3) / 1e12, "TBps_warm": abytes / (warm_ms / steps * 1e-3) / 1e12,
         "TFLOPs": w.flops / (per_step_ms * 1e-3) / 1e12,
         "algorithmic_bytes": abytes, "flops": w.flops,
