@@ -158,6 +158,43 @@ def test_tile_launch_shapes(rl, M, K, N, n_tile, waves):
     compare(Y, Z, w.dtype, f"tile {M}x{K}x{N} shape={n_tile} waves={waves}")
 
 
+# ------------------------------------------------------------------ seeded random shapes
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    shapes = []
+    for _ in range(n):
+        M = int(rng.choice([1, 2, 3, 5, 9, 16, 17, 40, 64, 65, 100, 129, 255, 256, 257, 400, 700]))
+        K = int(rng.integers(1, 400)) * 8
+        N = int(rng.integers(1, 400)) * 8
+        shapes.append((M, K, N))
+    return shapes
+
+
+@pytest.mark.parametrize("gated", [False, True])
+@pytest.mark.parametrize("M,K,N", _random_shapes(36, 20240517))
+def test_random_shapes_automatic_choice(rl, M, K, N, gated):
+    """Whatever the automatic choice picks for a shape (GEMV, skinny, tile kernels with and without
+    the K split) agrees with the oracle on sampled rows."""
+    import torch
+    if gated:
+        N = (N + 15) // 16 * 16
+    dtype = "bf16" if (M + K + N) % 3 else "f16"
+    w = workloads.make(M, K, N, dtype, 1e-5, 6000 + M + 3 * K + 7 * N, outlier_frac=0.05 if M > 16 else 0.0,
+                       n_check_rows=min(M, 24))
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps, rows=w.check_rows)
+    X, g, W = upload(w)
+    Y = (rl.rmsnorm_gated_mlp if gated else rl.rmsnorm_linear)(X, g, W, w.eps)
+    torch.cuda.synchronize()
+    used = rl.rl_last_variant()
+    assert used != "naive"
+    Yh = to_host_f64(Y[torch.from_numpy(w.check_rows).cuda()], dtype)
+    if gated:
+        from util import compare_gated
+        compare_gated(Yh, Z, dtype, f"random gated {M}x{K}x{N} {dtype}->{used}")
+    else:
+        compare(Yh, Z, dtype, f"random {M}x{K}x{N} {dtype}->{used}")
+
+
 # ------------------------------------------------------------------ skinny kernel, block after block
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("M,K,N", [(65, 264, 136), (128, 1032, 520), (200, 4096, 1024), (1024, 520, 264)])
