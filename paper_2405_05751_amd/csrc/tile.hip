@@ -324,6 +324,8 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
     //   wait for this wave's W loads of tile kt+1, barrier (tile kt+1 complete in nxt; all of
     //   this tile's fragments are in registers)
     //   step 3: MFMA on set 1 | read next tile's step 0 -> set 0 | W tile kt+2 -> buffer cur
+    // (In the plain product X could take W's road straight into LDS; measured 1 % slower at 8192^3
+    // and 7 % slower at 256 x 8192 x 8192 than going through registers two tiles ahead.)
     // An X register is reloaded, for tile kt+2, in the very group that has just stored it: every
     // global load then has a whole K tile of matrix work to arrive in, and the loads stay spread
     // out one or two per group of MFMAs.
