@@ -60,7 +60,7 @@ template <> struct Mfma16<Fp16> {
 // steps (8 W loads per lane each) kept in flight per wave; X is fetched one run ahead (two runs
 // ahead measured 1 % slower at M <= 16)
 constexpr int skinny_depth(int MB) { return MB == 1 ? 4 : 3; }
-constexpr int skinny_waves(int MB) { return 4; }    // 8 (two waves per SIMD, MB <= 2 only) measured no faster
+constexpr int skinny_waves(int MB) { return 4; }    // 8 (two waves per SIMD at MB = 1) measured equal or up to 20 % slower
 
 template <typename T, int MB, bool FUSED, bool GATED>
 __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArgs a)
