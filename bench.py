@@ -319,7 +319,8 @@ def main():
                          "or MxKxN (a bf16 workload of that shape)")
     ap.add_argument("--variant", default="auto")
     ap.add_argument("--no-graph", action="store_true", help="enqueue the timed steps one by one")
-    ap.add_argument("--others", action="store_true", help="also time the other four configurations")
+    ap.add_argument("--others", action="store_true", help="(default) also time the other four configurations")
+    ap.add_argument("--no-others", action="store_true", help="time the named workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
     ap.add_argument("--autotune", action="store_true",
                     help="let the library's launch-shape tuner pick the shape for this workload first")
@@ -390,7 +391,7 @@ def main():
     }
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, mem_bound)
-    if args.others:
+    if (args.others or name == "decode") and not args.no_others:
         import workloads
         others = []
         for other in workloads.CONFIG_NAMES:
