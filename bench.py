@@ -330,7 +330,7 @@ def main():
                     help="only run the plain copy kernel on MiB of data ten times (memory-counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus must be 1 (sharding is design-only, see DESIGN.md)",
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (a split of W and Y along N across GPUs needs no exchange; it is not built here)",
               file=sys.stderr)
         sys.exit(2)
 
