@@ -40,11 +40,12 @@ typedef enum {
 typedef enum { RL_F16 = 0, RL_BF16 = 1, RL_F32 = 2 } rl_dtype;
 
 typedef enum {
-    RL_AUTO = 0,          /* pick by shape: M = 1 and N < 16384 GEMV; M <= 64 skinny; above that the two-kernel tile
-                             form, or the fused tile kernel when the workspace has no room for it */
+    RL_AUTO = 0,          /* pick by shape: M = 1 and N < 16384 GEMV; M <= 64 skinny, and up to M = 1024 while
+                             ceil(M / 64) K N <= 1.4e8 (0.9e8 for N > 6144); else the two-kernel tile form, or the fused tile kernel
+                             when the workspace has no room for it */
     RL_GEMV_SPLITK = 1,   /* M <= 16, no matrix cores, K split over workgroups */
-    RL_MFMA_SKINNY = 2,   /* matrix cores, 64 rows per launch (M <= 1024: one launch after the other), K split
-                             over the waves of a workgroup and over workgroups */
+    RL_MFMA_SKINNY = 2,   /* matrix cores, 64 rows per workgroup (M <= 1024: a row block per 64 rows in the same
+                             launch), K split over the waves of a workgroup and over workgroups */
     RL_MFMA_TILE = 3,     /* large M: 256x256 output tiles on matrix cores, one fused kernel */
     RL_NAIVE = 4,         /* any shape and type, fp32 arithmetic, slow */
     RL_MFMA_TILE_PRE = 5  /* M > 64: X (.) g and 1/rms written once by a first kernel (workspace of 2 M K + 4 M bytes),

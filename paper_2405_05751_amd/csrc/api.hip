@@ -125,8 +125,13 @@ rl_variant choose_auto(const Problem& p)
     // (N < 16384); without a split, and from two rows on, the matrix-core kernel is faster
     if (p.M == 1 && p.N < 16384) return RL_GEMV_SPLITK;
     if (p.M <= 64) return RL_MFMA_SKINNY;
-    // (the skinny kernel can run larger M block after block; the tile kernels, split over K when
-    // their tiles are few, measured faster from M = 65 on)
+    // Above 64 rows the skinny kernel runs one row block per 64 rows in the same launch; every row
+    // block pulls its own copy of W into its compute unit (from L2 after the first), so it wins
+    // while (row blocks) x K x N is small and loses to the tile kernels beyond about 1.4e8, earlier
+    // for wide W (measured: 128x4096x6144 27 against 31 us, 512x4096x4096 37 against 43 us,
+    // 1024x2048x2048 22 against 37 us; 768x1024x8192 41 against 37 us, 128x8192x10240 70 against
+    // 59 us, 256x4096x28672 131 against 81 us).
+    if (p.M <= 1024 && double((p.M + 63) / 64) * p.K * p.N <= (p.N <= 6144 ? 1.4e8 : 0.9e8)) return RL_MFMA_SKINNY;
     return RL_MFMA_TILE;
 }
 
@@ -194,6 +199,7 @@ rl_status run(Problem& p, void* stream)
         rl_variant first = choose_auto(p);
         if (first == RL_MFMA_TILE && prefers_two_kernels(p)) order[n_order++] = RL_MFMA_TILE_PRE;
         order[n_order++] = first;
+        if (first == RL_MFMA_SKINNY && p.M > 64) order[n_order++] = RL_MFMA_TILE;   // e.g. no room for the split
         if (first != RL_NAIVE) order[n_order++] = RL_NAIVE;
     }
     const char* why = "variant cannot run this shape";

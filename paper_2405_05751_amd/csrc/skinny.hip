@@ -1,5 +1,5 @@
-// Matrix-core variant of the fused RMSNorm + MatMul for small M (up to 64 rows per launch; more
-// rows run launch after launch): still bound by streaming
+// Matrix-core variant of the fused RMSNorm + MatMul for small M (64 rows per workgroup; more rows
+// as further row blocks in the same launch): still bound by streaming
 // W once from HBM, but each W element now meets up to 64 rows of X-hat, which plain FMAs could not
 // keep up with.  One v_mfma_f32_16x16x32 per 16 rows x 16 columns x 32 k.
 //
@@ -34,6 +34,7 @@ struct SkinnyArgs {
     int n_tiles;
     int n_tile;      // live columns per workgroup: a multiple of 8, at most kSkinnyTile
     int H;           // gated block: N = 2H, a tile is n_tile/2 gate columns and the same up columns; else 0
+    int RB;          // row blocks of 64 rows in this launch (M > 64): workgroup (row block, tile, slab)
     float* ws_partial; float* ws_sumsq; unsigned* counter;
     unsigned long long* trace; int trace_groups;
 };
@@ -78,10 +79,22 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
     const int i = lane & 15, q = lane >> 4;
     trace_stamp(a.trace, a.trace_groups, 0);
 
-    int b = blockIdx.x;
+    // Workgroups are dealt round-robin to the 8 XCDs; renumber so that the slabs of a tile, and the
+    // row blocks that stream the same part of W, share an XCD and start together: W then comes
+    // from HBM once and from that XCD's L2 for the other row blocks (a hint, nothing depends on it).
+    int b = blockIdx.x, rb = 0;
     const int total = a.n_tiles * a.S;
-    if ((total & 7) == 0) b = (b & 7) * (total >> 3) + (b >> 3);   // slabs of a tile share an XCD (hint)
+    if ((total & 7) == 0) {
+        const int j = b >> 3;
+        rb = j % a.RB;
+        b = (b & 7) * (total >> 3) + j / a.RB;
+    } else {
+        rb = b % a.RB;
+        b /= a.RB;
+    }
     const int tile = b / a.S, slab = b % a.S;
+    const int Mh = min(a.M - 64 * rb, 64);   // rows of this row block (all of M when there is one block)
+    const u16* Xb = a.X + size_t(rb) * 64 * a.K;
     // plain: the tile's W columns start at n0.  Gated: the tile is half = n_tile/2 gate columns from
     // hn0 and the up columns of the same outputs, H further on; lane chunk i is one or the other.
     const int half = a.n_tile >> 1;
@@ -95,7 +108,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
     const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint4_t*>(a.W + size_t(k0) * (a.N >> 3)), 0, klen * a.N * 2, kSkFlags);
     const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<u16*>(a.X), 0, a.M * a.K * 2, kSkFlags);
+        const_cast<u16*>(Xb), 0, Mh * a.K * 2, kSkFlags);
     const __amdgpu_buffer_rsrc_t grs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<u16*>(FUSED ? a.g : a.X), 0, a.K * 2, kSkFlags);
     const int wrow = a.N * 2;
@@ -125,9 +138,9 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
     // last row again: the repeated line costs nothing, nothing computed from those rows is ever
     // stored, and no instruction has part of its lanes out of range (measured the same as reading
     // zeros there).
-    const int rlim = a.M - r8;
+    const int rlim = Mh - r8;
     const int xlane = r8 * a.K * 2;          // used only where r8 < M
-    const int xlast = (a.M - 1) * a.K * 2;
+    const int xlast = (Mh - 1) * a.K * 2;
     auto issue_x = [&](int t) {
         const int kr = (NW * t + wave) * 64 + c8 * 8;               // slab-relative k of this lane's chunk
         const int koff = (k0 + kr) * 2;
@@ -258,20 +271,23 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
     __syncthreads();
     trace_stamp(a.trace, a.trace_groups, 3);
 
-    TailArgs ta{a.Y, a.M, a.N, a.n_tile, GATED ? half : 0, a.H, a.eps, a.inv_K, a.S, a.ws_partial, a.ws_sumsq, a.counter,
-                a.trace, a.trace_groups};
+    // every row block is a problem of its own to the epilogue: its rows of Y, its share of the workspace
+    TailArgs ta{a.Y + size_t(rb) * 64 * (GATED ? a.H : a.N), Mh, a.N, a.n_tile, GATED ? half : 0, a.H, a.eps, a.inv_K, a.S,
+                a.ws_partial + size_t(rb) * a.S * 64 * a.N, a.ws_sumsq + size_t(rb) * total * kSumsqStride,
+                a.counter + size_t(rb) * a.n_tiles * kCounterStride, a.trace, a.trace_groups};
     splitk_tail<T, MT, N_TILE, FUSED, NW, GATED>(ta, red, &s_sumsq[0][0], s_rinv, &s_last, tile, slab, n0);
 }
 
 // ------------------------------------------------------------------------------------------- host
-struct SkinnyPlan { int MB, S, k_slab, n_tiles, n_tile; size_t lds; bool ok; const char* why; };
+constexpr int kSkinnyMaxM = 1024;
+struct SkinnyPlan { int MB, RB, S, k_slab, n_tiles, n_tile; size_t lds; bool ok; const char* why; };
 
 static SkinnyPlan skinny_plan(const Problem& p)
 {
     SkinnyPlan pl{};
     pl.ok = false;
     if (p.dt == F32) { pl.why = "skinny variant handles 16-bit types only"; return pl; }
-    if (p.M > 64) { pl.why = "skinny kernel takes at most 64 rows per launch"; return pl; }
+    if (p.M > kSkinnyMaxM) { pl.why = "skinny variant needs M <= 1024"; return pl; }
     if (p.N % 8 != 0 || p.K % 8 != 0) { pl.why = "skinny variant needs N % 8 == 0 and K % 8 == 0"; return pl; }
     if (int64_t(p.M) * p.K * 2 >= (int64_t(1) << 31)) { pl.why = "skinny variant needs M*K < 2^30"; return pl; }
     if (p.n_tile != 0 && (p.n_tile % 8 != 0 || p.n_tile < 8 || p.n_tile > kSkinnyTile)) {
@@ -282,7 +298,9 @@ static SkinnyPlan skinny_plan(const Problem& p)
         pl.why = "gated block: skinny variant needs H % 8 == 0 and n_tile % 16 == 0";
         return pl;
     }
-    pl.MB = (p.M + 15) / 16;
+    pl.RB = (p.M + 63) / 64;                 // row blocks of 64 rows, all in one launch
+    pl.MB = pl.RB > 1 ? 4 : (p.M + 15) / 16;
+    const int Mb = std::min(p.M, 64);        // rows per workgroup
     const int gran = 64 * skinny_waves(pl.MB);
     int n_tile = p.n_tile, S = p.k_split;
     if (n_tile == 0 || S <= 0) {
@@ -300,11 +318,11 @@ static SkinnyPlan skinny_plan(const Problem& p)
             const int tiles = (p.N + nt - 1) / nt;
             for (int s = (p.k_split > 0 ? p.k_split : 1); s <= (p.k_split > 0 ? p.k_split : 16); s *= 2) {
                 if (s > 1 && 2 * s * gran > p.K) break;
-                if (tiles > kMaxCounters || int64_t(tiles) * s * kSumsqStride > kMaxSumsqFloats) continue;
-                if (s > 1 && int64_t(s) * p.M * p.N * 4 > (int64_t(48) << 20)) continue;   // fits the library workspace
-                const double bytes = double(p.K) * p.N * 2.0;
-                const double wgs = double(tiles) * s;
-                const double wg_bytes = (double(p.K) / s) * (nt * 2.0 + p.M * 2.0);         // its W and its X
+                if (int64_t(tiles) * pl.RB > kMaxCounters || int64_t(tiles) * pl.RB * s * kSumsqStride > kMaxSumsqFloats) continue;
+                if (s > 1 && int64_t(s) * pl.RB * 64 * p.N * 4 > (int64_t(48) << 20)) continue;   // fits the library workspace
+                const double bytes = double(p.K) * p.N * 2.0;                                // W comes from HBM once
+                const double wgs = double(tiles) * s * pl.RB;
+                const double wg_bytes = (double(p.K) / s) * (nt * 2.0 + Mb * 2.0);           // its W and its X
                 const double per_unit = double((int64_t(wgs) + 255) / 256) * wg_bytes / 36.0e3;
                 const double stream_us = std::max(bytes / 5.7e6, per_unit);
                 const double tail_us = s > 1 ? 3.0 + 2.0 * s * double(p.M) * p.N * 4.0 / 2.0e6 : 0.5;
@@ -326,9 +344,9 @@ static SkinnyPlan skinny_plan(const Problem& p)
     S = (p.K + k_slab - 1) / k_slab;
     pl.S = S;
     pl.k_slab = k_slab;
-    if (pl.n_tiles > kMaxCounters) { pl.why = "too many column tiles"; return pl; }
-    if (int64_t(pl.n_tiles) * S * kSumsqStride > kMaxSumsqFloats) { pl.why = "too many K slabs"; return pl; }
-    if (int64_t(S + 16) * p.M * p.N * 4 >= (int64_t(1) << 31)) { pl.why = "split-K partials too large"; return pl; }
+    if (int64_t(pl.n_tiles) * pl.RB > kMaxCounters) { pl.why = "too many column tiles"; return pl; }
+    if (int64_t(pl.n_tiles) * pl.RB * S * kSumsqStride > kMaxSumsqFloats) { pl.why = "too many K slabs"; return pl; }
+    if (int64_t(S + 16) * Mb * p.N * 4 >= (int64_t(1) << 31)) { pl.why = "split-K partials too large"; return pl; }
     pl.lds = size_t(skinny_waves(pl.MB)) * 16 * pl.MB * kSkinnyTile * 4;
     pl.ok = true;
     return pl;
@@ -336,22 +354,15 @@ static SkinnyPlan skinny_plan(const Problem& p)
 
 size_t skinny_workspace_bytes(const Problem& p)
 {
-    // larger M runs block after block through the same workspace: full blocks and the last one
-    size_t need = 0;
-    for (int m : {std::min(p.M, 64), p.M % 64}) {
-        if (m == 0) continue;
-        Problem q = p;
-        q.M = m;
-        SkinnyPlan pl = skinny_plan(q);
-        if (pl.ok && pl.S > 1) need = std::max(need, size_t(pl.S) * q.M * q.N * 4);
-    }
-    return need;
+    SkinnyPlan pl = skinny_plan(p);
+    if (!pl.ok || pl.S <= 1) return 0;
+    return size_t(pl.RB) * pl.S * std::min(p.M, 64) * p.N * 4;    // [row block][slab][rows][N]
 }
 
 template <typename T, int MB>
 static hipError_t skinny_go(const SkinnyArgs& a, bool fused, bool gated, const SkinnyPlan& pl, hipStream_t s)
 {
-    dim3 grid(pl.n_tiles * pl.S);
+    dim3 grid(pl.n_tiles * pl.S * pl.RB);
     static LdsOnce once;                     // 128 KiB of dynamic LDS at MB = 4
     hipError_t e = raise_lds_once(once, {(const void*)skinny_kernel<T, MB, true, false>,
                                          (const void*)skinny_kernel<T, MB, false, false>,
@@ -375,7 +386,9 @@ static hipError_t skinny_mb(const SkinnyArgs& a, bool fused, bool gated, const S
     }
 }
 
-static hipError_t launch_skinny_block(const Problem& p, hipStream_t s, const char** why)
+// M <= 64: one row block.  M up to 1024: a row block per 64 rows, all in one launch, the row
+// blocks that read the same part of W side by side on one XCD (see the kernel).
+hipError_t launch_skinny(const Problem& p, hipStream_t s, const char** why)
 {
     SkinnyPlan pl = skinny_plan(p);
     if (!pl.ok) { if (why) *why = pl.why; return hipErrorInvalidValue; }
@@ -388,44 +401,11 @@ static hipError_t launch_skinny_block(const Problem& p, hipStream_t s, const cha
     a.M = p.M; a.K = p.K; a.N = p.N; a.eps = p.eps; a.inv_K = 1.0f / float(p.K);
     a.k_slab = pl.k_slab; a.S = pl.S; a.n_tiles = pl.n_tiles; a.n_tile = pl.n_tile;
     a.H = p.gated ? p.N / 2 : 0;
+    a.RB = pl.RB;
     a.ws_partial = p.ws_partial; a.ws_sumsq = p.ws_sumsq; a.counter = p.ws_counter;
     a.trace = p.trace; a.trace_groups = p.trace_groups;
     const bool fused = p.fused != 0, gated = p.gated != 0;
     return p.dt == F16 ? skinny_mb<Fp16>(a, fused, gated, pl, s) : skinny_mb<Bf16>(a, fused, gated, pl, s);
-}
-
-// M > 64: one launch per block of 64 rows, in stream order (they share the workspace).  Every launch
-// streams W again - from the last-level cache when W fits it - which still beats a tile kernel
-// whose M/256 x N/256 workgroups would leave most of the chip idle; the caller decides when.
-constexpr int kSkinnyMaxM = 1024;
-
-static Problem skinny_rows(const Problem& p, int r0)
-{
-    Problem q = p;
-    q.M = std::min(64, p.M - r0);
-    q.X = static_cast<const char*>(p.X) + size_t(r0) * p.K * 2;
-    q.Y = static_cast<char*>(p.Y) + size_t(r0) * (p.gated ? p.N / 2 : p.N) * 2;
-    return q;
-}
-
-hipError_t launch_skinny(const Problem& p, hipStream_t s, const char** why)
-{
-    if (p.M <= 64) return launch_skinny_block(p, s, why);
-    if (p.M > kSkinnyMaxM) { if (why) *why = "skinny variant needs M <= 1024"; return hipErrorInvalidValue; }
-    if (p.dt == F32) { if (why) *why = "skinny variant handles 16-bit types only"; return hipErrorInvalidValue; }
-    for (int r0 = 0; r0 < p.M; r0 += 64) {   // all blocks can run, or none is launched
-        SkinnyPlan pl = skinny_plan(skinny_rows(p, r0));
-        if (!pl.ok) { if (why) *why = pl.why; return hipErrorInvalidValue; }
-        if (pl.S > 1 && (!p.ws_partial || !p.ws_sumsq || !p.ws_counter)) {
-            if (why) *why = "split-K needs the workspace";
-            return hipErrorInvalidValue;
-        }
-    }
-    for (int r0 = 0; r0 < p.M; r0 += 64) {
-        hipError_t e = launch_skinny_block(skinny_rows(p, r0), s, why);
-        if (e != hipSuccess) return e;
-    }
-    return hipSuccess;
 }
 
 }  // namespace rmsnl

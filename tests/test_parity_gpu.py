@@ -207,12 +207,18 @@ def test_skinny_runs_larger_m_in_blocks_of_64_rows(rl, M, K, N, dtype):
 
 
 def test_mid_m_automatic_choice(rl):
-    """Above 64 rows the tile kernels (two-kernel form, split over K); from two rows the skinny kernel."""
+    """Above 64 rows: row blocks of the skinny kernel while (row blocks) x K x N is small, the tile
+    kernels (two-kernel form, split over K) beyond; from two rows the skinny kernel."""
     w = workloads.make(128, 2048, 2048, "bf16", 1e-5, 4900)
     Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
     Y, used = _run(rl, w, "auto")
+    assert used == "skinny"
+    compare(Y, Z, w.dtype, "auto -> skinny at 128x2048x2048")
+    w = workloads.make(640, 4096, 8192, "bf16", 1e-5, 4902, n_check_rows=32)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps, rows=w.check_rows)
+    Y, used = _run(rl, w, "auto", rows=w.check_rows)
     assert used == "tile_pre"
-    compare(Y, Z, w.dtype, "auto -> tile_pre at M = 128")
+    compare(Y, Z, w.dtype, "auto -> tile_pre at 640x4096x8192")
     w = workloads.make(2, 1024, 2048, "bf16", 1e-5, 4901)
     Y, used = _run(rl, w, "auto")
     assert used == "skinny"
@@ -240,7 +246,7 @@ def test_tile_pre_variant(rl, M, K, N, dtype, tuning):
 
 def test_tile_pre_is_the_automatic_choice_for_large_shapes(rl):
     import torch
-    w = workloads.make(1024, 264, 4096, "bf16", 1e-5, 4700)
+    w = workloads.make(1100, 264, 4096, "bf16", 1e-5, 4700)
     Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
     Y, used = _run(rl, w, "auto")
     assert used == "tile_pre"
@@ -391,14 +397,23 @@ def test_unfused_pair(rl, name):
 
 @pytest.mark.parametrize("M,K,N", [(65, 1032, 264), (130, 1544, 520), (300, 4104, 1288), (1100, 520, 4104)])
 def test_plain_product_with_few_tiles_is_split_over_k(rl, M, K, N):
+    """matmul through the tile kernels (forced: the automatic choice may prefer the skinny kernel
+    at these sizes) takes the K split when its tiles are few, and through the automatic choice."""
     import torch
     w = workloads.make(M, K, N, "bf16", 1e-5, 5100 + M + K + N)
     X, _, W = upload(w)
+    Zp = oracle.matmul(w.X, w.W, "bf16")
+    rl.rl_set_variant("tile_pre")
+    try:
+        Y = rl.matmul(X, W)
+        torch.cuda.synchronize()
+        assert rl.rl_last_variant() == "tile_pre"
+    finally:
+        rl.rl_set_variant("auto")
+    compare(to_host_f64(Y, "bf16"), Zp, "bf16", f"matmul {M}x{K}x{N}, tile kernels")
     Y = rl.matmul(X, W)
     torch.cuda.synchronize()
-    tiles = -(-M // 256) * -(-N // 256)
-    assert rl.rl_last_variant() == ("tile_pre" if tiles <= 128 and K >= 512 else "tile")
-    compare(to_host_f64(Y, "bf16"), oracle.matmul(w.X, w.W, "bf16"), "bf16", f"matmul {M}x{K}x{N}")
+    compare(to_host_f64(Y, "bf16"), Zp, "bf16", f"matmul {M}x{K}x{N}, auto -> {rl.rl_last_variant()}")
 
 
 @pytest.mark.parametrize("M,K", [(1, 8), (3, 100), (5, 4096), (2, 16384), (4, 20000)])
