@@ -117,7 +117,8 @@ rl_variant rl_last_variant(void);
  *   k_split number of K slabs (split-K factor) of the GEMV and skinny variants; for the tile variant
  *           the waves per workgroup (4 or 8); for the two-kernel tile variant n_tile = 1 makes k_split
  *           (1 to 16) the number of K slabs of its product (1 = no split; otherwise the library splits
- *           when the 256x256 tiles are too few to fill the chip).
+ *           when the 256x256 tiles are too few to fill the chip), and n_tile = 2 makes k_split the number
+ *           of slabs for the tiles left over after the last full round of 256 (1 = no such split).
  *           For rl_qknorm_attention k_split is the number of splits of the sequence (at least 64 positions each).
  * Values a variant cannot honour give RL_ERR_UNSUPPORTED at the next call.
  */

@@ -24,6 +24,7 @@ struct Problem {
     int fused;            // 1: RMSNorm prologue + row scaling, 0: plain product
     int gated;            // 1: W is [K][N] = [gate | up] with N = 2H, Y is [M][H] = SiLU(Z_gate) * Z_up
     const float* rscale;  // plain product only: Y rows scaled by rscale[i] in the epilogue, or null
+    int tile_limit;       // tile kernel only: run the first tile_limit tiles of its order (0 = all)
     DType dt;
     // split-K workspace (may be null when the chosen launch needs none)
     float* ws_partial;    // [S][M][N] partial B

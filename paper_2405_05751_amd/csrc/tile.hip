@@ -36,7 +36,29 @@ struct TileArgs {
     // fp32 tile to part [slab][M][N]; tiles_m * tiles_n workgroups per slab
     int k_slab;
     float* part;
+    // A launch may cover only tiles tile_base .. tile_base + tiles_here - 1 of the order below
+    // (tiles_here = 0: all of them).  SPLIT launches of such a range store compact partial tiles,
+    // part [slab][tile - tile_base][256][256].
+    int tile_base, tiles_here;
 };
+
+// position b of the tile order -> tile row and column.  Workgroups are dealt round-robin to the 8
+// XCDs, each with its own L2: when the grid allows, XCD x works through a band of tile rows, four
+// rows at a time, so the ~32 tiles it runs together share few X and W panels in that L2.
+__device__ __host__ __forceinline__ void tile_at(int b, int tiles_m, int tiles_n, int* tm, int* tn)
+{
+    if ((tiles_m & 7) == 0) {
+        const int band = tiles_m >> 3;               // tile rows per XCD
+        const int x = b & 7, idx = b >> 3;           // idx in [0, band * tiles_n)
+        const int grp_rows = (band & 3) == 0 ? 4 : (band & 1) == 0 ? 2 : 1;
+        const int per_grp = grp_rows * tiles_n;
+        const int grp = idx / per_grp, in = idx % per_grp;
+        *tm = x * band + grp * grp_rows + in % grp_rows;
+        *tn = in / grp_rows;
+    } else {
+        *tm = b / tiles_n; *tn = b % tiles_n;
+    }
+}
 
 // Tile shapes: 0 = 256 rows x 256 columns (2 x NW/2 waves), 1 = 128 rows x 512 columns (1 x NW waves).
 // The second halves the X-hat staging work per matrix instruction (an X tile then meets 512
@@ -125,28 +147,13 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
 
-    // Tile order: workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  When the
-    // grid allows, XCD x works through a band of tile rows, four rows at a time, so the ~32 tiles
-    // it runs together share few X and W panels in that L2.
     int tm, tn;
-    const int n_tiles = a.tiles_m * a.tiles_n;
+    const int n_tiles = a.tiles_here ? a.tiles_here : a.tiles_m * a.tiles_n;   // tiles of this launch
     const int slab = SPLIT ? int(blockIdx.x) / n_tiles : 0;
     const int kb = SPLIT ? slab * a.k_slab : 0;                     // first k of this workgroup
     const int Kend = SPLIT ? min(a.K, kb + a.k_slab) : a.K;         // k at or beyond it reads as zero
-    {
-        const int b = SPLIT ? int(blockIdx.x) % n_tiles : int(blockIdx.x);
-        if ((a.tiles_m & 7) == 0) {
-            const int band = a.tiles_m >> 3;             // tile rows per XCD
-            const int x = b & 7, idx = b >> 3;           // idx in [0, band * tiles_n)
-            const int grp_rows = (band & 3) == 0 ? 4 : (band & 1) == 0 ? 2 : 1;
-            const int per_grp = grp_rows * a.tiles_n;
-            const int grp = idx / per_grp, in = idx % per_grp;
-            tm = x * band + grp * grp_rows + in % grp_rows;
-            tn = in / grp_rows;
-        } else {
-            tm = b / a.tiles_n; tn = b % a.tiles_n;
-        }
-    }
+    const int t_local = SPLIT ? int(blockIdx.x) % n_tiles : int(blockIdx.x);
+    tile_at(t_local + a.tile_base, a.tiles_m, a.tiles_n, &tm, &tn);
     const int m0 = tm * BM, n0 = GATED ? tn * (BN / 2) : tn * BN;   // gated: first output column of the tile
     const int rows_here = min(BM, a.M - m0);
 
@@ -391,18 +398,20 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
     // ---- epilogue: D register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its tile
     const int col_l = lane & 31, rowq = 4 * (lane >> 5);
     if constexpr (SPLIT) {
-        float* base = a.part + size_t(slab) * a.M * a.N;
+        const bool compact = a.tiles_here != 0;          // [slab][tile][BM][BN] instead of [slab][M][N]
+        float* base = compact ? a.part + (size_t(slab) * n_tiles + t_local) * (BM * BN)
+                              : a.part + size_t(slab) * a.M * a.N;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = wm * (BM / WM) + i * 32 + 8 * (r >> 2) + rowq + (r & 3);
                 if (m0 + row < a.M) {
-                    const int c0 = n0 + wn * (BN / WN) + col_l;
-                    float* prow = base + size_t(m0 + row) * a.N + c0;
+                    const int ct = wn * (BN / WN) + col_l;       // column inside the tile
+                    float* prow = compact ? base + row * BN + ct : base + size_t(m0 + row) * a.N + n0 + ct;
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        if (c0 + j * 32 < a.N) prow[j * 32] = acc[i][j][r];
+                        if (n0 + ct + j * 32 < a.N) prow[j * 32] = acc[i][j][r];
                 }
             }
         return;
@@ -483,14 +492,16 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
     }
     a.H = p.gated ? p.N / 2 : 0;
     a.rscale = p.fused ? nullptr : p.rscale;
-    a.k_slab = 0; a.part = nullptr;
+    a.k_slab = 0; a.part = nullptr; a.tile_base = 0; a.tiles_here = 0;
     a.tiles_m = (p.M + BM - 1) / BM;
     a.tiles_n = p.gated ? (a.H + BN / 2 - 1) / (BN / 2) : (p.N + BN - 1) / BN;
     if (int64_t(a.tiles_m) * a.tiles_n >= (int64_t(1) << 31)) {
         if (why) *why = "too many tiles";
         return hipErrorInvalidValue;
     }
-    dim3 grid(a.tiles_m * a.tiles_n);
+    if (p.tile_limit < 0 || p.tile_limit > a.tiles_m * a.tiles_n) { if (why) *why = "bad tile range"; return hipErrorInvalidValue; }
+    a.tiles_here = p.tile_limit;
+    dim3 grid(p.tile_limit ? p.tile_limit : a.tiles_m * a.tiles_n);
     const bool fused = p.fused != 0;
     if (p.gated && !fused)                  // gate over a product of a materialised X-hat, scaled per row
         return p.dt == F16 ? tile_nw<Fp16, false, true>(a, grid, nw, shape, s) : tile_nw<Bf16, false, true>(a, grid, nw, shape, s);
@@ -548,7 +559,7 @@ static hipError_t launch_tile_split(const Problem& q, int S, int k_slab, float* 
     TileArgs a;
     a.X = (const u16*)q.X; a.g = nullptr; a.W = (const u16*)q.W; a.Y = (u16*)q.Y;
     a.M = q.M; a.K = q.K; a.N = q.N; a.eps = 0.f; a.inv_K = 0.f;
-    a.H = 0; a.rscale = nullptr; a.k_slab = k_slab; a.part = part;
+    a.H = 0; a.rscale = nullptr; a.k_slab = k_slab; a.part = part; a.tile_base = 0; a.tiles_here = 0;
     a.tiles_m = (q.M + 255) / 256;
     a.tiles_n = (q.N + 255) / 256;
     dim3 grid(a.tiles_m * a.tiles_n * S);
@@ -570,6 +581,80 @@ static hipError_t launch_tile_split(const Problem& q, int S, int k_slab, float* 
         if (q.gated) tile_reduce_kernel<Bf16, true><<<rgrid, 256, 0, s>>>(part, q.rscale, Y, q.M, q.N, S);
         else         tile_reduce_kernel<Bf16, false><<<rgrid, 256, 0, s>>>(part, q.rscale, Y, q.M, q.N, S);
     }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------- the last, partial round of tiles split over K
+// A grid of t tiles runs in ceil(t / 256) rounds on 256 compute units, however little the last round
+// holds.  When the last round holds few tiles (at most 128), the full rounds run unsplit and the
+// remaining tiles are split over K so that they fill one short round, with compact fp32 partial tiles
+// and a reduction over just those tiles.
+template <typename T>
+__global__ __launch_bounds__(256) void tile_reduce_rem_kernel(const float* __restrict__ part, const float* __restrict__ rscale,
+                                                              u16* __restrict__ Y, int M, int N, int S,
+                                                              int tiles_m, int tiles_n, int tile_base, int rem)
+{
+    const int64_t idx = int64_t(blockIdx.x) * 256 + threadIdx.x;      // one thread per four columns of a tile row
+    const int t = int(idx / (256 * 64));
+    if (t >= rem) return;
+    const int r = int(idx % (256 * 64)) / 64, c = (int(idx) & 63) * 4;
+    int tm, tn;
+    tile_at(tile_base + t, tiles_m, tiles_n, &tm, &tn);
+    const int m = tm * 256 + r, n = tn * 256 + c;
+    if (m >= M || n >= N) return;
+    const float* src = part + (size_t(t) * 256 + r) * 256 + c;
+    const size_t slab = size_t(rem) * 256 * 256;
+    float4_t v = *(const float4_t*)src;
+    for (int s = 1; s < S; ++s) v += *(const float4_t*)(src + s * slab);
+    const float ri = rscale ? rscale[m] : 1.f;
+    uint2_t out = {Elem<T>::pack(v[0] * ri, v[1] * ri), Elem<T>::pack(v[2] * ri, v[3] * ri)};
+    *(uint2_t*)(Y + size_t(m) * N + n) = out;
+}
+
+// full rounds, remainder and its slabs for a plain product (rem = 0: no such split)
+static void tile_rem_plan(const Problem& p, int* full, int* rem, int* S, int* k_slab)
+{
+    const int64_t tiles = int64_t((p.M + 255) / 256) * ((p.N + 255) / 256);
+    *full = int(tiles / 256 * 256);
+    *rem = 0; *S = 1; *k_slab = p.K;
+    if (p.gated || tiles <= 256 || tiles > (int64_t(1) << 24)) return;
+    const int r = int(tiles - *full);
+    int s = r ? std::min(16, 256 / r) : 1;
+    s = std::min(s, std::max(1, p.K / 256));
+    if (p.n_tile == 2) s = (p.k_split >= 1 && p.k_split <= 16) ? p.k_split : 1;   // tuning override of this split only
+    if (r == 0 || s < 2) return;
+    const int ks = ((p.K + s - 1) / s + BK - 1) / BK * BK;
+    *rem = r; *S = (p.K + ks - 1) / ks; *k_slab = ks;
+    if (*S < 2) { *rem = 0; *S = 1; *k_slab = p.K; }
+}
+
+// q: the plain product (X-hat materialised or a plain matmul).  Tiles [0, full) unsplit, the rest in S slabs.
+static hipError_t launch_tile_rem(const Problem& q, int full, int rem, int S, int k_slab, float* part, hipStream_t s,
+                                  const char** why)
+{
+    Problem head = q;
+    head.tile_limit = full;
+    head.n_tile = 0; head.k_split = 0;
+    hipError_t e = launch_tile(head, s, why);
+    if (e != hipSuccess) return e;
+    TileArgs a;
+    a.X = (const u16*)q.X; a.g = nullptr; a.W = (const u16*)q.W; a.Y = (u16*)q.Y;
+    a.M = q.M; a.K = q.K; a.N = q.N; a.eps = 0.f; a.inv_K = 0.f;
+    a.H = 0; a.rscale = nullptr; a.k_slab = k_slab; a.part = part; a.tile_base = full; a.tiles_here = rem;
+    a.tiles_m = (q.M + 255) / 256;
+    a.tiles_n = (q.N + 255) / 256;
+    dim3 grid(rem * S);
+    static LdsOnce once;
+    e = raise_lds_once(once, {(const void*)tile_kernel<Fp16, false, 8, false, 0, true>,
+                              (const void*)tile_kernel<Bf16, false, 8, false, 0, true>}, int(tile_lds(0)));
+    if (e != hipSuccess) return e;
+    if (q.dt == F16) tile_kernel<Fp16, false, 8, false, 0, true><<<grid, 512, tile_lds(0), s>>>(a);
+    else             tile_kernel<Bf16, false, 8, false, 0, true><<<grid, 512, tile_lds(0), s>>>(a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    dim3 rgrid((unsigned)(rem * 64));        // 256 x 64 threads per tile
+    if (q.dt == F16) tile_reduce_rem_kernel<Fp16><<<rgrid, 256, 0, s>>>(part, q.rscale, (u16*)q.Y, q.M, q.N, S, a.tiles_m, a.tiles_n, full, rem);
+    else             tile_reduce_rem_kernel<Bf16><<<rgrid, 256, 0, s>>>(part, q.rscale, (u16*)q.Y, q.M, q.N, S, a.tiles_m, a.tiles_n, full, rem);
     return hipGetLastError();
 }
 
@@ -661,7 +746,10 @@ size_t tile_pre_workspace_bytes(const Problem& p)
 {
     int S, k_slab;
     tile_pre_split(p, &S, &k_slab);
-    return (p.fused ? xhat_bytes(p) + rscale_bytes(p) : 0) + (S > 1 ? size_t(S) * p.M * p.N * 4 : 0);
+    int full, rem, RS, rks;
+    tile_rem_plan(p, &full, &rem, &RS, &rks);
+    const size_t part = S > 1 ? size_t(S) * p.M * p.N * 4 : rem ? size_t(RS) * rem * 256 * 256 * 4 : 0;
+    return (p.fused ? xhat_bytes(p) + rscale_bytes(p) : 0) + part;
 }
 
 hipError_t launch_tile_pre(const Problem& p, hipStream_t s, const char** why)
@@ -678,6 +766,11 @@ hipError_t launch_tile_pre(const Problem& p, hipStream_t s, const char** why)
     }
     int S, k_slab;
     tile_pre_split(p, &S, &k_slab);
+    {
+        int full, rem, RS, rks;
+        tile_rem_plan(p, &full, &rem, &RS, &rks);
+        if (rem && !p.ws_partial) { if (why) *why = "two-kernel tile variant needs the workspace"; return hipErrorInvalidValue; }
+    }
     if ((p.fused || S > 1) && !p.ws_partial) { if (why) *why = "two-kernel tile variant needs the workspace"; return hipErrorInvalidValue; }
     Problem q = p;                           // the product, scaled per row if it is the fused block's
     float* part = p.ws_partial;
@@ -694,7 +787,10 @@ hipError_t launch_tile_pre(const Problem& p, hipStream_t s, const char** why)
         q.rscale = nullptr;                  // the plain product (matmul): no first kernel, only the split
     }
     if (S > 1) return launch_tile_split(q, S, k_slab, part, s);
-    if (p.n_tile == 1) { q.n_tile = 0; q.k_split = 0; }   // the override was for the split only
+    int full, rem, RS, rks;
+    tile_rem_plan(p, &full, &rem, &RS, &rks);
+    if (rem) return launch_tile_rem(q, full, rem, RS, rks, part, s, why);
+    if (p.n_tile == 1 || p.n_tile == 2) { q.n_tile = 0; q.k_split = 0; }   // the override was for the splits only
     const char* w2 = nullptr;
     hipError_t e = launch_tile(q, s, &w2);
     if (e != hipSuccess && why && w2) *why = w2;

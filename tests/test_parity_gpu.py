@@ -244,6 +244,18 @@ def test_tile_pre_variant(rl, M, K, N, dtype, tuning):
     compare(Y, Yt, w.dtype, "tile_pre against tile")
 
 
+@pytest.mark.parametrize("tuning", [(0, 0), (2, 1), (2, 3)])
+@pytest.mark.parametrize("M,K,N", [(300, 1024, 33280), (4100, 2056, 4096), (2048, 520, 8448)])
+def test_tile_pre_splits_the_last_partial_round(rl, M, K, N, tuning):
+    """More than 256 tiles with a few left over (4, 16, 8 here): full rounds unsplit, the rest split over
+    K with compact partial tiles; both tile orders (8 | tile rows or not); (2, 1) switches the split off."""
+    w = workloads.make(M, K, N, "bf16", 1e-5, 4650 + M + K + N, outlier_frac=0.02, n_check_rows=48)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps, rows=w.check_rows)
+    Y, used = _run(rl, w, "tile_pre", tuning=tuning, rows=w.check_rows)
+    assert used == "tile_pre"
+    compare(Y, Z, w.dtype, f"tile_pre {M}x{K}x{N} remainder split {tuning}")
+
+
 def test_tile_pre_is_the_automatic_choice_for_large_shapes(rl):
     import torch
     w = workloads.make(1100, 264, 4096, "bf16", 1e-5, 4700)
