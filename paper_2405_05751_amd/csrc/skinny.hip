@@ -63,7 +63,8 @@ template <> struct Mfma16<Fp16> {
 constexpr int skinny_depth(int MB) { return MB == 1 ? 4 : 3; }
 constexpr int skinny_waves(int MB) { return 4; }    // 8 (two waves per SIMD at MB = 1) measured equal or up to 20 % slower
 
-template <typename T, int MB, bool FUSED, bool GATED>
+// MULTI: the launch holds several row blocks of 64 rows (M > 64; MB = 4 then).
+template <typename T, int MB, bool FUSED, bool GATED, bool MULTI = false>
 __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArgs a)
 {
     constexpr int NW = skinny_waves(MB);
@@ -84,7 +85,9 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
     // from HBM once and from that XCD's L2 for the other row blocks (a hint, nothing depends on it).
     int b = blockIdx.x, rb = 0;
     const int total = a.n_tiles * a.S;
-    if ((total & 7) == 0) {
+    if (!MULTI) {
+        if ((total & 7) == 0) b = (b & 7) * (total >> 3) + (b >> 3);
+    } else if ((total & 7) == 0) {
         const int j = b >> 3;
         rb = j % a.RB;
         b = (b & 7) * (total >> 3) + j / a.RB;
@@ -93,8 +96,8 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
         b /= a.RB;
     }
     const int tile = b / a.S, slab = b % a.S;
-    const int Mh = min(a.M - 64 * rb, 64);   // rows of this row block (all of M when there is one block)
-    const u16* Xb = a.X + size_t(rb) * 64 * a.K;
+    const int Mh = MULTI ? min(a.M - 64 * rb, 64) : a.M;   // rows of this row block
+    const u16* Xb = MULTI ? a.X + size_t(rb) * 64 * a.K : a.X;
     // plain: the tile's W columns start at n0.  Gated: the tile is half = n_tile/2 gate columns from
     // hn0 and the up columns of the same outputs, H further on; lane chunk i is one or the other.
     const int half = a.n_tile >> 1;
@@ -272,9 +275,14 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
     trace_stamp(a.trace, a.trace_groups, 3);
 
     // every row block is a problem of its own to the epilogue: its rows of Y, its share of the workspace
-    TailArgs ta{a.Y + size_t(rb) * 64 * (GATED ? a.H : a.N), Mh, a.N, a.n_tile, GATED ? half : 0, a.H, a.eps, a.inv_K, a.S,
-                a.ws_partial + size_t(rb) * a.S * 64 * a.N, a.ws_sumsq + size_t(rb) * total * kSumsqStride,
-                a.counter + size_t(rb) * a.n_tiles * kCounterStride, a.trace, a.trace_groups};
+    TailArgs ta{a.Y, Mh, a.N, a.n_tile, GATED ? half : 0, a.H, a.eps, a.inv_K, a.S,
+                a.ws_partial, a.ws_sumsq, a.counter, a.trace, a.trace_groups};
+    if (MULTI) {
+        ta.Y += size_t(rb) * 64 * (GATED ? a.H : a.N);
+        ta.ws_partial += size_t(rb) * a.S * 64 * a.N;
+        ta.ws_sumsq += size_t(rb) * total * kSumsqStride;
+        ta.counter += size_t(rb) * a.n_tiles * kCounterStride;
+    }
     splitk_tail<T, MT, N_TILE, FUSED, NW, GATED>(ta, red, &s_sumsq[0][0], s_rinv, &s_last, tile, slab, n0);
 }
 
@@ -359,30 +367,31 @@ size_t skinny_workspace_bytes(const Problem& p)
     return size_t(pl.RB) * pl.S * std::min(p.M, 64) * p.N * 4;    // [row block][slab][rows][N]
 }
 
-template <typename T, int MB>
+template <typename T, int MB, bool MULTI>
 static hipError_t skinny_go(const SkinnyArgs& a, bool fused, bool gated, const SkinnyPlan& pl, hipStream_t s)
 {
     dim3 grid(pl.n_tiles * pl.S * pl.RB);
     static LdsOnce once;                     // 128 KiB of dynamic LDS at MB = 4
-    hipError_t e = raise_lds_once(once, {(const void*)skinny_kernel<T, MB, true, false>,
-                                         (const void*)skinny_kernel<T, MB, false, false>,
-                                         (const void*)skinny_kernel<T, MB, true, true>}, 144 * 1024);
+    hipError_t e = raise_lds_once(once, {(const void*)skinny_kernel<T, MB, true, false, MULTI>,
+                                         (const void*)skinny_kernel<T, MB, false, false, MULTI>,
+                                         (const void*)skinny_kernel<T, MB, true, true, MULTI>}, 144 * 1024);
     if (e != hipSuccess) return e;
     const int nt = 64 * skinny_waves(MB);
-    if (gated)      skinny_kernel<T, MB, true, true><<<grid, nt, pl.lds, s>>>(a);
-    else if (fused) skinny_kernel<T, MB, true, false><<<grid, nt, pl.lds, s>>>(a);
-    else            skinny_kernel<T, MB, false, false><<<grid, nt, pl.lds, s>>>(a);
+    if (gated)      skinny_kernel<T, MB, true, true, MULTI><<<grid, nt, pl.lds, s>>>(a);
+    else if (fused) skinny_kernel<T, MB, true, false, MULTI><<<grid, nt, pl.lds, s>>>(a);
+    else            skinny_kernel<T, MB, false, false, MULTI><<<grid, nt, pl.lds, s>>>(a);
     return hipGetLastError();
 }
 
 template <typename T>
 static hipError_t skinny_mb(const SkinnyArgs& a, bool fused, bool gated, const SkinnyPlan& pl, hipStream_t s)
 {
+    if (pl.RB > 1) return skinny_go<T, 4, true>(a, fused, gated, pl, s);
     switch (pl.MB) {
-    case 1:  return skinny_go<T, 1>(a, fused, gated, pl, s);
-    case 2:  return skinny_go<T, 2>(a, fused, gated, pl, s);
-    case 3:  return skinny_go<T, 3>(a, fused, gated, pl, s);
-    default: return skinny_go<T, 4>(a, fused, gated, pl, s);
+    case 1:  return skinny_go<T, 1, false>(a, fused, gated, pl, s);
+    case 2:  return skinny_go<T, 2, false>(a, fused, gated, pl, s);
+    case 3:  return skinny_go<T, 3, false>(a, fused, gated, pl, s);
+    default: return skinny_go<T, 4, false>(a, fused, gated, pl, s);
     }
 }
 
