@@ -223,6 +223,15 @@ rl_status rl_set_trace(void* dev_ptr, size_t bytes);
 size_t rl_trace_slots(void);
 
 /*
+ * Launch order of the tile kernels (diagnostics, host only, no device work): the workgroup at
+ * `position` (0 .. tiles - 1, tiles = ceil(M / 256) * ceil(N / 256)) of a launch over an M x N output
+ * computes the 256 x 256 tile (*tile_row, *tile_col).  The order places the tiles that one XCD runs
+ * together in blocks of 4 x 8; every tile appears at exactly one position.  RL_ERR_INVALID_ARG for a
+ * position outside the range or more than 2^24 tiles.
+ */
+rl_status rl_tile_order(int64_t M, int64_t N, int64_t position, int64_t* tile_row, int64_t* tile_col);
+
+/*
  * Measurement helpers (not on the hot path): a plain device-to-device copy kernel of
  * `bytes` bytes (multiple of 16) used to calibrate memory counters and to measure the
  * achievable streaming rate, and a register-only matrix-core loop of `iters` iterations

@@ -59,6 +59,8 @@ EXPORTS = {
     "rl_set_workspace": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t]),
     "rl_set_trace": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t]),
     "rl_trace_slots": (ctypes.c_size_t, []),
+    "rl_tile_order": (ctypes.c_int, [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                     ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]),
     "rl_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]),
     "rl_workspace_default_bytes": (ctypes.c_size_t, []),
     "rl_probe_copy": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
@@ -280,6 +282,13 @@ def rl_set_trace(buf: Optional[torch.Tensor]) -> None:
 
 def rl_trace_slots() -> int:
     return int(lib().rl_trace_slots())
+
+
+def rl_tile_order(M: int, N: int, position: int):
+    """(tile_row, tile_col) of the workgroup at `position` of a tile-kernel launch over an M x N output."""
+    tm, tn = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().rl_tile_order(M, N, position, ctypes.byref(tm), ctypes.byref(tn)))
+    return int(tm.value), int(tn.value)
 
 
 def rl_workspace_bytes(M: int, K: int, N: int, dtype: torch.dtype) -> int:

@@ -494,6 +494,20 @@ rl_status rl_set_trace(void* dev_ptr, size_t bytes)
 
 size_t rl_trace_slots(void) { return kTraceSlots; }
 
+rl_status rl_tile_order(int64_t M, int64_t N, int64_t position, int64_t* tile_row, int64_t* tile_col)
+{
+    if (!tile_row || !tile_col) return fail(RL_ERR_INVALID_ARG, "null output pointer");
+    if (M < 1 || N < 1) return fail(RL_ERR_INVALID_ARG, "tile order needs M, N >= 1");
+    const int64_t tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+    if (tiles_m * tiles_n > (int64_t(1) << 24) || tiles_m > (int64_t(1) << 24) || tiles_n > (int64_t(1) << 24))
+        return fail(RL_ERR_INVALID_ARG, "more than 2^24 tiles");
+    if (position < 0 || position >= tiles_m * tiles_n) return fail(RL_ERR_INVALID_ARG, "position outside the launch");
+    int tm = 0, tn = 0;
+    tile_order_at(int(position), int(tiles_m), int(tiles_n), &tm, &tn);
+    *tile_row = tm; *tile_col = tn;
+    return RL_OK;
+}
+
 rl_status rl_set_workspace(void* dev_ptr, size_t bytes)
 {
     int dev = 0;

@@ -52,6 +52,8 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why);
 // plain product of X-hat scaled per row
 hipError_t launch_tile_pre(const Problem& p, hipStream_t s, const char** why);
 size_t tile_pre_workspace_bytes(const Problem& p);
+// tile of the workgroup at position b of the tile kernels' order over tiles_m x tiles_n tiles (host)
+void tile_order_at(int b, int tiles_m, int tiles_n, int* tm, int* tn);
 // bytes of partial-B workspace the launch of this problem would use (0 = no split)
 size_t gemv_workspace_bytes(const Problem& p);
 size_t skinny_workspace_bytes(const Problem& p);

@@ -43,22 +43,44 @@ struct TileArgs {
 };
 
 // position b of the tile order -> tile row and column.  Workgroups are dealt round-robin to the 8
-// XCDs, each with its own L2: when the grid allows, XCD x works through a band of tile rows, four
-// rows at a time, so the ~32 tiles it runs together share few X and W panels in that L2.
+// XCDs, each with its own L2, and a compute unit holds one workgroup, so the 32 workgroups with
+// positions 8 i + x, i in a run of 32, are what XCD x runs together; they should share few X and W
+// panels.  When the tile rows divide into 8 bands of a multiple of 4 rows, XCD x works through band
+// x, four rows at a time (4 x 8 tiles together).  Otherwise the tiles are listed panel by panel of
+// 4 tile rows, column by column inside a panel, and that list is cut into runs of 32 which are
+// dealt to the XCDs in turn: again blocks of 4 x 8 tiles, whatever the shape of the grid
+// (2048 x 8192 x 8192: 3-5 % faster than row by row).  Positions beyond the last full round of 256
+// are dealt in equal consecutive shares when they divide by 8, else one by one.
 __device__ __host__ __forceinline__ void tile_at(int b, int tiles_m, int tiles_n, int* tm, int* tn)
 {
-    if ((tiles_m & 7) == 0) {
+    if ((tiles_m & 31) == 0) {
         const int band = tiles_m >> 3;               // tile rows per XCD
         const int x = b & 7, idx = b >> 3;           // idx in [0, band * tiles_n)
-        const int grp_rows = (band & 3) == 0 ? 4 : (band & 1) == 0 ? 2 : 1;
-        const int per_grp = grp_rows * tiles_n;
+        const int per_grp = 4 * tiles_n;
         const int grp = idx / per_grp, in = idx % per_grp;
-        *tm = x * band + grp * grp_rows + in % grp_rows;
-        *tn = in / grp_rows;
-    } else {
-        *tm = b / tiles_n; *tn = b % tiles_n;
+        *tm = x * band + grp * 4 + in % 4;
+        *tn = in / 4;
+        return;
     }
+    const int tiles = tiles_m * tiles_n;
+    const int base = tiles & ~255;
+    int l = b;
+    if (b < base) {
+        const int x = b & 7, idx = b >> 3;
+        l = (((idx >> 5) << 3) + x) * 32 + (idx & 31);
+    } else if (((tiles - base) & 7) == 0) {
+        const int r = b - base;
+        l = base + (r & 7) * ((tiles - base) >> 3) + (r >> 3);
+    }
+    const int per_panel = 4 * tiles_n;
+    const int panel = l / per_panel, in = l - panel * per_panel;
+    const int left = tiles_m - 4 * panel;
+    const int rows = left < 4 ? left : 4;
+    *tm = 4 * panel + in % rows;
+    *tn = in / rows;
 }
+
+void tile_order_at(int b, int tiles_m, int tiles_n, int* tm, int* tn) { tile_at(b, tiles_m, tiles_n, tm, tn); }
 
 // Tile shapes: 0 = 256 rows x 256 columns (2 x NW/2 waves), 1 = 128 rows x 512 columns (1 x NW waves).
 // The second halves the X-hat staging work per matrix instruction (an X tile then meets 512

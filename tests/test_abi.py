@@ -125,3 +125,24 @@ def test_gated_and_tuner_reject_bad_arguments(rl):
     import torch
     rl.rl_autotune_clear()
     assert rl.rl_autotune_get(4, 64, 64, torch.bfloat16) == ("auto", 0, 0)
+
+
+def test_tile_order_visits_every_tile_once(rl):
+    """Host logic of the tile kernels: the launch order is a one-to-one map of positions onto tiles,
+    for grids with and without full rounds of 256, band-divisible rows, ragged panels and remainders."""
+    for M, N in [(8192, 8192), (2048, 8192), (4096, 14336), (2304, 8192), (1280, 4352), (1100, 264),
+                 (300, 256 * 37), (256 * 19, 256 * 23), (256 * 64, 256 * 3), (1, 8)]:
+        tm, tn = -(-M // 256), -(-N // 256)
+        seen = set()
+        for b in range(tm * tn):
+            r, c = rl.rl_tile_order(M, N, b)
+            assert 0 <= r < tm and 0 <= c < tn, (M, N, b, r, c)
+            seen.add((r, c))
+        assert len(seen) == tm * tn, (M, N)
+    # the 32 workgroups one XCD runs together (positions 8 i + x, 32 consecutive i) form a 4 x 8 block
+    for M, N in [(8192, 8192), (2048, 8192), (4096, 14336)]:
+        for x in (0, 5):
+            tiles = [rl.rl_tile_order(M, N, 8 * i + x) for i in range(32)]
+            assert len({r for r, _ in tiles}) <= 4 and len({c for _, c in tiles}) <= 9, (M, N, x, tiles)
+    with pytest.raises(rl.RmsnlError):
+        rl.rl_tile_order(512, 512, 4)
