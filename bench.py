@@ -60,7 +60,8 @@ def _workload(name):
                           n_check_rows=min(M, 64))
 
 
-def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=True, gated=False, autotune=False):
+def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=True, gated=False, autotune=False,
+                 interleaved=False):
     import workloads
     from tests.util import compare, compare_gated, to_device, to_host_f64
 
@@ -85,10 +86,14 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
         tuned = rl.rl_autotune_get(w.M, w.K, w.N, tdt, gated)
 
     fused_call = rl.rmsnorm_gated_mlp if gated else rl.rmsnorm_linear
+    Wf = Ws                                      # what the fused call reads
+    if gated and interleaved:                    # gate and up columns interleaved in groups of 64, repacked once
+        fused_call = rl.rmsnorm_gated_mlp_interleaved
+        Wf = [rl.rl_interleave_gate_up(W) for W in Ws]
 
     def step(i):
         j = i % copies
-        fused_call(Xs[j], gs[j], Ws[j], w.eps, Ys[j])
+        fused_call(Xs[j], gs[j], Wf[j], w.eps, Ys[j])
 
     for i in range(max(warmup, 1)):
         step(i)
@@ -108,7 +113,7 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
 
     cold = make_runner(step)
     ev_ms, wall_ms = min((_time_region(cold, torch) for _ in range(3)), key=lambda t: t[0])
-    warm = make_runner(lambda i: fused_call(Xs[0], gs[0], Ws[0], w.eps, Ys[0]))
+    warm = make_runner(lambda i: fused_call(Xs[0], gs[0], Wf[0], w.eps, Ys[0]))
     warm_ms, _ = min((_time_region(warm, torch) for _ in range(3)), key=lambda t: t[0])
 
     # the unfused pair from the same library, same rotation, for the fusion gain on this hardware
@@ -155,7 +160,7 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
     per_step_ms = ev_ms / steps
     mem_bound = w.M <= 64
     res = {
-        "workload": name + ("+gate" if gated else ""), "M": w.M, "K": w.K, "N": w.N, "dtype": w.dtype, "variant": used,
+        "workload": name + ("+gate" if gated else "") + ("(interleaved W)" if gated and interleaved else ""), "M": w.M, "K": w.K, "N": w.N, "dtype": w.dtype, "variant": used,
         "copies_rotated": copies, "us_per_step": per_step_ms * 1e3,
         "us_per_step_warm": warm_ms / steps * 1e3, "us_per_step_unfused_pair": pair_ms / steps * 1e3,
         "wall_us_per_step": wall_ms / steps * 1e3,
@@ -324,6 +329,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
     ap.add_argument("--autotune", action="store_true",
                     help="let the library's launch-shape tuner pick the shape for this workload first")
+    ap.add_argument("--interleaved", action="store_true",
+                    help="with --gated: W's gate and up columns interleaved in groups of 64 (rmsnorm_gated_mlp_interleaved)")
     ap.add_argument("--gated", action="store_true",
                     help="time the gated block (SiLU(gate) * up epilogue, W read as [gate | up]) on the workload")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="MiB",
@@ -366,7 +373,7 @@ def main():
         M, K, N = (int(v) for v in name.lower().split("x"))
         steps = 20 if 2.0 * M * K * N > 2e11 else 100
     res, w = run_workload(rl, torch, name, steps, args.warmup, args.variant, use_graph=not args.no_graph,
-                          gated=args.gated, autotune=args.autotune)
+                          gated=args.gated, autotune=args.autotune, interleaved=args.interleaved)
     mem_bound = w.M <= 64
     if mem_bound:
         metric, unit, value = "fused RMSNorm+MatMul TB/s", "TB/s", res["TBps"]

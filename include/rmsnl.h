@@ -100,6 +100,24 @@ rl_status rmsnorm_gated_mlp(const void* X, const void* g, const void* W, float e
 rl_status silu_mul(const void* Z, void* Y, int64_t M, int64_t H, rl_dtype dt, void* stream);
 
 /*
+ * The same gated block (the paper's GatedMLP benchmark) on a W whose gate and up columns are
+ * interleaved in groups of 64, the layout a caller gives its weights once, when it loads them:
+ *
+ *     Wi [K][2H]: columns 128 j .. 128 j + 63 are the gate columns of outputs 64 j .. 64 j + 63, columns
+ *     128 j + 64 .. 128 j + 127 the up columns of the same outputs; H % 64 == 0
+ *     Y[i][h] = SiLU(Z_gate[i][h]) * Z_up[i][h] exactly as rmsnorm_gated_mlp computes it
+ *
+ * A workgroup that owns a run of outputs then reads one contiguous run of columns per row of W, as
+ * in the plain block, instead of two runs half as long that lie H columns apart.  The result is the
+ * one rmsnorm_gated_mlp gives on the two-halves W (same kernels, only the column a lane fetches
+ * differs).  Not covered by rl_autotune.  rl_interleave_gate_up writes Wi from W = [gate | up] (both
+ * [K][2H] DEVICE arrays of type dt, 16-byte aligned, not the same buffer), on `stream`.
+ */
+rl_status rmsnorm_gated_mlp_interleaved(const void* X, const void* g, const void* Wi, float eps, void* Y,
+                                        int64_t M, int64_t K, int64_t H, rl_dtype dt, void* stream);
+rl_status rl_interleave_gate_up(const void* W, void* Wi, int64_t K, int64_t H, rl_dtype dt, void* stream);
+
+/*
  * Variant control (process-wide).  RL_AUTO is the default; the environment variable
  * RL_VARIANT (auto|gemv|skinny|tile|tile_pre|naive) sets the initial value.  A forced variant that
  * cannot run a shape makes the call return RL_ERR_UNSUPPORTED instead of falling back.

@@ -36,6 +36,11 @@ EXPORTS = {
     "rmsnorm_gated_mlp": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
                                          ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                          ctypes.c_int, ctypes.c_void_p]),
+    "rmsnorm_gated_mlp_interleaved": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
+                                                     ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                                     ctypes.c_int, ctypes.c_void_p]),
+    "rl_interleave_gate_up": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                             ctypes.c_int, ctypes.c_void_p]),
     "rl_qknorm_attention": (ctypes.c_int, [ctypes.c_void_p] * 7 + [ctypes.c_float, ctypes.c_void_p] +
                             [ctypes.c_int64] * 4 + [ctypes.c_int, ctypes.c_void_p]),
     "silu_mul": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
@@ -170,6 +175,36 @@ def rmsnorm_gated_mlp(X: torch.Tensor, g: torch.Tensor, W: torch.Tensor, eps: fl
     _check(lib().rmsnorm_gated_mlp(_dev(X, "X"), _dev(g, "g"), _dev(W, "W"), float(eps), _dev(Y, "Y"),
                                    M, K, H, _DTYPES[X.dtype], _stream(stream)))
     return Y
+
+
+def rmsnorm_gated_mlp_interleaved(X: torch.Tensor, g: torch.Tensor, Wi: torch.Tensor, eps: float,
+                                  Y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """rmsnorm_gated_mlp on a W interleaved in groups of 64 columns (see rl_interleave_gate_up)."""
+    M, K = X.shape
+    K2, N = Wi.shape
+    if K2 != K or N % 2 or g.shape != (K,) or X.dtype != Wi.dtype or X.dtype != g.dtype:
+        raise ValueError("shape or dtype mismatch")
+    H = N // 2
+    if Y is None:
+        Y = torch.empty((M, H), dtype=X.dtype, device=X.device)
+    elif Y.shape != (M, H) or Y.dtype != X.dtype:
+        raise ValueError("Y has the wrong shape or dtype")
+    _check(lib().rmsnorm_gated_mlp_interleaved(_dev(X, "X"), _dev(g, "g"), _dev(Wi, "Wi"), float(eps), _dev(Y, "Y"),
+                                               M, K, H, _DTYPES[X.dtype], _stream(stream)))
+    return Y
+
+
+def rl_interleave_gate_up(W: torch.Tensor, Wi: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """W [K][2H] = [gate | up] -> the layout rmsnorm_gated_mlp_interleaved reads."""
+    K, N = W.shape
+    if N % 2:
+        raise ValueError("W needs an even number of columns")
+    if Wi is None:
+        Wi = torch.empty_like(W)
+    elif Wi.shape != W.shape or Wi.dtype != W.dtype:
+        raise ValueError("Wi has the wrong shape or dtype")
+    _check(lib().rl_interleave_gate_up(_dev(W, "W"), _dev(Wi, "Wi"), K, N // 2, _DTYPES[W.dtype], _stream(stream)))
+    return Wi
 
 
 def silu_mul(Z: torch.Tensor, Y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:

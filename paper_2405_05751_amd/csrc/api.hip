@@ -184,7 +184,7 @@ rl_status run(Problem& p, void* stream)
         p.trace_groups = g_trace_groups;
         if (forced == RL_AUTO) {
             auto it = g_tuned.find(TuneKey(p.M, p.K, p.N, int(p.dt), p.gated));
-            if (it != g_tuned.end() && p.fused) tuned = it->second;
+            if (it != g_tuned.end() && p.fused && !p.gate_group) tuned = it->second;   // (tuned on the two-halves layout)
         }
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -258,6 +258,36 @@ rl_status rmsnorm_gated_mlp(const void* X, const void* g, const void* W, float e
     p.M = int(M); p.K = int(K); p.N = int(2 * H);
     p.eps = eps; p.fused = 1; p.gated = 1; p.dt = DType(dt);
     return run(p, stream);
+}
+
+rl_status rmsnorm_gated_mlp_interleaved(const void* X, const void* g, const void* Wi, float eps, void* Y,
+                                        int64_t M, int64_t K, int64_t H, rl_dtype dt, void* stream)
+{
+    if (!X || !g || !Wi || !Y) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (H < 1 || H >= (int64_t(1) << 30)) return fail(RL_ERR_INVALID_ARG, "H must be in [1, 2^30)");
+    if (H % 64 != 0) return fail(RL_ERR_INVALID_ARG, "the interleaved layout needs H % 64 == 0");
+    if (rl_status st = check_dims(M, K, 2 * H, dt)) return st;
+    if (!std::isfinite(eps) || eps < 0.f) return fail(RL_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    if (!aligned16(X) || !aligned16(g) || !aligned16(Wi) || !aligned16(Y))
+        return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    Problem p{};
+    p.X = X; p.g = g; p.W = Wi; p.Y = Y;
+    p.M = int(M); p.K = int(K); p.N = int(2 * H);
+    p.eps = eps; p.fused = 1; p.gated = 1; p.gate_group = 64; p.dt = DType(dt);
+    return run(p, stream);
+}
+
+rl_status rl_interleave_gate_up(const void* W, void* Wi, int64_t K, int64_t H, rl_dtype dt, void* stream)
+{
+    if (!W || !Wi) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (W == Wi) return fail(RL_ERR_INVALID_ARG, "W and Wi must be different buffers");
+    if (H < 1 || H >= (int64_t(1) << 30)) return fail(RL_ERR_INVALID_ARG, "H must be in [1, 2^30)");
+    if (H % 64 != 0) return fail(RL_ERR_INVALID_ARG, "the interleaved layout needs H % 64 == 0");
+    if (rl_status st = check_dims(1, K, 2 * H, dt)) return st;
+    if (!aligned16(W) || !aligned16(Wi)) return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    hipError_t e = launch_interleave_gate_up(W, Wi, K, int(H), DType(dt), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+    return RL_OK;
 }
 
 rl_status silu_mul(const void* Z, void* Y, int64_t M, int64_t H, rl_dtype dt, void* stream)

@@ -23,6 +23,8 @@ struct Problem {
     float eps;
     int fused;            // 1: RMSNorm prologue + row scaling, 0: plain product
     int gated;            // 1: W is [K][N] = [gate | up] with N = 2H, Y is [M][H] = SiLU(Z_gate) * Z_up
+    int gate_group;       // gated: 0 = W's halves are gate and up; 64 = groups of 64 gate columns alternate with
+                          // the 64 up columns of the same outputs (H % 64 == 0)
     const float* rscale;  // plain product only: Y rows scaled by rscale[i] in the epilogue, or null
     int tile_limit;       // tile kernel only: run the first tile_limit tiles of its order (0 = all)
     DType dt;
@@ -84,6 +86,7 @@ hipError_t launch_qkattn(const void* Q, const void* K, const void* V, const void
                          int splits, hipStream_t s);
 size_t qkattn_workspace_bytes(int64_t B, int64_t H, int64_t S, int64_t D, DType dt);
 hipError_t launch_silu_mul(const void* Z, void* Y, int M, int H, DType dt, hipStream_t s);
+hipError_t launch_interleave_gate_up(const void* W, void* Wi, int64_t K, int H, DType dt, hipStream_t s);
 
 hipError_t launch_ntrans(const void* X, const void* Hh, const void* A, float eps, void* Y, int M, int D, DType dt,
                          hipStream_t s);
@@ -162,6 +165,14 @@ template <> struct Elem<float> {
 // rinv = 1 / sqrt(A / K + eps), correctly rounded division and root (not the fast approximations)
 __device__ __forceinline__ float row_scale(float sumsq, float inv_K, float eps) {
     return 1.0f / __fsqrt_rn(__fmaf_rn(sumsq, inv_K, eps));
+}
+
+// Gated block: the W column that feeds the gate (up = false) or the up (up = true) input of output h.
+// G = 0: W = [gate | up], two halves of H columns.  G = 64: columns 128 j .. 128 j + 63 are the gate
+// columns of outputs 64 j .. 64 j + 63 and the next 64 their up columns (8 consecutive outputs from a
+// multiple of 8 stay 8 consecutive columns either way).
+__device__ __forceinline__ int gated_col(int h, bool up, int H, int G) {
+    return G ? ((h >> 6) << 7) + (h & 63) + (up ? 64 : 0) : h + (up ? H : 0);
 }
 
 // SiLU(v) = v / (1 + exp(-v)) in fp32 (the activation of the paper's GatedMLP block)

@@ -30,6 +30,7 @@ struct GemvArgs {
     int S;           // number of slabs
     int n_tiles;
     int H;           // gated block: N = 2H, a tile is N_TILE/2 gate columns and the same outputs' up columns; else 0
+    int G;           // gated block: layout of W, see gated_col()
     float* ws_partial; float* ws_sumsq; unsigned* counter;
     unsigned long long* trace; int trace_groups;
 };
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(64 * gemv_waves(MT)) void gemv_splitk_kernel(GemvAr
     // plain: the tile's W columns start at n0.  Gated: the tile is N_TILE/2 gate columns from n0 and
     // the up columns of the same outputs, H further on; lane chunk col8 is one or the other.
     const int n0 = GATED ? tile * (N_TILE / 2) : tile * N_TILE;
-    const int ccol = GATED ? (col8 < LPR / 2 ? n0 + col8 * 8 : a.H + n0 + (col8 - LPR / 2) * 8) : n0 + col8 * 8;
+    const int ccol = GATED ? gated_col(n0 + (col8 % (LPR / 2)) * 8, col8 >= LPR / 2, a.H, a.G) : n0 + col8 * 8;
     const int k0 = slab * a.k_slab;
     const int klen = min(a.k_slab, a.K - k0);
     const int R = a.k_slab / NG;             // rows per lane group, a multiple of 8
@@ -241,7 +242,7 @@ __global__ __launch_bounds__(64 * gemv_waves(MT)) void gemv_splitk_kernel(GemvAr
     __syncthreads();
 
     trace_stamp(a.trace, a.trace_groups, 3);         // workgroup partial in LDS
-    TailArgs ta{a.Y, a.M, a.N, N_TILE, GATED ? N_TILE / 2 : 0, a.H, a.eps, a.inv_K, a.S, a.ws_partial, a.ws_sumsq, a.counter,
+    TailArgs ta{a.Y, a.M, a.N, N_TILE, GATED ? N_TILE / 2 : 0, a.H, a.G, a.eps, a.inv_K, a.S, a.ws_partial, a.ws_sumsq, a.counter,
                 a.trace, a.trace_groups};
     splitk_tail<T, MT, N_TILE, FUSED, NW, GATED>(ta, red, &s_sumsq[0][0], s_rinv, &s_last, tile, slab, n0);
 }
@@ -355,6 +356,7 @@ hipError_t launch_gemv(const Problem& p, hipStream_t s, const char** why)
     a.M = p.M; a.K = p.K; a.N = p.N; a.eps = p.eps; a.inv_K = 1.0f / float(p.K);
     a.k_slab = pl.k_slab; a.S = pl.S; a.n_tiles = pl.n_tiles;
     a.H = p.gated ? p.N / 2 : 0;
+    a.G = p.gate_group;
     a.ws_partial = p.ws_partial; a.ws_sumsq = p.ws_sumsq; a.counter = p.ws_counter;
     a.trace = p.trace; a.trace_groups = p.trace_groups;
     const bool fused = p.fused != 0, gated = p.gated != 0;

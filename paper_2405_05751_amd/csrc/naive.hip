@@ -15,9 +15,9 @@ __global__ __launch_bounds__(256) void naive_kernel(const typename Elem<T>::stor
                                                     const typename Elem<T>::store_t* __restrict__ g,
                                                     const typename Elem<T>::store_t* __restrict__ W,
                                                     typename Elem<T>::store_t* __restrict__ Y,
-                                                    int M, int K, int N, float eps, float inv_K)
+                                                    int M, int K, int N, float eps, float inv_K, int G)
 {
-    // GATED: N = 2H; output column n < H needs W columns n (gate) and H + n (up)
+    // GATED: N = 2H; output column n < H needs its gate and its up column of W (gated_col)
     const int NO = GATED ? N / 2 : N;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -34,10 +34,10 @@ __global__ __launch_bounds__(256) void naive_kernel(const typename Elem<T>::stor
             A = __fmaf_rn(x, x, A);
             xg = x * Elem<T>::to_f32(g[k]);
         }
-        float w = live ? Elem<T>::to_f32(W[size_t(k) * N + n]) : 0.f;
+        float w = live ? Elem<T>::to_f32(W[size_t(k) * N + (GATED ? gated_col(n, false, NO, G) : n)]) : 0.f;
         B = __fmaf_rn(xg, w, B);
         if (GATED) {
-            float wu = live ? Elem<T>::to_f32(W[size_t(k) * N + NO + n]) : 0.f;
+            float wu = live ? Elem<T>::to_f32(W[size_t(k) * N + gated_col(n, true, NO, G)]) : 0.f;
             U = __fmaf_rn(xg, wu, U);
         }
     }
@@ -69,10 +69,10 @@ static hipError_t launch_naive_g(const Problem& p, hipStream_t s)
     dim3 grid(((GATED ? p.N / 2 : p.N) + 63) / 64, p.M);
     if (p.fused)
         naive_kernel<T, true, GATED><<<grid, 256, 0, s>>>((const S*)p.X, (const S*)p.g, (const S*)p.W, (S*)p.Y,
-                                                          p.M, p.K, p.N, p.eps, 1.0f / float(p.K));
+                                                          p.M, p.K, p.N, p.eps, 1.0f / float(p.K), p.gate_group);
     else
         naive_kernel<T, false, GATED><<<grid, 256, 0, s>>>((const S*)p.X, nullptr, (const S*)p.W, (S*)p.Y,
-                                                           p.M, p.K, p.N, 0.f, 0.f);
+                                                           p.M, p.K, p.N, 0.f, 0.f, p.gate_group);
     return hipGetLastError();
 }
 
@@ -104,6 +104,31 @@ hipError_t launch_silu_mul(const void* Z, void* Y, int M, int H, DType dt, hipSt
     case BF16: silu_mul_kernel<Bf16><<<grid, 256, 0, s>>>((const u16*)Z, (u16*)Y, H); break;
     default:   silu_mul_kernel<float><<<grid, 256, 0, s>>>((const float*)Z, (float*)Y, H); break;
     }
+    return hipGetLastError();
+}
+
+// W [K][2H] = [gate | up] -> Wi with groups of 64 gate columns alternating with the 64 up columns of the
+// same outputs (gated_col with G = 64).  One thread per 16 bytes; H % 64 == 0.
+__global__ __launch_bounds__(256) void interleave_gate_up_kernel(const uint4_t* __restrict__ W, uint4_t* __restrict__ Wi,
+                                                                 int64_t chunks, int row_chunks, int per16, int H)
+{
+    const int64_t idx = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (idx >= chunks) return;
+    const int64_t k = idx / row_chunks;
+    const int c = int(idx % row_chunks) * per16;         // first source column of the chunk
+    const bool up = c >= H;
+    const int dst = gated_col(up ? c - H : c, up, H, 64);
+    Wi[k * row_chunks + dst / per16] = W[idx];
+}
+
+hipError_t launch_interleave_gate_up(const void* W, void* Wi, int64_t K, int H, DType dt, hipStream_t s)
+{
+    const int per16 = dt == F32 ? 4 : 8;                 // columns in 16 bytes
+    const int row_chunks = 2 * H / per16;
+    const int64_t chunks = K * row_chunks;
+    if ((chunks + 255) / 256 >= (int64_t(1) << 31)) return hipErrorInvalidValue;
+    interleave_gate_up_kernel<<<dim3((unsigned)((chunks + 255) / 256)), 256, 0, s>>>((const uint4_t*)W, (uint4_t*)Wi, chunks,
+                                                                                     row_chunks, per16, H);
     return hipGetLastError();
 }
 

@@ -34,6 +34,7 @@ struct SkinnyArgs {
     int n_tiles;
     int n_tile;      // live columns per workgroup: a multiple of 8, at most kSkinnyTile
     int H;           // gated block: N = 2H, a tile is n_tile/2 gate columns and the same up columns; else 0
+    int G;           // gated block: layout of W, see gated_col()
     int RB;          // row blocks of 64 rows in this launch (M > 64): workgroup (row block, tile, slab)
     float* ws_partial; float* ws_sumsq; unsigned* counter;
     unsigned long long* trace; int trace_groups;
@@ -102,7 +103,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
     // hn0 and the up columns of the same outputs, H further on; lane chunk i is one or the other.
     const int half = a.n_tile >> 1;
     const int n0 = GATED ? tile * half : tile * a.n_tile;
-    const int ccol = GATED ? (i * 8 < half ? n0 + i * 8 : a.H + n0 + (i * 8 - half)) : n0 + i * 8;
+    const int ccol = GATED ? gated_col(n0 + (i * 8 < half ? i * 8 : i * 8 - half), i * 8 >= half, a.H, a.G) : n0 + i * 8;
     const bool live = i * 8 < a.n_tile;      // narrower tiles leave the last column chunks idle
     const int k0 = slab * a.k_slab;
     const int klen = min(a.k_slab, a.K - k0);
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
     trace_stamp(a.trace, a.trace_groups, 3);
 
     // every row block is a problem of its own to the epilogue: its rows of Y, its share of the workspace
-    TailArgs ta{a.Y, Mh, a.N, a.n_tile, GATED ? half : 0, a.H, a.eps, a.inv_K, a.S,
+    TailArgs ta{a.Y, Mh, a.N, a.n_tile, GATED ? half : 0, a.H, a.G, a.eps, a.inv_K, a.S,
                 a.ws_partial, a.ws_sumsq, a.counter, a.trace, a.trace_groups};
     if (MULTI) {
         ta.Y += size_t(rb) * 64 * (GATED ? a.H : a.N);
@@ -410,6 +411,7 @@ hipError_t launch_skinny(const Problem& p, hipStream_t s, const char** why)
     a.M = p.M; a.K = p.K; a.N = p.N; a.eps = p.eps; a.inv_K = 1.0f / float(p.K);
     a.k_slab = pl.k_slab; a.S = pl.S; a.n_tiles = pl.n_tiles; a.n_tile = pl.n_tile;
     a.H = p.gated ? p.N / 2 : 0;
+    a.G = p.gate_group;
     a.RB = pl.RB;
     a.ws_partial = p.ws_partial; a.ws_sumsq = p.ws_sumsq; a.counter = p.ws_counter;
     a.trace = p.trace; a.trace_groups = p.trace_groups;

@@ -18,7 +18,8 @@ struct TailArgs {
     int M, N;        // N: columns of W (= row length of the partial workspace, and of Y unless gated)
     int n_live;      // columns of the tile that belong to it (<= N_TILE)
     int half;        // gated block: the tile's first `half` columns are gate columns hn0.., the next `half` the
-    int H;           //   up columns H + hn0.. of W, and Y [M][H] gets SiLU(gate) * up; half = 0: plain block
+    int H;           //   up columns of the same outputs, and Y [M][H] gets SiLU(gate) * up; half = 0: plain block
+    int G;           // gated block: where those columns lie in W, see gated_col()
     float eps, inv_K;
     int S;
     float* ws_partial; float* ws_sumsq; unsigned* counter;
@@ -59,7 +60,7 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
         return m < a.M && c < a.n_live && n0 + c < a.N;
     };
     auto wcol = [&](int c) {
-        if (GATED) return c < a.half ? n0 + c : a.H + n0 + (c - a.half);
+        if (GATED) return gated_col(n0 + (c < a.half ? c : c - a.half), c >= a.half, a.H, a.G);
         return n0 + c;
     };
     // plain block: Y = B * rinv.  Gated block: the quad is a gate quad, u the up quad of the same

@@ -31,6 +31,7 @@ struct TileArgs {
     float eps, inv_K;
     int tiles_m, tiles_n;
     int H;           // gated block: N = 2H, a tile is 128 gate columns and the up columns of the same outputs; else 0
+    int G;           // gated block: layout of W, see gated_col()
     const float* rscale;   // plain product: per-row factor applied in the epilogue, or null
     // SPLIT kernels: workgroup (tile, slab) covers k in [slab * k_slab, +k_slab) and stores its
     // fp32 tile to part [slab][M][N]; tiles_m * tiles_n workgroups per slab
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
         const int wc = (8 * wchunk) / (BN / WN), within = (8 * wchunk) % (BN / WN);
         const int jn = within / 32, jj = within % 32;
         const int hc = wc * (BN / WN / 2) + (jn % (TN / 2)) * 32 + jj;       // output column inside the tile
-        wcol = (jn >= TN / 2 ? a.H : 0) + n0 + hc;
+        wcol = gated_col(n0 + hc, jn >= TN / 2, a.H, a.G);
         wcol_ok = n0 + hc < a.H;
     }
     const int woff = wcol_ok ? (wrow * a.N + wcol) * 2 : kTileOut;
@@ -513,6 +514,7 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
         return hipErrorInvalidValue;
     }
     a.H = p.gated ? p.N / 2 : 0;
+    a.G = p.gate_group;
     a.rscale = p.fused ? nullptr : p.rscale;
     a.k_slab = 0; a.part = nullptr; a.tile_base = 0; a.tiles_here = 0;
     a.tiles_m = (p.M + BM - 1) / BM;
@@ -539,7 +541,7 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
 // column h paired with column H + h).  One thread per four output columns.
 template <typename T, bool GATED>
 __global__ __launch_bounds__(256) void tile_reduce_kernel(const float* __restrict__ part, const float* __restrict__ rscale,
-                                                          u16* __restrict__ Y, int M, int N, int S)
+                                                          u16* __restrict__ Y, int M, int N, int S, int G)
 {
     const int H = N / 2;
     const int cols4 = (GATED ? H : N) / 4;               // groups of four output columns per row
@@ -547,13 +549,14 @@ __global__ __launch_bounds__(256) void tile_reduce_kernel(const float* __restric
     if (idx >= int64_t(M) * cols4) return;
     const int row = int(idx / cols4), c = int(idx % cols4) * 4;
     const size_t slab = size_t(M) * N;
-    const float* src = part + size_t(row) * N + c;
+    const float* src = part + size_t(row) * N + (GATED ? gated_col(c, false, H, G) : c);
+    const int up = GATED ? gated_col(c, true, H, G) - gated_col(c, false, H, G) : 0;   // from the gate quad to the up quad
     float4_t v = *(const float4_t*)src, u = float4_t{0.f, 0.f, 0.f, 0.f};
-    if (GATED) u = *(const float4_t*)(src + H);
+    if (GATED) u = *(const float4_t*)(src + up);
     for (int s = 1; s < S; ++s) {
         const float4_t t = *(const float4_t*)(src + s * slab);
         v += t;
-        if (GATED) u += *(const float4_t*)(src + s * slab + H);
+        if (GATED) u += *(const float4_t*)(src + s * slab + up);
     }
     const float ri = rscale ? rscale[row] : 1.f;
     float o[4];
@@ -581,7 +584,7 @@ static hipError_t launch_tile_split(const Problem& q, int S, int k_slab, float* 
     TileArgs a;
     a.X = (const u16*)q.X; a.g = nullptr; a.W = (const u16*)q.W; a.Y = (u16*)q.Y;
     a.M = q.M; a.K = q.K; a.N = q.N; a.eps = 0.f; a.inv_K = 0.f;
-    a.H = 0; a.rscale = nullptr; a.k_slab = k_slab; a.part = part; a.tile_base = 0; a.tiles_here = 0;
+    a.H = 0; a.G = 0; a.rscale = nullptr; a.k_slab = k_slab; a.part = part; a.tile_base = 0; a.tiles_here = 0;
     a.tiles_m = (q.M + 255) / 256;
     a.tiles_n = (q.N + 255) / 256;
     dim3 grid(a.tiles_m * a.tiles_n * S);
@@ -597,11 +600,11 @@ static hipError_t launch_tile_split(const Problem& q, int S, int k_slab, float* 
     dim3 rgrid((unsigned)((groups + 255) / 256));
     u16* Y = (u16*)q.Y;
     if (q.dt == F16) {
-        if (q.gated) tile_reduce_kernel<Fp16, true><<<rgrid, 256, 0, s>>>(part, q.rscale, Y, q.M, q.N, S);
-        else         tile_reduce_kernel<Fp16, false><<<rgrid, 256, 0, s>>>(part, q.rscale, Y, q.M, q.N, S);
+        if (q.gated) tile_reduce_kernel<Fp16, true><<<rgrid, 256, 0, s>>>(part, q.rscale, Y, q.M, q.N, S, q.gate_group);
+        else         tile_reduce_kernel<Fp16, false><<<rgrid, 256, 0, s>>>(part, q.rscale, Y, q.M, q.N, S, 0);
     } else {
-        if (q.gated) tile_reduce_kernel<Bf16, true><<<rgrid, 256, 0, s>>>(part, q.rscale, Y, q.M, q.N, S);
-        else         tile_reduce_kernel<Bf16, false><<<rgrid, 256, 0, s>>>(part, q.rscale, Y, q.M, q.N, S);
+        if (q.gated) tile_reduce_kernel<Bf16, true><<<rgrid, 256, 0, s>>>(part, q.rscale, Y, q.M, q.N, S, q.gate_group);
+        else         tile_reduce_kernel<Bf16, false><<<rgrid, 256, 0, s>>>(part, q.rscale, Y, q.M, q.N, S, 0);
     }
     return hipGetLastError();
 }
@@ -662,7 +665,7 @@ static hipError_t launch_tile_rem(const Problem& q, int full, int rem, int S, in
     TileArgs a;
     a.X = (const u16*)q.X; a.g = nullptr; a.W = (const u16*)q.W; a.Y = (u16*)q.Y;
     a.M = q.M; a.K = q.K; a.N = q.N; a.eps = 0.f; a.inv_K = 0.f;
-    a.H = 0; a.rscale = nullptr; a.k_slab = k_slab; a.part = part; a.tile_base = full; a.tiles_here = rem;
+    a.H = 0; a.G = 0; a.rscale = nullptr; a.k_slab = k_slab; a.part = part; a.tile_base = full; a.tiles_here = rem;
     a.tiles_m = (q.M + 255) / 256;
     a.tiles_n = (q.N + 255) / 256;
     dim3 grid(rem * S);

@@ -118,6 +118,12 @@ def test_gated_and_tuner_reject_bad_arguments(rl):
     assert L.rmsnorm_gated_mlp(16, 16, 16, 0.0, 16, 1, 8, 0, 1, None) == ERR_INVALID
     assert L.rmsnorm_gated_mlp(16, 16, 16, -1.0, 16, 1, 8, 8, 1, None) == ERR_INVALID
     assert L.silu_mul(None, 16, 1, 8, 1, None) == ERR_INVALID
+    assert L.rmsnorm_gated_mlp_interleaved(16, 16, None, 0.0, 16, 1, 8, 64, 1, None) == ERR_INVALID
+    assert L.rmsnorm_gated_mlp_interleaved(16, 16, 16, 0.0, 16, 1, 8, 96, 1, None) == ERR_INVALID    # H % 64 != 0
+    assert "H % 64" in rl.rl_last_error()
+    assert L.rl_interleave_gate_up(16, 16, 8, 64, 1, None) == ERR_INVALID                            # same buffer
+    assert L.rl_interleave_gate_up(16, 32, 8, 32, 1, None) == ERR_INVALID
+    assert L.rl_interleave_gate_up(16, 32, 0, 64, 1, None) == ERR_INVALID
     assert L.silu_mul(16, 24, 1, 8, 1, None) == ERR_INVALID
     assert L.rl_autotune(None, 16, 16, 0.0, 16, 1, 8, 8, 1, 0, 5, None, None) == ERR_INVALID
     assert L.rl_autotune(16, 16, 16, 0.0, 16, 1, 8, 7, 1, 1, 5, None, None) == ERR_INVALID      # gated needs even N

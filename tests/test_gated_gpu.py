@@ -2,7 +2,8 @@
 fp64 oracle, through the C ABI.  Needs an MI355X.
 
 Bar: see util.compare_gated (the plain block's tolerance propagated through the gate, plus the
-output rounding).  Inputs are seeded and synthetic; W is [K][2H] = [gate | up].
+output rounding).  Inputs are seeded and synthetic; W is [K][2H] = [gate | up], or the same columns interleaved in
+groups of 64 for rmsnorm_gated_mlp_interleaved.
 """
 import numpy as np
 import pytest
@@ -186,6 +187,117 @@ def test_fast_variants_refuse_odd_halves(rl):
     for variant in ("gemv", "skinny", "tile"):
         with pytest.raises(rl.RmsnlError):
             _run(rl, w, variant)
+
+
+# ------------------------------------------------------------------ W interleaved in groups of 64
+def _interleave_host(W: np.ndarray, H: int) -> np.ndarray:
+    """[gate | up] -> groups of 64 gate columns alternating with the same outputs' 64 up columns."""
+    K = W.shape[0]
+    return np.ascontiguousarray(
+        np.stack([W[:, :H].reshape(K, H // 64, 64), W[:, H:].reshape(K, H // 64, 64)], axis=2).reshape(K, 2 * H))
+
+
+def _run_interleaved(rl, w, variant="auto", tuning=(0, 0), repack_on_device=False):
+    import torch
+    H = w.N // 2
+    X, g, W = upload(w)
+    if repack_on_device:
+        Wi = rl.rl_interleave_gate_up(W)
+    else:
+        Wi = to_device(_interleave_host(w.W, H), w.dtype)
+    rl.rl_set_variant(variant)
+    rl.rl_set_tuning(*tuning)
+    try:
+        Y = rl.rmsnorm_gated_mlp_interleaved(X, g, Wi, w.eps)
+        torch.cuda.synchronize()
+        used = rl.rl_last_variant()
+        Y2 = rl.rmsnorm_gated_mlp(X, g, W, w.eps)          # the two-halves layout, same variant and launch shape
+        torch.cuda.synchronize()
+    finally:
+        rl.rl_set_variant("auto")
+        rl.rl_set_tuning(0, 0)
+    return to_host_f64(Y, w.dtype), used, to_host_f64(Y2, w.dtype)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("K,H", [(1, 64), (37, 192), (520, 4096)])
+def test_interleave_kernel_is_the_permutation(rl, K, H, dtype):
+    import torch
+    w = workloads.make(1, K, 2 * H, dtype, 1e-5, 7650 + K + H)
+    _, _, W = upload(w)
+    Wi = rl.rl_interleave_gate_up(W)
+    torch.cuda.synchronize()
+    want = to_device(_interleave_host(w.W, H), dtype)
+    assert torch.equal(Wi.view(torch.uint8), want.view(torch.uint8))
+
+
+ISHAPES = [
+    # M, K, H with H % 64 == 0
+    (1, 64, 64), (2, 72, 192), (5, 264, 128), (8, 512, 256), (16, 1024, 2048), (17, 520, 448),
+    (33, 1032, 384), (64, 264, 576), (65, 256, 128), (100, 520, 320), (130, 1544, 256),
+    (257, 264, 192), (300, 776, 640), (512, 512, 512),
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("variant", ["auto", "gemv", "skinny", "tile", "tile_pre", "naive"])
+@pytest.mark.parametrize("M,K,H", ISHAPES)
+def test_gated_interleaved_shapes(rl, M, K, H, variant, dtype):
+    """Against the oracle on the de-interleaved W, and bit for bit against the two-halves call (the
+    arithmetic is the same, only the column a lane fetches differs)."""
+    if variant == "tile_pre" and M <= 64:
+        pytest.skip("the two-kernel form is for large M")
+    if variant == "gemv" and M > 16:
+        pytest.skip("gemv needs M <= 16")
+    w = workloads.make(M, K, 2 * H, dtype, 1e-5, 7660 + M * 3 + K + H, outlier_frac=0.1 if M > 8 else 0.0)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used, Y2 = _run_interleaved(rl, w, variant, repack_on_device=(M % 2 == 0))
+    if variant != "auto":
+        assert used == variant
+    compare_gated(Y, Z, dtype, f"gated interleaved {M}x{K}x2*{H} {dtype}/{variant}->{used}")
+    assert np.array_equal(Y, Y2), f"interleaved and two-halves results differ ({variant}->{used})"
+
+
+@pytest.mark.parametrize("variant,tuning", [("skinny", (128, 2)), ("skinny", (64, 3)), ("skinny", (32, 8)),
+                                            ("gemv", (128, 5)), ("gemv", (256, 2)), ("gemv", (512, 4)),
+                                            ("tile", (256, 4)), ("tile", (512, 8)),
+                                            ("tile_pre", (1, 1)), ("tile_pre", (1, 4))])
+def test_gated_interleaved_launch_shapes(rl, variant, tuning):
+    M = 3 if variant == "gemv" else 16 if variant == "skinny" else 300
+    w = workloads.make(M, 2056, 2 * 1088, "bf16", 1e-5, 7680 + sum(tuning))
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used, Y2 = _run_interleaved(rl, w, variant, tuning=tuning)
+    assert used == variant
+    compare_gated(Y, Z, "bf16", f"gated interleaved {variant} {tuning}")
+    assert np.array_equal(Y, Y2)
+
+
+def test_gated_interleaved_f32_and_bad_h(rl):
+    w = workloads.make(7, 100, 2 * 64, "f32", 1e-5, 7690)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    Y, used, _ = _run_interleaved(rl, w)
+    assert used == "naive"
+    compare_gated(Y, Z, "f32", "gated interleaved f32")
+    w = workloads.make(2, 64, 2 * 96, "bf16", 1e-5, 7691)            # H % 64 != 0
+    X, g, W = upload(w)
+    with pytest.raises(rl.RmsnlError):
+        rl.rmsnorm_gated_mlp_interleaved(X, g, W, w.eps)
+    with pytest.raises(rl.RmsnlError):
+        rl.rl_interleave_gate_up(W)
+
+
+def test_gateup_config_interleaved(rl):
+    """Config 4 as the gated MLP with interleaved weights, at full size, on sampled rows."""
+    import torch
+    w = workloads.config("gateup")
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps, rows=w.check_rows)
+    X, g, W = upload(w)
+    Wi = rl.rl_interleave_gate_up(W)
+    Y = rl.rmsnorm_gated_mlp_interleaved(X, g, Wi, w.eps)
+    torch.cuda.synchronize()
+    assert rl.rl_last_variant() == "skinny"
+    Yr = to_host_f64(Y[torch.from_numpy(np.asarray(w.check_rows)).cuda()], w.dtype)
+    compare_gated(Yr, Z, w.dtype, "gateup gated interleaved")
 
 
 # ------------------------------------------------------------------ the launch-shape tuner
