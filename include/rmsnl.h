@@ -40,7 +40,7 @@ typedef enum {
 typedef enum { RL_F16 = 0, RL_BF16 = 1, RL_F32 = 2 } rl_dtype;
 
 typedef enum {
-    RL_AUTO = 0,          /* pick by shape: M = 1 and N < 16384 GEMV; M <= 64 skinny, and up to M = 1024 while
+    RL_AUTO = 0,          /* pick by shape: GEMV for M = 1 and N < 10240, and for M <= 4 while K N <= 6e6; M <= 64 skinny, and up to M = 1024 while
                              ceil(M / 64) K N <= 1.4e8 (0.9e8 for N > 6144); else the two-kernel tile form, or the fused tile kernel
                              when the workspace has no room for it */
     RL_GEMV_SPLITK = 1,   /* M <= 16, no matrix cores, K split over workgroups */

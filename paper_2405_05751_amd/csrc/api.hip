@@ -121,9 +121,12 @@ rl_variant choose_auto(const Problem& p)
     if (p.dt == F32) return RL_NAIVE;
     if (p.N % 8 != 0 || p.K % 8 != 0) return RL_NAIVE;
     if (p.gated && p.N % 16 != 0) return RL_NAIVE;
-    // one row: the GEMV kernel is ahead by 2 to 8 % while W needs a split over K to fill the chip
-    // (N < 16384); without a split, and from two rows on, the matrix-core kernel is faster
-    if (p.M == 1 && p.N < 16384) return RL_GEMV_SPLITK;
+    // one row: the GEMV kernel is ahead by 2 to 8 % while W needs a deep split over K to fill the chip
+    // (measured at N <= 8192; at N = 11008, 13824, 14336 the matrix-core kernel is 10-17 % ahead).  Two
+    // to four rows: the GEMV kernel's shorter chain of dependent steps wins while W is small (2 x 2048 x
+    // 2048: 6.5 against 8.8 us, 4 x 2048 x 2048: 7.6 against 8.8 us; 2 x 3072 x 3072: 12.9 against 11.3 us).
+    if (p.M == 1 && p.N < 10240) return RL_GEMV_SPLITK;
+    if (p.M <= 4 && double(p.K) * p.N <= 6.0e6) return RL_GEMV_SPLITK;
     if (p.M <= 64) return RL_MFMA_SKINNY;
     // Above 64 rows the skinny kernel runs one row block per 64 rows in the same launch; every row
     // block pulls its own copy of W into its compute unit (from L2 after the first), so it wins

@@ -17,6 +17,7 @@
 //     partial A through to memory, the last workgroup to arrive at the tile's counter adds the S
 //     partials in slab order (so the result does not depend on arrival order), scales by
 //     1/sqrt(A/K + eps), rounds once and stores.
+#include <algorithm>
 #include "common.hpp"
 #include "splitk.hpp"
 
@@ -272,9 +273,10 @@ static GemvPlan gemv_plan(const Problem& p)
     const int gran = 8 * nw * (64 / pl.LPR);                   // 8 rows per batch and lane group
     int S = p.k_split;
     if (S <= 0) {
-        // about 512 waves' worth of workgroups per 64 compute units, but no slab shorter than two batches per lane group
+        // about 512 waves' worth of workgroups per 64 compute units, but no slab shorter than one batch per
+        // lane group (two batches measured 8-10 % slower at 2048 x 2048 and 1024 x 4096)
         S = (2048 / nw + pl.n_tiles - 1) / pl.n_tiles;
-        const int s_max = (p.K + 2 * gran - 1) / (2 * gran);
+        const int s_max = std::min(32, (p.K + gran - 1) / gran);     // (64 slabs of 8192 x 1024: 9.3 against 8.4 us)
         if (S > s_max) S = s_max;
         if (S < 1) S = 1;
     }

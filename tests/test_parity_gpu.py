@@ -208,7 +208,7 @@ def test_skinny_runs_larger_m_in_blocks_of_64_rows(rl, M, K, N, dtype):
 
 def test_mid_m_automatic_choice(rl):
     """Above 64 rows: row blocks of the skinny kernel while (row blocks) x K x N is small, the tile
-    kernels (two-kernel form, split over K) beyond; from two rows the skinny kernel."""
+    kernels (two-kernel form, split over K) beyond; from two rows the skinny kernel, unless W is small."""
     w = workloads.make(128, 2048, 2048, "bf16", 1e-5, 4900)
     Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
     Y, used = _run(rl, w, "auto")
@@ -219,10 +219,16 @@ def test_mid_m_automatic_choice(rl):
     Y, used = _run(rl, w, "auto", rows=w.check_rows)
     assert used == "tile_pre"
     compare(Y, Z, w.dtype, "auto -> tile_pre at 640x4096x8192")
-    w = workloads.make(2, 1024, 2048, "bf16", 1e-5, 4901)
+    w = workloads.make(2, 4096, 4096, "bf16", 1e-5, 4901)
     Y, used = _run(rl, w, "auto")
     assert used == "skinny"
     compare(Y, oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps), w.dtype, "auto -> skinny at M = 2")
+    for M, K, N, want in [(2, 1024, 2048, "gemv"), (4, 2048, 2048, "gemv"), (4, 3072, 3072, "skinny"),
+                          (1, 1024, 10240, "skinny"), (1, 1024, 8192, "gemv")]:
+        w = workloads.make(M, K, N, "bf16", 1e-5, 4903 + M + N)
+        Y, used = _run(rl, w, "auto")
+        assert used == want, (M, K, N, used)
+        compare(Y, oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps), w.dtype, f"auto -> {want} at {M}x{K}x{N}")
 
 
 # ------------------------------------------------------------------ two-kernel tile variant
