@@ -41,7 +41,7 @@ typedef enum { RL_F16 = 0, RL_BF16 = 1, RL_F32 = 2 } rl_dtype;
 
 typedef enum {
     RL_AUTO = 0,          /* pick by shape: GEMV for M = 1 and N < 10240, and for M <= 4 while K N <= 6e6; M <= 64 skinny, and up to M = 1024 while
-                             ceil(M / 64) K N <= 1.4e8 (0.9e8 for N > 6144); else the two-kernel tile form, or the fused tile kernel
+                             ceil(M / 64) K N <= 1.4e8 (0.9e8 for N > 6144 and M > 128); else the two-kernel tile form, or the fused tile kernel
                              when the workspace has no room for it */
     RL_GEMV_SPLITK = 1,   /* M <= 16, no matrix cores, K split over workgroups */
     RL_MFMA_SKINNY = 2,   /* matrix cores, 64 rows per workgroup (M <= 1024: a row block per 64 rows in the same

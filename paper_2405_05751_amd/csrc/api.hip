@@ -133,8 +133,10 @@ rl_variant choose_auto(const Problem& p)
     // while (row blocks) x K x N is small and loses to the tile kernels beyond about 1.4e8, earlier
     // for wide W (measured: 128x4096x6144 27 against 31 us, 512x4096x4096 37 against 43 us,
     // 1024x2048x2048 22 against 37 us; 768x1024x8192 41 against 37 us, 128x8192x10240 70 against
-    // 59 us, 256x4096x28672 131 against 81 us).
-    if (p.M <= 1024 && double((p.M + 63) / 64) * p.K * p.N <= (p.N <= 6144 ? 1.4e8 : 0.9e8)) return RL_MFMA_SKINNY;
+    // 59 us, 256x4096x28672 131 against 81 us).  With two row blocks the wide-W limit does not apply
+    // (128x4096x14336 41 against 47 us, 128x8192x8192 44 against 53 us, 128x7168x7168 40 against 45 us).
+    const int row_blocks = (p.M + 63) / 64;
+    if (p.M <= 1024 && double(row_blocks) * p.K * p.N <= (p.N <= 6144 || row_blocks == 2 ? 1.4e8 : 0.9e8)) return RL_MFMA_SKINNY;
     return RL_MFMA_TILE;
 }
 
