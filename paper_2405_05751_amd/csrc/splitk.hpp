@@ -77,6 +77,17 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
     if (a.S == 1) {
         if (tid < MT) s_rinv[tid] = FUSED ? row_scale(asum, a.inv_K, a.eps) : 1.f;
         __syncthreads();
+        if (GATED && 2 * a.half == N_TILE) {
+            // full-width gated tile: one thread per output quad, so that no thread sits out on an up quad
+            constexpr int HQ = N_TILE / 8;   // output quads per row
+#pragma unroll
+            for (int qi = 0; qi < (QPT + 1) / 2; ++qi) {
+                const int p = tid + qi * NT;
+                const int m = p / HQ, c = (p % HQ) * 4;
+                if (p < MT * HQ && live(m, c)) store_y(m, c, wg_sum(m, c), wg_sum(m, c + a.half), s_rinv[m]);
+            }
+            return;
+        }
 #pragma unroll
         for (int qi = 0; qi < QPT; ++qi) {
             const int p = tid + qi * NT;
