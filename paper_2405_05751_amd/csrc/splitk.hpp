@@ -7,6 +7,7 @@
 // bit-reproducible -- applies 1/sqrt(A/K + eps), rounds once and stores.  The counter is left at
 // zero for the next call.  No float atomics, no cache-wide write-back or invalidate.
 #pragma once
+#include <type_traits>
 #include "common.hpp"
 
 namespace rmsnl {
@@ -153,30 +154,46 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
         for (int h = 0; h < NQ; ++h) yv[qi][h] = kZero4;
         asq[qi] = 0.f;
     }
-    for (int s0 = 0; s0 < a.S; s0 += SB) {   // slabs at or beyond S are out of range: zero
-        uint4_t q[QPT][NQ][SB];
-        float u[QPT][SB];
+    // B slabs per batch (slabs at or beyond S are out of range and read as zero, but every load still
+    // takes its turn in the address unit: a batch no longer than the slab count needs, and none at all
+    // in a wave without a live quad)
+    auto gather = [&](auto batch) {
+        constexpr int B = decltype(batch)::value;
+        for (int s0 = 0; s0 < a.S; s0 += B) {
+            uint4_t q[QPT][NQ][B];
+            float u[QPT][B];
 #pragma unroll
-        for (int qi = 0; qi < QPT; ++qi)
+            for (int qi = 0; qi < QPT; ++qi)
 #pragma unroll
-            for (int j = 0; j < SB; ++j) {
-                // the whole offset goes through the range check (a scalar offset would not)
+                for (int j = 0; j < B; ++j) {
+                    // the whole offset goes through the range check (a scalar offset would not)
 #pragma unroll
-                for (int h = 0; h < NQ; ++h)
-                    q[qi][h][j] = __builtin_amdgcn_raw_buffer_load_b128(
-                        prs, int(unsigned(poff[qi][h]) + unsigned((s0 + j) * slab_bytes)), 0, kDev);
-                if (FUSED)
-                    u[qi][j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
-                        srs, int(unsigned(soff[qi]) + unsigned((s0 + j) * kSumsqStride * 4)), 0, kDev));
-            }
+                    for (int h = 0; h < NQ; ++h)
+                        q[qi][h][j] = __builtin_amdgcn_raw_buffer_load_b128(
+                            prs, int(unsigned(poff[qi][h]) + unsigned((s0 + j) * slab_bytes)), 0, kDev);
+                    if (FUSED)
+                        u[qi][j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+                            srs, int(unsigned(soff[qi]) + unsigned((s0 + j) * kSumsqStride * 4)), 0, kDev));
+                }
 #pragma unroll
-        for (int qi = 0; qi < QPT; ++qi)
+            for (int qi = 0; qi < QPT; ++qi)
 #pragma unroll
-            for (int j = 0; j < SB; ++j) {
+                for (int j = 0; j < B; ++j) {
 #pragma unroll
-                for (int h = 0; h < NQ; ++h) yv[qi][h] += __builtin_bit_cast(float4_t, q[qi][h][j]);
-                if (FUSED) asq[qi] += u[qi][j];
-            }
+                    for (int h = 0; h < NQ; ++h) yv[qi][h] += __builtin_bit_cast(float4_t, q[qi][h][j]);
+                    if (FUSED) asq[qi] += u[qi][j];
+                }
+        }
+    };
+    bool live_here = false;
+#pragma unroll
+    for (int qi = 0; qi < QPT; ++qi) live_here |= poff[qi][0] != kNowhere;
+    if (__builtin_amdgcn_ballot_w64(live_here) != 0) {   // uniform over the wave
+        bool done = false;
+        if constexpr (SB > 2) if (!done && a.S <= 2) { gather(std::integral_constant<int, 2>{}); done = true; }
+        if constexpr (SB > 4) if (!done && a.S <= 4) { gather(std::integral_constant<int, 4>{}); done = true; }
+        if constexpr (SB > 8) if (!done && a.S <= 8) { gather(std::integral_constant<int, 8>{}); done = true; }
+        if (!done) gather(std::integral_constant<int, SB>{});
     }
     trace_stamp(a.trace, a.trace_groups, 6);         // all slabs' partials read
 #pragma unroll
