@@ -147,6 +147,39 @@ def test_gemv_launch_shapes(rl, n_tile, k_split):
     compare(Y, Z, w.dtype, f"gemv n_tile={n_tile} k_split={k_split}")
 
 
+@pytest.mark.parametrize("gated", [False, True])
+@pytest.mark.parametrize("variant,M", [("gemv", 1), ("gemv", 3), ("gemv", 16), ("skinny", 5), ("skinny", 40)])
+@pytest.mark.parametrize("k_split", [2, 3, 4, 5, 8, 9, 16, 17, 32])
+def test_every_slab_count_of_the_split_k_epilogue(rl, variant, M, k_split, gated):
+    """The last arriver fetches the slabs' partials in batches sized to the slab count (2, 4, 8, 16 per
+    batch, several batches beyond): every size, with ragged tiles, and twice in a row (the arrival
+    counters must be back at zero)."""
+    import torch
+    K = 128 * 33 if variant == "gemv" else 256 * 33
+    N = 1544 if not gated else 2 * 776
+    w = workloads.make(M, K, N, "bf16", 1e-5, 3100 + M + k_split, n_check_rows=min(M, 8))
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps, rows=w.check_rows)
+    X, g, W = upload(w)
+    call = rl.rmsnorm_gated_mlp if gated else rl.rmsnorm_linear
+    rl.rl_set_variant(variant)
+    rl.rl_set_tuning(128, k_split)
+    try:
+        Y1 = call(X, g, W, w.eps)
+        Y2 = call(X, g, W, w.eps)
+        torch.cuda.synchronize()
+        assert rl.rl_last_variant() == variant
+    finally:
+        rl.rl_set_variant("auto")
+        rl.rl_set_tuning(0, 0)
+    assert torch.equal(Y1.view(torch.int16), Y2.view(torch.int16)), "same launch shape, different bits"
+    Yh = to_host_f64(Y1[torch.from_numpy(w.check_rows).cuda()], w.dtype)
+    if gated:
+        from util import compare_gated
+        compare_gated(Yh, Z, w.dtype, f"{variant} gated M={M} k_split={k_split}")
+    else:
+        compare(Yh, Z, w.dtype, f"{variant} M={M} k_split={k_split}")
+
+
 @pytest.mark.parametrize("n_tile,waves", [(256, 4), (256, 8), (512, 4), (512, 8)])
 @pytest.mark.parametrize("M,K,N", [(130, 1544, 520), (257, 264, 264), (300, 776, 1288), (512, 512, 1024)])
 def test_tile_launch_shapes(rl, M, K, N, n_tile, waves):
