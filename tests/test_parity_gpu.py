@@ -147,6 +147,36 @@ def test_gemv_launch_shapes(rl, n_tile, k_split):
     compare(Y, Z, w.dtype, f"gemv n_tile={n_tile} k_split={k_split}")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("M,K,N", [(2048, 1024, 4096), (1100, 520, 2056), (300, 4104, 264), (512, 776, 14336),
+                                   (257, 264, 8200)])
+def test_two_slabs_of_the_split_product(rl, M, K, N, dtype):
+    """Two slabs of the split product with ragged edges, the fused block and the plain product, twice in a
+    row bit for bit."""
+    import torch
+    w = workloads.make(M, K, N, dtype, 1e-5, 4950 + M + K + N, outlier_frac=0.05, n_check_rows=24)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps, rows=w.check_rows)
+    X, g, W = upload(w)
+    rows = torch.from_numpy(w.check_rows).cuda()
+    rl.rl_set_variant("tile_pre")
+    rl.rl_set_tuning(1, 2)
+    try:
+        Y1 = rl.rmsnorm_linear(X, g, W, w.eps)
+        Y2 = rl.rmsnorm_linear(X, g, W, w.eps)
+        Xn = rl.rmsnorm(X, g, w.eps)
+        P1 = rl.matmul(Xn, W)
+        torch.cuda.synchronize()
+        assert rl.rl_last_variant() == "tile_pre"
+    finally:
+        rl.rl_set_variant("auto")
+        rl.rl_set_tuning(0, 0)
+    assert torch.equal(Y1.view(torch.int16), Y2.view(torch.int16))
+    compare(to_host_f64(Y1[rows], dtype), Z, dtype, f"two slabs {M}x{K}x{N} {dtype}")
+    # the plain product of the rounded normalised rows: one more rounding than the fused block
+    Zp = oracle.matmul_f64(to_host_f64(Xn[rows], dtype), oracle.decode(w.W, dtype))
+    compare(to_host_f64(P1[rows], dtype), Zp, dtype, f"two slabs, plain product {M}x{K}x{N} {dtype}")
+
+
 @pytest.mark.parametrize("gated", [False, True])
 @pytest.mark.parametrize("variant,M", [("gemv", 1), ("gemv", 3), ("gemv", 16), ("skinny", 5), ("skinny", 40)])
 @pytest.mark.parametrize("k_split", [2, 3, 4, 5, 8, 9, 16, 17, 32])
