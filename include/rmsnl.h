@@ -70,6 +70,26 @@ rl_status rmsnorm_linear(const void* X, const void* g, const void* W, float eps,
                          int64_t M, int64_t K, int64_t N, rl_dtype dt, void* stream);
 
 /*
+ * rmsnorm_linear for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same launch shapes and
+ * the same result, bit for bit, as rmsnorm_linear; the difference is where the split-K kernels keep
+ * their arrival counters and fp32 partial sums: in a fixed device array that is part of the library's
+ * code object (rl_noalloc_scratch_bytes() = 8 MiB, of which 1280 KiB are counters and partial sums of
+ * squares; every device the library runs on holds its own copy until the process ends), never in
+ * memory from hipMalloc.  The call allocates nothing, frees nothing and does not synchronise; it
+ * ignores rl_set_workspace.  The first call on a device looks the array's address up and enqueues a
+ * small kernel on `stream` that zeroes the counters.
+ * A shape whose split-K partials do not fit returns RL_ERR_WORKSPACE ("fixed scratch buffer") and
+ * launches nothing; the two-kernel tile form, which would need 2 M K bytes, gives way to the one fused
+ * tile kernel, which needs none.
+ * All calls on a device share that device's array: calls that overlap in time on one device (different
+ * streams, or a graph replayed beside another call) race on it and must be ordered by the caller.
+ */
+rl_status rmsnorm_linear_noalloc(const void* X, const void* g, const void* W, float eps, void* Y,
+                                 int64_t M, int64_t K, int64_t N, rl_dtype dt, void* stream);
+size_t rl_noalloc_scratch_bytes(void);
+
+/*
  * Unfused pair, for A/B comparison with the fused call (the two-kernel baseline of
  * Fig. 2a: the normalised intermediate goes through device memory).
  *

@@ -29,6 +29,10 @@ EXPORTS = {
     "rmsnorm_linear": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
                                       ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                       ctypes.c_int, ctypes.c_void_p]),
+    "rmsnorm_linear_noalloc": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
+                                              ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                              ctypes.c_int, ctypes.c_void_p]),
+    "rl_noalloc_scratch_bytes": (ctypes.c_size_t, []),
     "rmsnorm": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
                                ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]),
     "matmul": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
@@ -135,6 +139,24 @@ def rmsnorm_linear(X: torch.Tensor, g: torch.Tensor, W: torch.Tensor, eps: float
     _check(lib().rmsnorm_linear(_dev(X, "X"), _dev(g, "g"), _dev(W, "W"), float(eps), _dev(Y, "Y"),
                                 M, K, N, _DTYPES[X.dtype], _stream(stream)))
     return Y
+
+
+def rmsnorm_linear_noalloc(X: torch.Tensor, g: torch.Tensor, W: torch.Tensor, eps: float, Y: torch.Tensor,
+                           stream=None) -> torch.Tensor:
+    """rmsnorm_linear through the entry point that allocates nothing; the caller brings Y."""
+    M, K = X.shape
+    K2, N = W.shape
+    if K2 != K or g.shape != (K,) or X.dtype != W.dtype or X.dtype != g.dtype:
+        raise ValueError("shape or dtype mismatch")
+    if Y.shape != (M, N) or Y.dtype != X.dtype:
+        raise ValueError("Y has the wrong shape or dtype")
+    _check(lib().rmsnorm_linear_noalloc(_dev(X, "X"), _dev(g, "g"), _dev(W, "W"), float(eps), _dev(Y, "Y"),
+                                        M, K, N, _DTYPES[X.dtype], _stream(stream)))
+    return Y
+
+
+def rl_noalloc_scratch_bytes() -> int:
+    return int(lib().rl_noalloc_scratch_bytes())
 
 
 def rmsnorm(X: torch.Tensor, g: torch.Tensor, eps: float, Xn: Optional[torch.Tensor] = None,

@@ -116,6 +116,45 @@ void carve(const Workspace& ws, Problem& p)
     p.ws_partial = reinterpret_cast<float*>(base + kHeadBytes);
 }
 
+// ---- the workspace of the entry point that allocates nothing: a file-scope device array.  Every
+// device the library runs on holds its own copy, at its own address, until the process ends; the
+// array's name is only a host-side handle, and the address the kernels get is looked up once per
+// device.  Same layout as every other workspace (see carve()).
+constexpr size_t kScratchBytes = size_t(8) << 20;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+namespace {
+void* g_scratch[kMaxDevices] = {};       // device address of the current device's copy, once looked up
+
+__global__ void scratch_clear_kernel(unsigned* p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+rl_status get_scratch(hipStream_t s, Workspace* out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(RL_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(RL_ERR_UNSUPPORTED, "device index out of range");
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_scratch[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return fail(RL_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        // the arrival counters must start at zero (the kernels leave them at zero after every call); a
+        // fill kernel, not a memset, so that a caller may capture this first call into a graph
+        const int n = int(kCounterBytes / sizeof(unsigned));
+        scratch_clear_kernel<<<(n + 255) / 256, 256, 0, s>>>(static_cast<unsigned*>(ptr), n);
+        e = hipGetLastError();
+        if (e != hipSuccess) return fail(RL_ERR_HIP, "clearing the scratch counters: %s", hipGetErrorString(e));
+        g_scratch[dev] = ptr;
+    }
+    *out = Workspace{g_scratch[dev], kScratchBytes, false};
+    return RL_OK;
+}
+
 rl_variant choose_auto(const Problem& p)
 {
     if (p.dt == F32) return RL_NAIVE;
@@ -151,7 +190,9 @@ bool prefers_two_kernels(const Problem& p)
 }
 
 // one attempt at one variant; hipErrorInvalidValue = the variant cannot run the shape
-hipError_t launch_variant(rl_variant v, Problem& p, hipStream_t s, const char** why, rl_status* ws_status)
+// fixed: the one workspace this call may use (nothing is allocated), or null for the library's own or the lent one
+hipError_t launch_variant(rl_variant v, Problem& p, hipStream_t s, const char** why, rl_status* ws_status,
+                          const Workspace* fixed = nullptr)
 {
     *ws_status = RL_OK;
     size_t need = 0;
@@ -161,7 +202,13 @@ hipError_t launch_variant(rl_variant v, Problem& p, hipStream_t s, const char** 
     p.ws_partial = nullptr; p.ws_sumsq = nullptr; p.ws_counter = nullptr;
     if (need) {
         Workspace ws;
-        *ws_status = get_workspace(need, s, &ws);
+        if (fixed) {
+            ws = *fixed;
+            *ws_status = ws.bytes >= need + kHeadBytes ? RL_OK
+                : fail(RL_ERR_WORKSPACE, "the shape needs more than the fixed scratch buffer holds (8 MiB in all)");
+        } else {
+            *ws_status = get_workspace(need, s, &ws);
+        }
         if (*ws_status != RL_OK) return hipErrorUnknown;
         carve(ws, p);
     }
@@ -175,7 +222,7 @@ hipError_t launch_variant(rl_variant v, Problem& p, hipStream_t s, const char** 
     }
 }
 
-rl_status run(Problem& p, void* stream)
+rl_status run(Problem& p, void* stream, const Workspace* fixed = nullptr)
 {
     rl_variant forced;
     Tuned tuned{RL_AUTO, 0, 0};
@@ -217,7 +264,7 @@ rl_status run(Problem& p, void* stream)
             p.k_split = use_tuned ? tuned.k_split : 0;
         }
         rl_status ws_status;
-        hipError_t e = launch_variant(v, p, s, &why, &ws_status);
+        hipError_t e = launch_variant(v, p, s, &why, &ws_status, fixed);
         if (ws_status != RL_OK) {
             // the two-kernel form is an optimisation: without room for it the fused kernel runs
             if (forced == RL_AUTO && v == RL_MFMA_TILE_PRE && ws_status == RL_ERR_WORKSPACE) continue;
@@ -248,6 +295,25 @@ rl_status rmsnorm_linear(const void* X, const void* g, const void* W, float eps,
     p.eps = eps; p.fused = 1; p.dt = DType(dt);
     return run(p, stream);
 }
+
+rl_status rmsnorm_linear_noalloc(const void* X, const void* g, const void* W, float eps, void* Y,
+                                 int64_t M, int64_t K, int64_t N, rl_dtype dt, void* stream)
+{
+    if (!X || !g || !W || !Y) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (rl_status st = check_dims(M, K, N, dt)) return st;
+    if (!std::isfinite(eps) || eps < 0.f) return fail(RL_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    if (!aligned16(X) || !aligned16(g) || !aligned16(W) || !aligned16(Y))
+        return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    Workspace ws;
+    if (rl_status st = get_scratch(static_cast<hipStream_t>(stream), &ws)) return st;
+    Problem p{};
+    p.X = X; p.g = g; p.W = W; p.Y = Y;
+    p.M = int(M); p.K = int(K); p.N = int(N);
+    p.eps = eps; p.fused = 1; p.dt = DType(dt);
+    return run(p, stream, &ws);
+}
+
+size_t rl_noalloc_scratch_bytes(void) { return kScratchBytes; }
 
 rl_status rmsnorm_gated_mlp(const void* X, const void* g, const void* W, float eps, void* Y,
                             int64_t M, int64_t K, int64_t H, rl_dtype dt, void* stream)
