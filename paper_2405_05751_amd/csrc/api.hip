@@ -424,7 +424,7 @@ rl_status rl_autotune(const void* X, const void* g, const void* W, float eps, vo
             for (int nt : {128, 256, 512})
                 for (int ks : {0, 4, 8, 16, 32}) cands.push_back({RL_GEMV_SPLITK, nt, ks});
         if (M <= 1024)
-            for (int ks : {1, 2, 4, 8, 16}) cands.push_back({RL_MFMA_SKINNY, 0, ks});
+            for (int ks = 1; ks <= 16; ++ks) cands.push_back({RL_MFMA_SKINNY, 0, ks});
         if (M > 16)
             for (int shape : {256, 512})
                 for (int nw : {4, 8}) cands.push_back({RL_MFMA_TILE, shape, nw});

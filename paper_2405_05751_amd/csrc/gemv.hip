@@ -40,21 +40,50 @@ constexpr int kWAux = 2;             // cache policy of the W loads: nt (streame
 constexpr int kOut = 0x7ffffff0;     // a byte offset beyond any buffer resource: reads as zero
 constexpr int kRsrcFlags = 0x00020000;
 
-// batches of 8 rows in flight per lane
-constexpr int gemv_depth(int MT) { return MT <= 2 ? 4 : 2; }
+// batches of 8 rows in flight per lane.  Up to four rows of X (the automatic choice's range) W goes
+// through LDS, two batches deep: a compute unit keeps about 32 KiB of loads in flight whatever the
+// kernel asks for, so a deeper queue buys nothing, and 64 KiB of ring lets two workgroups share a unit.
+constexpr bool gemv_w_lds(int MT) { return MT <= 4; }
+constexpr int gemv_depth(int MT) { return 2; }
+constexpr int kGemvBatchBytes = 8 * 1024;     // 8 wave-wide loads of 1 KiB
+
+// s_waitcnt for the vector-memory counter alone (n <= 63)
+#define RL_GEMV_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 // waves per workgroup (8, in half as many workgroups, measured 6 % slower at the decode projection)
 constexpr int gemv_waves(int MT) { return 4; }
 
+// What the first loads need comes as leading scalar arguments: the dispatcher preloads up to 14
+// dwords of those into registers before the wave starts, so the first loads of W do not wait for
+// a fetch of the argument block (a round trip to memory at the head of every launch).  The rest
+// rides in a struct behind them and is fetched while the loads are in flight.
+struct GemvCold {
+    u16* Y;
+    float eps, inv_K;
+    int H, G;
+    float* ws_partial; float* ws_sumsq; unsigned* counter;
+    unsigned long long* trace; int trace_groups;
+};
+
 template <typename T, int MT, int LPR, bool FUSED, bool GATED>
-__global__ __launch_bounds__(64 * gemv_waves(MT)) void gemv_splitk_kernel(GemvArgs a)
+__global__ __launch_bounds__(64 * gemv_waves(MT)) void gemv_splitk_kernel(
+    const uint4_t* W, const u16* X, const u16* g, int M, int K, int N, int k_slab, int S, int n_tiles, GemvCold cold)
 {
+    GemvArgs a;
+    a.X = X; a.g = g; a.W = W; a.Y = cold.Y;
+    a.M = M; a.K = K; a.N = N; a.eps = cold.eps; a.inv_K = cold.inv_K;
+    a.k_slab = k_slab; a.S = S; a.n_tiles = n_tiles; a.H = cold.H; a.G = cold.G;
+    a.ws_partial = cold.ws_partial; a.ws_sumsq = cold.ws_sumsq; a.counter = cold.counter;
+    a.trace = cold.trace; a.trace_groups = cold.trace_groups;
     constexpr int NW = gemv_waves(MT);
     constexpr int N_TILE = LPR * 8;
     constexpr int RPI = 64 / LPR;            // lane groups per wave = W rows per wave-wide load
     constexpr int NG = NW * RPI;             // lane groups per workgroup
     constexpr int D = gemv_depth(MT);
     constexpr bool XLDS = MT > 4;            // X-hat through LDS instead of registers
-    extern __shared__ float smem[];          // XLDS: xs [MT][k_slab]; later red [NW][MT][N_TILE]
+    constexpr bool WLDS = gemv_w_lds(MT);    // W through LDS (direct loads) instead of registers
+    constexpr int RING = WLDS ? NW * D * kGemvBatchBytes : 0;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];   // WLDS: the W ring first
+    float* smem = reinterpret_cast<float*>(smem_raw + RING);                   // XLDS: xs [MT][k_slab]; later red [NW][MT][N_TILE]
     __shared__ float s_sumsq[NW][MT];
     __shared__ float s_rinv[MT];
     __shared__ int s_last;
@@ -91,12 +120,31 @@ __global__ __launch_bounds__(64 * gemv_waves(MT)) void gemv_splitk_kernel(GemvAr
     const int wrow = a.N * 2;
     const int voff0 = (r0 * a.N + ccol) * 2;
 
-    uint4_t w[D][8];
+    // W through LDS: a direct load writes lane l's 16 bytes at byte 16 l of its KiB, so batch slot d
+    // of this wave is [8 loads][64 lanes][16 bytes] and every lane reads back exactly what it
+    // asked for.  Measured against loads into registers on the same access shape: the stream of a
+    // 1 x 4096 x 4096 launch ends 2 us earlier (data that lands in LDS does not queue for the
+    // register file's write port).  The compiler cannot see these loads, so the wait for a batch
+    // is placed by hand: loads complete in order, and the count passed to s_waitcnt is the
+    // number of loads issued after the batch's last one.
+    const uint32_t ring = uint32_t(uintptr_t(smem_raw)) + uint32_t(wave) * (D * kGemvBatchBytes);
+    const uint4_t wdesc = {uint32_t(uintptr_t(a.W + size_t(k0) * (a.N >> 3))), uint32_t(uintptr_t(a.W + size_t(k0) * (a.N >> 3)) >> 32),
+                           uint32_t(klen * a.N * 2), uint32_t(kRsrcFlags)};
+    auto load_w_lds = [&](uint32_t dst, int v) {
+        const uint4_t desc = wdesc;
+        uint32_t keep;                       // M0 carries the LDS address; whatever it held is put back
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                     "buffer_load_dwordx4 %2, %3, 0 offen nt lds\n\ts_mov_b32 m0, %0"
+                     : "=&s"(keep) : "s"(dst), "v"(v), "s"(desc) : "memory");
+    };
+    uint4_t w[WLDS ? 1 : D][8];
     uint4_t xq[D][XLDS ? 1 : MT], gq[D];
-    auto issue = [&](int bi, int d) {        // batch bi of this group into register set d
+    auto issue = [&](int bi, int d) {        // batch bi of this group into register set (or ring slot) d
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            w[d][j] = __builtin_amdgcn_raw_buffer_load_b128(wrs, voff0 + (bi * 8 + j) * wrow, 0, kWAux);
+        for (int j = 0; j < 8; ++j) {
+            if (WLDS) load_w_lds(__builtin_amdgcn_readfirstlane(ring + d * kGemvBatchBytes + j * 1024), voff0 + (bi * 8 + j) * wrow);
+            else w[d][j] = __builtin_amdgcn_raw_buffer_load_b128(wrs, voff0 + (bi * 8 + j) * wrow, 0, kWAux);
+        }
         if (!XLDS) {
             const int koff = (r0 + bi * 8 < klen) ? (k0 + r0 + bi * 8) * 2 : kOut;
             if (FUSED) gq[d] = __builtin_amdgcn_raw_buffer_load_b128(grs, koff, 0, 0);
@@ -156,7 +204,22 @@ __global__ __launch_bounds__(64 * gemv_waves(MT)) void gemv_splitk_kernel(GemvAr
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[m][e] = 0.f;
 
+    // loads issued per batch after its W loads: g (fused only) and the rows of X
+    constexpr int kAfterW = (XLDS ? 0 : MT) + ((FUSED && !XLDS) ? 1 : 0);
     auto consume = [&](int bi, int d) {
+        constexpr int WS = WLDS ? 0 : 1;     // (register mode indexes w by slot, LDS mode has one set)
+        if (WLDS) {
+            // batches bi .. min(bi + D - 1, nB - 1) are in flight; D = 2
+            if (bi + 1 < nB) RL_GEMV_WAIT_VM(kAfterW + 8 + kAfterW);
+            else RL_GEMV_WAIT_VM(kAfterW);
+            asm volatile("" ::: "memory");
+            const unsigned char* slot = smem_raw + wave * (D * kGemvBatchBytes) + d * kGemvBatchBytes + lane * 16;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) w[0][j] = *reinterpret_cast<const uint4_t*>(slot + j * 1024);
+            // the slot may be refilled once these reads have returned
+            __builtin_amdgcn_s_waitcnt(0xc07f);          // lgkmcnt(0)
+            asm volatile("" ::: "memory");
+        }
         float h[MT][8];
         if (XLDS) {
 #pragma unroll
@@ -186,8 +249,8 @@ __global__ __launch_bounds__(64 * gemv_waves(MT)) void gemv_splitk_kernel(GemvAr
             float wf[8];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                wf[2 * e] = Elem<T>::lo(w[d][j][e]);
-                wf[2 * e + 1] = Elem<T>::hi(w[d][j][e]);
+                wf[2 * e] = Elem<T>::lo(w[WS * d][j][e]);
+                wf[2 * e + 1] = Elem<T>::hi(w[WS * d][j][e]);
             }
 #pragma unroll
             for (int m = 0; m < MT; ++m)
@@ -295,7 +358,8 @@ static GemvPlan gemv_plan(const Problem& p)
     if (int64_t(S + 16) * p.M * p.N * 4 >= (int64_t(1) << 31)) { pl.why = "split-K partials too large"; return pl; }
     const size_t xs = pl.MT > 4 ? size_t(k_slab) * pl.MT * 4 : 0;
     const size_t red = size_t(nw) * pl.MT * n_tile * 4;
-    pl.lds = xs > red ? xs : red;
+    const size_t ring = gemv_w_lds(pl.MT) ? size_t(nw) * gemv_depth(pl.MT) * kGemvBatchBytes : 0;
+    pl.lds = ring + (xs > red ? xs : red);
     pl.ok = true;
     return pl;
 }
@@ -314,12 +378,15 @@ static hipError_t gemv_go(const GemvArgs& a, bool fused, bool gated, const GemvP
     static LdsOnce once;                     // allow more than 64 KiB of dynamic LDS
     hipError_t e = raise_lds_once(once, {(const void*)gemv_splitk_kernel<T, MT, LPR, true, false>,
                                          (const void*)gemv_splitk_kernel<T, MT, LPR, false, false>,
-                                         (const void*)gemv_splitk_kernel<T, MT, LPR, true, true>}, 96 * 1024);
+                                         (const void*)gemv_splitk_kernel<T, MT, LPR, true, true>}, 128 * 1024);
     if (e != hipSuccess) return e;
     const int nt = 64 * gemv_waves(MT);
-    if (gated)      gemv_splitk_kernel<T, MT, LPR, true, true><<<grid, nt, pl.lds, s>>>(a);
-    else if (fused) gemv_splitk_kernel<T, MT, LPR, true, false><<<grid, nt, pl.lds, s>>>(a);
-    else            gemv_splitk_kernel<T, MT, LPR, false, false><<<grid, nt, pl.lds, s>>>(a);
+    const GemvCold c{a.Y, a.eps, a.inv_K, a.H, a.G, a.ws_partial, a.ws_sumsq, a.counter, a.trace, a.trace_groups};
+#define RL_GEMV_ARGS a.W, a.X, a.g, a.M, a.K, a.N, a.k_slab, a.S, a.n_tiles, c
+    if (gated)      gemv_splitk_kernel<T, MT, LPR, true, true><<<grid, nt, pl.lds, s>>>(RL_GEMV_ARGS);
+    else if (fused) gemv_splitk_kernel<T, MT, LPR, true, false><<<grid, nt, pl.lds, s>>>(RL_GEMV_ARGS);
+    else            gemv_splitk_kernel<T, MT, LPR, false, false><<<grid, nt, pl.lds, s>>>(RL_GEMV_ARGS);
+#undef RL_GEMV_ARGS
     return hipGetLastError();
 }
 

@@ -29,7 +29,8 @@ struct SkinnyArgs {
     const u16* X; const u16* g; const uint4_t* W; u16* Y;
     int M, K, N;
     float eps, inv_K;
-    int k_slab;      // rows of W per slab, a multiple of 64 rows x the waves of a workgroup
+    int k_slab;      // most rows of W in a slab (a multiple of 64): slab s takes the 64-row runs
+                     // [s R / S, (s + 1) R / S) of the R = ceil(K / 64) runs, so slabs differ by at most one run
     int S;
     int n_tiles;
     int n_tile;      // live columns per workgroup: a multiple of 8, at most kSkinnyTile
@@ -40,6 +41,9 @@ struct SkinnyArgs {
     unsigned long long* trace; int trace_groups;
 };
 
+#ifndef RL_SKINNY_TWO_PART
+#define RL_SKINNY_TWO_PART 1
+#endif
 constexpr int kSkinnyTile = 128;     // most columns per workgroup (16 lanes x 8)
 constexpr int kSkAux = 2;            // W loads: nt
 constexpr int kSkOut = 0x7ffffff0;
@@ -64,10 +68,28 @@ template <> struct Mfma16<Fp16> {
 constexpr int skinny_depth(int MB) { return MB == 1 ? 4 : 3; }
 constexpr int skinny_waves(int MB) { return 4; }    // 8 (two waves per SIMD at MB = 1) measured equal or up to 20 % slower
 
+// Leading scalar arguments are preloaded into registers by the dispatcher (see the GEMV kernel);
+// what the first loads do not need follows in a struct.
+struct SkinnyCold {
+    u16* Y;
+    float eps, inv_K;
+    int H, G;
+    float* ws_partial; float* ws_sumsq; unsigned* counter;
+    unsigned long long* trace; int trace_groups;
+};
+
 // MULTI: the launch holds several row blocks of 64 rows (M > 64; MB = 4 then).
 template <typename T, int MB, bool FUSED, bool GATED, bool MULTI = false>
-__global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArgs a)
+__global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(
+    const uint4_t* W, const u16* X, const u16* g, int M, int K, int N, int k_slab, int S, int n_tiles, int n_tile,
+    int RB, SkinnyCold cold)
 {
+    SkinnyArgs a;
+    a.X = X; a.g = g; a.W = W; a.Y = cold.Y;
+    a.M = M; a.K = K; a.N = N; a.eps = cold.eps; a.inv_K = cold.inv_K;
+    a.k_slab = k_slab; a.S = S; a.n_tiles = n_tiles; a.n_tile = n_tile; a.H = cold.H; a.G = cold.G; a.RB = RB;
+    a.ws_partial = cold.ws_partial; a.ws_sumsq = cold.ws_sumsq; a.counter = cold.counter;
+    a.trace = cold.trace; a.trace_groups = cold.trace_groups;
     constexpr int NW = skinny_waves(MB);
     constexpr int MT = 16 * MB;
     constexpr int N_TILE = kSkinnyTile;
@@ -105,9 +127,13 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
     const int n0 = GATED ? tile * half : tile * a.n_tile;
     const int ccol = GATED ? gated_col(n0 + (i * 8 < half ? i * 8 : i * 8 - half), i * 8 >= half, a.H, a.G) : n0 + i * 8;
     const bool live = i * 8 < a.n_tile;      // narrower tiles leave the last column chunks idle
-    const int k0 = slab * a.k_slab;
-    const int klen = min(a.k_slab, a.K - k0);
-    const int nPairs = a.k_slab / (64 * NW); // 64-row runs per wave (uniform; rows past klen read zero)
+    const int runs = (a.K + 63) >> 6;        // 64-row runs of W in all
+    const int run0 = int(int64_t(slab) * runs / a.S), run1 = int(int64_t(slab + 1) * runs / a.S);
+    const int k0 = run0 * 64;
+    const int klen = min(run1 * 64, a.K) - k0;
+    // runs of this wave: wave w takes runs w, w + NW, ... of the slab (the waves of a workgroup may
+    // differ by one; nothing in the K loop is shared between them)
+    const int nPairs = (run1 - run0 - wave + NW - 1) / NW;
 
     const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint4_t*>(a.W + size_t(k0) * (a.N >> 3)), 0, klen * a.N * 2, kSkFlags);
@@ -187,9 +213,17 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) ss[mb] = 0.f;
 
+    // X-hat = X (.) g is exact in fp32 (two 16-bit significands), but the matrix cores take 16-bit
+    // operands.  Up to 32 rows this kernel has matrix-core time to spare, so X-hat goes in as two
+    // operands, its rounded value and the rounding's remainder (hi + lo, each exact in the storage
+    // type, together good to 16 more bits), at two matrix instructions per step: the result then
+    // carries no rounding of X-hat at all, only the final one of Y.  From 33 rows on the second
+    // instruction is not free any more (64 x 4096 x 28672: +5 %; several row blocks: +20 %), and
+    // X-hat is rounded once, as the tile kernels round it.
+    constexpr bool TWO = FUSED && RL_SKINNY_TWO_PART && MB <= 2;
     auto consume = [&](int d, int h) {
-        // A operands: X-hat = X (.) g rounded once to the storage type; squares of the raw X
-        uint4_t aop[MB], gq;
+        // A operands: X-hat = X (.) g in the storage type (see above); squares of the raw X
+        uint4_t aop[MB], alo[TWO ? MB : 1], gq;
         if (FUSED) gq = *reinterpret_cast<const uint4_t*>(stage + st_g + ((2 * q + h) << 4));
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
@@ -200,7 +234,9 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
                     const float x0 = Elem<T>::lo(xq[e]), x1 = Elem<T>::hi(xq[e]);
                     ss[mb] = __fmaf_rn(x0, x0, ss[mb]);
                     ss[mb] = __fmaf_rn(x1, x1, ss[mb]);
-                    aop[mb][e] = Elem<T>::pack(x0 * Elem<T>::lo(gq[e]), x1 * Elem<T>::hi(gq[e]));
+                    const float p0 = x0 * Elem<T>::lo(gq[e]), p1 = x1 * Elem<T>::hi(gq[e]);
+                    aop[mb][e] = Elem<T>::pack(p0, p1);
+                    if (TWO) alo[mb][e] = Elem<T>::pack(p0 - Elem<T>::lo(aop[mb][e]), p1 - Elem<T>::hi(aop[mb][e]));
                 }
             } else {
                 aop[mb] = xq;
@@ -215,7 +251,10 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(SkinnyArg
                 bop[t] = __builtin_amdgcn_perm(w[d][2 * t + 1][c >> 1], w[d][2 * t][c >> 1],
                                                (c & 1) ? 0x07060302u : 0x05040100u);
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) acc[mb][c] = Mfma16<T>::run(aop[mb], bop, acc[mb][c]);
+            for (int mb = 0; mb < MB; ++mb) {
+                acc[mb][c] = Mfma16<T>::run(aop[mb], bop, acc[mb][c]);
+                if (TWO) acc[mb][c] = Mfma16<T>::run(alo[mb], bop, acc[mb][c]);
+            }
         }
     };
 
@@ -310,32 +349,46 @@ static SkinnyPlan skinny_plan(const Problem& p)
     pl.RB = (p.M + 63) / 64;                 // row blocks of 64 rows, all in one launch
     pl.MB = pl.RB > 1 ? 4 : (p.M + 15) / 16;
     const int Mb = std::min(p.M, 64);        // rows per workgroup
-    const int gran = 64 * skinny_waves(pl.MB);
+    const int runs = (p.K + 63) / 64;        // 64-row runs of W; a slab is a whole number of them
+    const int nw = skinny_waves(pl.MB);
     int n_tile = p.n_tile, S = p.k_split;
     if (n_tile == 0 || S <= 0) {
-        // Pick the slab count with a small cost model.  W streams at the HBM rate this kernel
-        // reaches (5.7 TB/s) unless the compute units holding workgroups cannot pull their share
-        // of W plus their slab of X that fast (about 36 GB/s each in this kernel; with more
-        // workgroups than units some units hold several, one after the other as far as the
-        // stream is concerned); every extra slab costs the split-K epilogue's latency plus a
-        // write and a read of an fp32 partial tile set.
+        // Pick the slab count with a small cost model, fitted to a sweep of every slab count over 65
+        // shapes (M 2 to 64; W from 1024 x 4096 to 28672 x 8192): the pick is within 1.5 % of the best
+        // slab count on average, 9 % at worst.  W streams at the HBM rate unless the compute units
+        // holding workgroups cannot pull their share of W plus their slab of X that fast (a unit
+        // takes in about 45 GB/s; with more workgroups than units some units hold several, one
+        // after the other as far as the stream is concerned: a launch of just over 256 workgroups
+        // measured up to 30 % slower than one of just under); every extra slab costs a write and a
+        // read of an fp32 partial tile set on top of the epilogue's fixed latency.
         double best = 1e30;
         int best_nt = kSkinnyTile, best_s = 1;
         // (narrower tiles measured slower: their row segments stop being whole 128-byte lines, so
         // the width stays at 128 unless the caller asks otherwise)
         for (int nt = (p.n_tile ? p.n_tile : kSkinnyTile); nt >= (p.n_tile ? p.n_tile : kSkinnyTile); nt -= 8) {
             const int tiles = (p.N + nt - 1) / nt;
-            for (int s = (p.k_split > 0 ? p.k_split : 1); s <= (p.k_split > 0 ? p.k_split : 16); s *= 2) {
-                if (s > 1 && 2 * s * gran > p.K) break;
+            for (int s = (p.k_split > 0 ? p.k_split : 1); s <= (p.k_split > 0 ? p.k_split : 16); ++s) {
+                if (s > 1 && s * nw > runs) break;                                           // at least one run per wave
                 if (int64_t(tiles) * pl.RB > kMaxCounters || int64_t(tiles) * pl.RB * s * kSumsqStride > kMaxSumsqFloats) continue;
                 if (s > 1 && int64_t(s) * pl.RB * 64 * p.N * 4 > (int64_t(48) << 20)) continue;   // fits the library workspace
-                const double bytes = double(p.K) * p.N * 2.0;                                // W comes from HBM once
                 const double wgs = double(tiles) * s * pl.RB;
-                const double wg_bytes = (double(p.K) / s) * (nt * 2.0 + Mb * 2.0);           // its W and its X
-                const double per_unit = double((int64_t(wgs) + 255) / 256) * wg_bytes / 36.0e3;
-                const double stream_us = std::max(bytes / 5.7e6, per_unit);
-                const double tail_us = s > 1 ? 3.0 + 2.0 * s * double(p.M) * p.N * 4.0 / 2.0e6 : 0.5;
-                const double t = stream_us + tail_us;
+                const double slab_rows = 64.0 * ((runs + s - 1) / s);                        // the longest slab
+                const double wg_bytes = slab_rows * (nt * 2.0 + Mb * 2.0);                   // its W and its X
+                double t;
+                if (pl.RB == 1) {
+                    const double hbm_us = double(p.K) * p.N * 2.0 / 6.5e6;                   // W comes from HBM once
+                    const double unit_us = double((int64_t(wgs) + 255) / 256) * wg_bytes / 45.0e3;
+                    const double stream_us = std::max(hbm_us, unit_us) + 0.15 * std::min(hbm_us, unit_us);
+                    const double tail_us = s > 1 ? 2.0 + 0.05 * s + 0.35 * s * double(p.M) * p.N * 8.0 / 1.0e6 : 0.0;
+                    t = stream_us + tail_us;
+                } else {
+                    // several row blocks (M > 64): the first model, which the choice between this
+                    // kernel and the tile kernels was measured with
+                    const double per_unit = double((int64_t(wgs) + 255) / 256) * wg_bytes / 36.0e3;
+                    const double stream_us = std::max(double(p.K) * p.N * 2.0 / 5.7e6, per_unit);
+                    const double tail_us = s > 1 ? 3.0 + 2.0 * s * double(p.M) * p.N * 4.0 / 2.0e6 : 0.5;
+                    t = stream_us + tail_us;
+                }
                 if (t < best) { best = t; best_nt = nt; best_s = s; }
             }
         }
@@ -344,13 +397,12 @@ static SkinnyPlan skinny_plan(const Problem& p)
     }
     pl.n_tile = n_tile;
     pl.n_tiles = p.gated ? (p.N / 2 + n_tile / 2 - 1) / (n_tile / 2) : (p.N + n_tile - 1) / n_tile;
-    int k_slab = (p.K + S - 1) / S;
-    k_slab = (k_slab + gran - 1) / gran * gran;
+    if (S > runs) S = runs;
     // the ring runs a few steps past the slab, and those offsets must stay below 2^31 as well
-    while (k_slab > gran && int64_t(k_slab + 4 * gran) * p.N * 2 >= (int64_t(1) << 31))
-        k_slab = (k_slab / 2 + gran - 1) / gran * gran;
-    if (int64_t(k_slab + 4 * gran) * p.N * 2 >= (int64_t(1) << 31)) { pl.why = "skinny variant needs N < 2^20"; return pl; }
-    S = (p.K + k_slab - 1) / k_slab;
+    const int64_t past = 2048;               // rows: more than PU + D / 2 + 1 runs of every wave
+    while ((int64_t(64) * ((runs + S - 1) / S) + past) * p.N * 2 >= (int64_t(1) << 31) && S < runs) ++S;
+    const int k_slab = 64 * ((runs + S - 1) / S);
+    if ((int64_t(k_slab) + past) * p.N * 2 >= (int64_t(1) << 31)) { pl.why = "skinny variant needs N < 2^20"; return pl; }
     pl.S = S;
     pl.k_slab = k_slab;
     if (int64_t(pl.n_tiles) * pl.RB > kMaxCounters) { pl.why = "too many column tiles"; return pl; }
@@ -378,9 +430,12 @@ static hipError_t skinny_go(const SkinnyArgs& a, bool fused, bool gated, const S
                                          (const void*)skinny_kernel<T, MB, true, true, MULTI>}, 144 * 1024);
     if (e != hipSuccess) return e;
     const int nt = 64 * skinny_waves(MB);
-    if (gated)      skinny_kernel<T, MB, true, true, MULTI><<<grid, nt, pl.lds, s>>>(a);
-    else if (fused) skinny_kernel<T, MB, true, false, MULTI><<<grid, nt, pl.lds, s>>>(a);
-    else            skinny_kernel<T, MB, false, false, MULTI><<<grid, nt, pl.lds, s>>>(a);
+    const SkinnyCold c{a.Y, a.eps, a.inv_K, a.H, a.G, a.ws_partial, a.ws_sumsq, a.counter, a.trace, a.trace_groups};
+#define RL_SKINNY_ARGS a.W, a.X, a.g, a.M, a.K, a.N, a.k_slab, a.S, a.n_tiles, a.n_tile, a.RB, c
+    if (gated)      skinny_kernel<T, MB, true, true, MULTI><<<grid, nt, pl.lds, s>>>(RL_SKINNY_ARGS);
+    else if (fused) skinny_kernel<T, MB, true, false, MULTI><<<grid, nt, pl.lds, s>>>(RL_SKINNY_ARGS);
+    else            skinny_kernel<T, MB, false, false, MULTI><<<grid, nt, pl.lds, s>>>(RL_SKINNY_ARGS);
+#undef RL_SKINNY_ARGS
     return hipGetLastError();
 }
 
