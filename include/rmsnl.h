@@ -90,6 +90,49 @@ rl_status rmsnorm_linear_noalloc(const void* X, const void* g, const void* W, fl
 size_t rl_noalloc_scratch_bytes(void);
 
 /*
+ * The fused block, and the gated block on top of it, with this call's own launch options and
+ * workspace instead of the process-wide settings (rl_set_variant, rl_set_tuning, rl_set_workspace):
+ * for callers with several streams, and for searches over launch shapes (the paper's search over grid
+ * dimensions, restricted to this kernel family).  opts == NULL means RL_AUTO with the library's workspace,
+ * i.e. exactly rmsnorm_linear / rmsnorm_gated_mlp.  Every field 0 means "automatic"; fields a variant
+ * does not have are ignored; a value the variant cannot honour gives RL_ERR_UNSUPPORTED.
+ *
+ *   struct_size    sizeof(rl_launch_opts), checked
+ *   variant        RL_AUTO or a forced variant (then no fallback, as with rl_set_variant)
+ *   columns        GEMV: columns of W per workgroup, 64, 128, 256 or 512; skinny: a multiple of 8 up to 128;
+ *                  fused tile kernel: 256 (256 x 256 tiles) or 512 (128 x 512 tiles)
+ *   slabs          K slabs: GEMV, skinny (1..16), and the product of the two-kernel tile form (1 = unsplit)
+ *   waves          fused tile kernel: waves per workgroup, 4 or 8
+ *   rem_slabs      two-kernel tile form: K slabs for the tiles left over after the last full round of 256
+ *   workspace      DEVICE buffer of workspace_bytes for this call alone (16-byte aligned, its first 256 KiB
+ *                  zero before the first call that uses it; the kernels leave them zero), or NULL for the
+ *                  library's own or the lent one.  Calls that run at the same time on different streams of one
+ *                  device must each bring their own.  Too small for the call: RL_ERR_WORKSPACE, except
+ *                  that RL_AUTO gives up the two-kernel tile form for the fused tile kernel.
+ *
+ * rmsnorm_gated_mlp_ex: interleaved != 0 reads W as rmsnorm_gated_mlp_interleaved does.
+ * rl_last_launch reports what the most recent successful call on this thread launched: variant, columns
+ * per workgroup (tile kernels: columns of a tile), K slabs (fused tile kernel: waves) and workgroups of its
+ * main kernel.
+ */
+typedef struct {
+    size_t struct_size;
+    rl_variant variant;
+    int columns;
+    int slabs;
+    int waves;
+    int rem_slabs;
+    void* workspace;
+    size_t workspace_bytes;
+} rl_launch_opts;
+rl_status rmsnorm_linear_ex(const void* X, const void* g, const void* W, float eps, void* Y,
+                            int64_t M, int64_t K, int64_t N, rl_dtype dt, const rl_launch_opts* opts, void* stream);
+rl_status rmsnorm_gated_mlp_ex(const void* X, const void* g, const void* W, float eps, void* Y,
+                               int64_t M, int64_t K, int64_t H, rl_dtype dt, int interleaved,
+                               const rl_launch_opts* opts, void* stream);
+rl_status rl_last_launch(rl_variant* variant, int* columns, int* slabs, int* workgroups);
+
+/*
  * Unfused pair, for A/B comparison with the fused call (the two-kernel baseline of
  * Fig. 2a: the normalised intermediate goes through device memory).
  *
@@ -279,6 +322,17 @@ rl_status rl_tile_order(int64_t M, int64_t N, int64_t position, int64_t* tile_ro
 rl_status rl_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
 rl_status rl_probe_read(const void* src, size_t bytes, void* sink, void* stream);
 rl_status rl_probe_mfma(void* sink, int iters, rl_dtype dt, void* stream);
+/*
+ * Streaming reads in the launch shapes of the small-M kernels, for a measured ceiling beside their
+ * figures.  rl_probe_read_strips: the DEVICE matrix src [rows][row_bytes] (row_bytes a multiple of 256,
+ * (rows + 256) * row_bytes < 2^31) is read as the GEMV and skinny kernels read W: one workgroup per
+ * 256-byte column strip and row part (`parts` of them, 1 <= parts <= rows), a wave-wide 16-byte load
+ * covering 4 rows of 256 bytes.  rl_probe_read_flat: `workgroups` workgroups read contiguous shares of
+ * `bytes` bytes, 1 KiB per wave-wide load.  Both read every byte once and write nothing
+ * (`sink`: 4 bytes of DEVICE memory that are practically never written).
+ */
+rl_status rl_probe_read_strips(const void* src, int64_t rows, int64_t row_bytes, int parts, void* sink, void* stream);
+rl_status rl_probe_read_flat(const void* src, size_t bytes, int workgroups, void* sink, void* stream);
 size_t rl_probe_mfma_sink_floats(void);
 double rl_probe_mfma_flops(int iters);
 

@@ -82,6 +82,28 @@ EXPORTS = {
 }
 
 
+class LaunchOpts(ctypes.Structure):
+    """rl_launch_opts of include/rmsnl.h."""
+    _fields_ = [("struct_size", ctypes.c_size_t), ("variant", ctypes.c_int), ("columns", ctypes.c_int),
+                ("slabs", ctypes.c_int), ("waves", ctypes.c_int), ("rem_slabs", ctypes.c_int),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+
+
+EXPORTS.update({
+    "rmsnorm_linear_ex": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
+                                         ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                         ctypes.c_int, ctypes.POINTER(LaunchOpts), ctypes.c_void_p]),
+    "rmsnorm_gated_mlp_ex": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
+                                            ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                            ctypes.c_int, ctypes.c_int, ctypes.POINTER(LaunchOpts), ctypes.c_void_p]),
+    "rl_last_launch": (ctypes.c_int, [ctypes.POINTER(ctypes.c_int)] * 4),
+    "rl_probe_read_strips": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+                                            ctypes.c_void_p, ctypes.c_void_p]),
+    "rl_probe_read_flat": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p,
+                                          ctypes.c_void_p]),
+})
+
+
 class RmsnlError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"rmsnl status {status}: {message}")
@@ -153,6 +175,66 @@ def rmsnorm_linear_noalloc(X: torch.Tensor, g: torch.Tensor, W: torch.Tensor, ep
     _check(lib().rmsnorm_linear_noalloc(_dev(X, "X"), _dev(g, "g"), _dev(W, "W"), float(eps), _dev(Y, "Y"),
                                         M, K, N, _DTYPES[X.dtype], _stream(stream)))
     return Y
+
+
+def _opts(variant="auto", columns=0, slabs=0, waves=0, rem_slabs=0, workspace: Optional[torch.Tensor] = None):
+    o = LaunchOpts()
+    o.struct_size = ctypes.sizeof(LaunchOpts)
+    o.variant = VARIANTS[variant] if isinstance(variant, str) else int(variant)
+    o.columns, o.slabs, o.waves, o.rem_slabs = int(columns), int(slabs), int(waves), int(rem_slabs)
+    if workspace is not None:
+        o.workspace = _dev(workspace, "workspace")
+        o.workspace_bytes = workspace.numel() * workspace.element_size()
+    return o
+
+
+def rmsnorm_linear_ex(X: torch.Tensor, g: torch.Tensor, W: torch.Tensor, eps: float, Y: Optional[torch.Tensor] = None,
+                      stream=None, **opts) -> torch.Tensor:
+    """rmsnorm_linear with this call's own launch options (variant, columns, slabs, waves, rem_slabs, workspace)."""
+    M, K = X.shape
+    K2, N = W.shape
+    if K2 != K or g.shape != (K,) or X.dtype != W.dtype or X.dtype != g.dtype:
+        raise ValueError("shape or dtype mismatch")
+    if Y is None:
+        Y = torch.empty((M, N), dtype=X.dtype, device=X.device)
+    elif Y.shape != (M, N) or Y.dtype != X.dtype:
+        raise ValueError("Y has the wrong shape or dtype")
+    o = _opts(**opts)
+    _check(lib().rmsnorm_linear_ex(_dev(X, "X"), _dev(g, "g"), _dev(W, "W"), float(eps), _dev(Y, "Y"),
+                                   M, K, N, _DTYPES[X.dtype], ctypes.byref(o), _stream(stream)))
+    return Y
+
+
+def rmsnorm_gated_mlp_ex(X: torch.Tensor, g: torch.Tensor, W: torch.Tensor, eps: float, Y: Optional[torch.Tensor] = None,
+                         interleaved: bool = False, stream=None, **opts) -> torch.Tensor:
+    M, K = X.shape
+    K2, N = W.shape
+    if K2 != K or N % 2 or g.shape != (K,) or X.dtype != W.dtype or X.dtype != g.dtype:
+        raise ValueError("shape or dtype mismatch")
+    H = N // 2
+    if Y is None:
+        Y = torch.empty((M, H), dtype=X.dtype, device=X.device)
+    elif Y.shape != (M, H) or Y.dtype != X.dtype:
+        raise ValueError("Y has the wrong shape or dtype")
+    o = _opts(**opts)
+    _check(lib().rmsnorm_gated_mlp_ex(_dev(X, "X"), _dev(g, "g"), _dev(W, "W"), float(eps), _dev(Y, "Y"),
+                                      M, K, H, _DTYPES[X.dtype], int(bool(interleaved)), ctypes.byref(o), _stream(stream)))
+    return Y
+
+
+def rl_last_launch():
+    """(variant name, columns, slabs, workgroups) of the most recent successful call on this thread."""
+    v, c, s, w = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().rl_last_launch(ctypes.byref(v), ctypes.byref(c), ctypes.byref(s), ctypes.byref(w)))
+    return VARIANT_NAMES[v.value], c.value, s.value, w.value
+
+
+def rl_probe_read_strips(src: torch.Tensor, rows: int, row_bytes: int, parts: int, sink: torch.Tensor, stream=None) -> None:
+    _check(lib().rl_probe_read_strips(_dev(src, "src"), rows, row_bytes, parts, _dev(sink, "sink"), _stream(stream)))
+
+
+def rl_probe_read_flat(src: torch.Tensor, nbytes: int, workgroups: int, sink: torch.Tensor, stream=None) -> None:
+    _check(lib().rl_probe_read_flat(_dev(src, "src"), nbytes, workgroups, _dev(sink, "sink"), _stream(stream)))
 
 
 def rl_noalloc_scratch_bytes() -> int:

@@ -21,6 +21,7 @@ constexpr int kMaxDevices = 16;
 
 thread_local char tl_error[512] = "";
 thread_local rl_variant tl_last_variant = RL_AUTO;
+thread_local int tl_last_plan[3] = {0, 0, 0};
 
 std::mutex g_mu;
 bool g_env_read = false;
@@ -205,7 +206,7 @@ hipError_t launch_variant(rl_variant v, Problem& p, hipStream_t s, const char** 
         if (fixed) {
             ws = *fixed;
             *ws_status = ws.bytes >= need + kHeadBytes ? RL_OK
-                : fail(RL_ERR_WORKSPACE, "the shape needs more than the fixed scratch buffer holds (8 MiB in all)");
+                : fail(RL_ERR_WORKSPACE, "the shape needs more workspace than this call's buffer holds (the scratch array of rmsnorm_linear_noalloc: 8 MiB in all)");
         } else {
             *ws_status = get_workspace(need, s, &ws);
         }
@@ -222,16 +223,19 @@ hipError_t launch_variant(rl_variant v, Problem& p, hipStream_t s, const char** 
     }
 }
 
-rl_status run(Problem& p, void* stream, const Workspace* fixed = nullptr)
+// opts: this call's variant and launch shape instead of the process-wide settings (or null)
+struct CallOpts { rl_variant variant; int n_tile, k_split; };
+
+rl_status run(Problem& p, void* stream, const Workspace* fixed = nullptr, const CallOpts* opts = nullptr)
 {
     rl_variant forced;
     Tuned tuned{RL_AUTO, 0, 0};
     {
         std::lock_guard<std::mutex> lk(g_mu);
         read_env_locked();
-        forced = g_variant;
-        p.n_tile = g_n_tile;
-        p.k_split = g_k_split;
+        forced = opts ? opts->variant : g_variant;
+        p.n_tile = opts ? opts->n_tile : g_n_tile;
+        p.k_split = opts ? opts->k_split : g_k_split;
         p.trace = g_trace;
         p.trace_groups = g_trace_groups;
         if (forced == RL_AUTO) {
@@ -240,6 +244,8 @@ rl_status run(Problem& p, void* stream, const Workspace* fixed = nullptr)
         }
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
+    tl_last_plan[0] = tl_last_plan[1] = tl_last_plan[2] = 0;
+    p.plan = tl_last_plan;
     rl_variant order[6];
     int n_order = 0;
     if (forced != RL_AUTO) {
@@ -314,6 +320,79 @@ rl_status rmsnorm_linear_noalloc(const void* X, const void* g, const void* W, fl
 }
 
 size_t rl_noalloc_scratch_bytes(void) { return kScratchBytes; }
+
+// the options of an _ex call as the launchers' (n_tile, k_split) pair, which means something else per variant
+static rl_status translate_opts(const rl_launch_opts* o, CallOpts* c, Workspace* ws, bool* has_ws)
+{
+    *has_ws = false;
+    c->variant = RL_AUTO; c->n_tile = 0; c->k_split = 0;
+    if (!o) return RL_OK;
+    if (o->struct_size != sizeof(rl_launch_opts)) return fail(RL_ERR_INVALID_ARG, "rl_launch_opts.struct_size must be sizeof(rl_launch_opts)");
+    if (o->variant < RL_AUTO || o->variant > RL_MFMA_TILE_PRE) return fail(RL_ERR_INVALID_ARG, "unknown variant");
+    if (o->columns < 0 || o->slabs < 0 || o->waves < 0 || o->rem_slabs < 0)
+        return fail(RL_ERR_INVALID_ARG, "launch options must be >= 0");
+    c->variant = o->variant;
+    switch (o->variant) {
+    case RL_GEMV_SPLITK: case RL_MFMA_SKINNY: c->n_tile = o->columns; c->k_split = o->slabs; break;
+    case RL_MFMA_TILE: c->n_tile = o->columns; c->k_split = o->waves; break;
+    case RL_MFMA_TILE_PRE:
+        if (o->slabs) { c->n_tile = 1; c->k_split = o->slabs; }
+        else if (o->rem_slabs) { c->n_tile = 2; c->k_split = o->rem_slabs; }
+        break;
+    default: break;
+    }
+    if (o->workspace) {
+        if (!aligned16(o->workspace) || o->workspace_bytes <= kHeadBytes)
+            return fail(RL_ERR_INVALID_ARG, "workspace must be 16-byte aligned and larger than 1280 KiB");
+        *ws = Workspace{o->workspace, o->workspace_bytes, false};
+        *has_ws = true;
+    }
+    return RL_OK;
+}
+
+rl_status rmsnorm_linear_ex(const void* X, const void* g, const void* W, float eps, void* Y,
+                            int64_t M, int64_t K, int64_t N, rl_dtype dt, const rl_launch_opts* opts, void* stream)
+{
+    if (!X || !g || !W || !Y) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (rl_status st = check_dims(M, K, N, dt)) return st;
+    if (!std::isfinite(eps) || eps < 0.f) return fail(RL_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    if (!aligned16(X) || !aligned16(g) || !aligned16(W) || !aligned16(Y))
+        return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    CallOpts c; Workspace ws; bool has_ws;
+    if (rl_status st = translate_opts(opts, &c, &ws, &has_ws)) return st;
+    Problem p{};
+    p.X = X; p.g = g; p.W = W; p.Y = Y;
+    p.M = int(M); p.K = int(K); p.N = int(N);
+    p.eps = eps; p.fused = 1; p.dt = DType(dt);
+    return run(p, stream, has_ws ? &ws : nullptr, opts ? &c : nullptr);
+}
+
+rl_status rmsnorm_gated_mlp_ex(const void* X, const void* g, const void* W, float eps, void* Y,
+                               int64_t M, int64_t K, int64_t H, rl_dtype dt, int interleaved,
+                               const rl_launch_opts* opts, void* stream)
+{
+    if (!X || !g || !W || !Y) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (H < 1 || H >= (int64_t(1) << 30)) return fail(RL_ERR_INVALID_ARG, "H must be in [1, 2^30)");
+    if (interleaved && H % 64 != 0) return fail(RL_ERR_INVALID_ARG, "the interleaved layout needs H % 64 == 0");
+    if (rl_status st = check_dims(M, K, 2 * H, dt)) return st;
+    if (!std::isfinite(eps) || eps < 0.f) return fail(RL_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    if (!aligned16(X) || !aligned16(g) || !aligned16(W) || !aligned16(Y))
+        return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    CallOpts c; Workspace ws; bool has_ws;
+    if (rl_status st = translate_opts(opts, &c, &ws, &has_ws)) return st;
+    Problem p{};
+    p.X = X; p.g = g; p.W = W; p.Y = Y;
+    p.M = int(M); p.K = int(K); p.N = int(2 * H);
+    p.eps = eps; p.fused = 1; p.gated = 1; p.gate_group = interleaved ? 64 : 0; p.dt = DType(dt);
+    return run(p, stream, has_ws ? &ws : nullptr, opts ? &c : nullptr);
+}
+
+rl_status rl_last_launch(rl_variant* variant, int* columns, int* slabs, int* workgroups)
+{
+    if (!variant || !columns || !slabs || !workgroups) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    *variant = tl_last_variant; *columns = tl_last_plan[0]; *slabs = tl_last_plan[1]; *workgroups = tl_last_plan[2];
+    return RL_OK;
+}
 
 rl_status rmsnorm_gated_mlp(const void* X, const void* g, const void* W, float eps, void* Y,
                             int64_t M, int64_t K, int64_t H, rl_dtype dt, void* stream)
@@ -660,6 +739,24 @@ rl_status rl_probe_read(const void* src, size_t bytes, void* sink, void* stream)
     if (!sink || !src || bytes == 0 || bytes % 16 || !aligned16(src))
         return fail(RL_ERR_INVALID_ARG, "probe read needs 16-byte aligned pointer and size");
     hipError_t e = launch_probe_read(src, bytes, sink, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RL_OK : fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+}
+
+rl_status rl_probe_read_strips(const void* src, int64_t rows, int64_t row_bytes, int parts, void* sink, void* stream)
+{
+    if (!sink || !src || !aligned16(src)) return fail(RL_ERR_INVALID_ARG, "probe needs a sink and a 16-byte aligned source");
+    if (rows < 1 || row_bytes < 256 || row_bytes % 256 || parts < 1 || parts > rows ||
+        (rows + 256) * row_bytes >= (int64_t(1) << 31) || (row_bytes / 256) * int64_t(parts) > (int64_t(1) << 20))
+        return fail(RL_ERR_INVALID_ARG, "strips probe: row_bytes a multiple of 256, 1 <= parts <= rows, (rows + 256) * row_bytes < 2^31");
+    hipError_t e = launch_probe_strips(src, int(rows), int(row_bytes), parts, sink, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RL_OK : fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+}
+
+rl_status rl_probe_read_flat(const void* src, size_t bytes, int workgroups, void* sink, void* stream)
+{
+    if (!sink || !src || bytes == 0 || bytes % 16 || !aligned16(src) || workgroups < 1 || workgroups > (1 << 20))
+        return fail(RL_ERR_INVALID_ARG, "flat probe needs a sink, a 16-byte aligned source and size, 1 <= workgroups <= 2^20");
+    hipError_t e = launch_probe_flat(src, bytes, workgroups, sink, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? RL_OK : fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
 }
 

@@ -352,6 +352,98 @@ hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStrea
     return hipGetLastError();
 }
 
+// Streaming-read probes with the launch shapes of the small-M kernels, for a measured ceiling beside
+// their figures.  Strips: the matrix [rows][row_bytes] is cut into strips of 256 bytes (128 16-bit
+// columns, what a workgroup of the GEMV and skinny kernels owns) and `parts` row ranges; workgroup
+// (strip, part) reads its rows with the kernels' own access shape (a wave-wide 16-byte load covers
+// 4 rows of 256 bytes), two batches of 8 loads per wave in flight, streaming cache policy, through a
+// range-checked buffer resource.  Flat: workgroup b of G reads the b-th contiguous share of the
+// buffer, 1 KiB per wave-wide load.
+__global__ __launch_bounds__(256) void probe_strips_kernel(const char* __restrict__ src, int rows, int row_bytes,
+                                                           int strips, int parts, uint32_t* __restrict__ sink)
+{
+    int b = blockIdx.x;
+    const int total = strips * parts;
+    if ((total & 7) == 0) b = (b & 7) * (total >> 3) + (b >> 3);       // the parts of a strip share an XCD
+    const int strip = b / parts, part = b % parts;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int prow = (rows + parts - 1) / parts;                        // rows per part
+    const int r0 = part * prow;
+    const int here = min(prow, rows - r0);
+    if (here <= 0) return;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(src) + size_t(r0) * row_bytes, 0, here * row_bytes, 0x00020000);
+    const int voff = strip * 256 + (lane & 15) * 16 + (lane >> 4) * row_bytes;
+    const int nchunks = (here + 127) / 128;                             // chunks of 32 rows per wave; rows past `here` read zero
+    uint4_t r[2][8];
+    uint4_t acc = {0, 0, 0, 0};
+    auto issue = [&](int c, int d) {
+        const int base = voff + ((c * 4 + wave) * 32) * row_bytes;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r[d][j] = __builtin_amdgcn_raw_buffer_load_b128(rs, base + j * 4 * row_bytes, 0, 2);
+    };
+    issue(0, 0);
+    if (nchunks > 1) issue(1, 1);
+    for (int c0 = 0; c0 < nchunks; c0 += 2) {
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            if (c0 + d < nchunks) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc ^= r[d][j];
+                if (c0 + d + 2 < nchunks) issue(c0 + d + 2, d);
+            }
+        }
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = acc.x;   // practically never taken; keeps the loads alive
+}
+
+__global__ __launch_bounds__(256) void probe_flat_kernel(const uint4_t* __restrict__ src, size_t n16, size_t share16,
+                                                         uint32_t* __restrict__ sink)
+{
+    const size_t lo = size_t(blockIdx.x) * share16;
+    const size_t hi = min(n16, lo + share16);
+    uint4_t acc = {0, 0, 0, 0};
+    // a wave takes alternate runs of 8 KiB (8 loads of 1 KiB), two runs in flight
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint4_t r[2][8];
+    auto issue = [&](size_t run, int d) {
+        const size_t base = lo + (run * 4 + wave) * 512 + lane;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            r[d][j] = base + j * 64 < hi ? __builtin_nontemporal_load(src + base + j * 64) : uint4_t{0, 0, 0, 0};
+    };
+    const size_t nruns = (hi > lo ? hi - lo + 2047 : 0) / 2048;
+    if (nruns == 0) return;
+    issue(0, 0);
+    if (nruns > 1) issue(1, 1);
+    for (size_t c0 = 0; c0 < nruns; c0 += 2) {
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            if (c0 + d < nruns) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc ^= r[d][j];
+                if (c0 + d + 2 < nruns) issue(c0 + d + 2, d);
+            }
+        }
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = acc.x;
+}
+
+hipError_t launch_probe_strips(const void* src, int rows, int row_bytes, int parts, void* sink, hipStream_t s)
+{
+    probe_strips_kernel<<<(row_bytes / 256) * parts, 256, 0, s>>>((const char*)src, rows, row_bytes, row_bytes / 256, parts,
+                                                                  (uint32_t*)sink);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_flat(const void* src, size_t bytes, int workgroups, void* sink, hipStream_t s)
+{
+    const size_t n16 = bytes / 16;
+    const size_t share16 = ((n16 + workgroups - 1) / workgroups + 2047) / 2048 * 2048;   // whole 32 KiB rounds per workgroup
+    probe_flat_kernel<<<workgroups, 256, 0, s>>>((const uint4_t*)src, n16, share16, (uint32_t*)sink);
+    return hipGetLastError();
+}
+
 // register-only MFMA loop: 4 independent 32x32x16 accumulators per wave, 4 waves per workgroup,
 // 4 workgroups per CU's worth of grid; flops = grid * 4 waves * iters * 4 * 32*32*16*2
 constexpr int kProbeBlocks = 1024;

@@ -461,6 +461,7 @@ hipError_t launch_skinny(const Problem& p, hipStream_t s, const char** why)
         if (why) *why = "split-K needs the workspace";
         return hipErrorInvalidValue;
     }
+    if (p.plan) { p.plan[0] = pl.n_tile; p.plan[1] = pl.S; p.plan[2] = pl.n_tiles * pl.S * pl.RB; }
     SkinnyArgs a;
     a.X = (const u16*)p.X; a.g = (const u16*)p.g; a.W = (const uint4_t*)p.W; a.Y = (u16*)p.Y;
     a.M = p.M; a.K = p.K; a.N = p.N; a.eps = p.eps; a.inv_K = 1.0f / float(p.K);

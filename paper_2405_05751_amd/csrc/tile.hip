@@ -528,6 +528,7 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
     if (p.tile_limit < 0 || p.tile_limit > a.tiles_m * a.tiles_n) { if (why) *why = "bad tile range"; return hipErrorInvalidValue; }
     a.tiles_here = p.tile_limit;
     dim3 grid(p.tile_limit ? p.tile_limit : a.tiles_m * a.tiles_n);
+    if (p.plan) { p.plan[0] = BN; p.plan[1] = nw; p.plan[2] = int(grid.x); }
     const bool fused = p.fused != 0;
     if (p.gated && !fused)                  // gate over a product of a materialised X-hat, scaled per row
         return p.dt == F16 ? tile_nw<Fp16, false, true>(a, grid, nw, shape, s) : tile_nw<Bf16, false, true>(a, grid, nw, shape, s);
@@ -813,7 +814,11 @@ hipError_t launch_tile_pre(const Problem& p, hipStream_t s, const char** why)
     } else {
         q.rscale = nullptr;                  // the plain product (matmul): no first kernel, only the split
     }
-    if (S > 1) return launch_tile_split(q, S, k_slab, part, s);
+    if (S > 1) {
+        if (p.plan) { p.plan[0] = 256; p.plan[1] = S; p.plan[2] = ((p.M + 255) / 256) * ((p.N + 255) / 256) * S; }
+        q.plan = nullptr;
+        return launch_tile_split(q, S, k_slab, part, s);
+    }
     int full, rem, RS, rks;
     tile_rem_plan(p, &full, &rem, &RS, &rks);
     if (rem) return launch_tile_rem(q, full, rem, RS, rks, part, s, why);
