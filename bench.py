@@ -31,23 +31,41 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0        # MI355X dense bf16/fp16 matrix, published (2.5 PFLOP/s)
 ROTATE_BYTES = 512 << 20
-# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same counters
-# read for the plain copy kernel (x2.0 and x1.0): profiles/hbm_traffic_pmc.md.  Counters cannot be read from
-# inside this process, so the table is refreshed by hand when a kernel's launch shape changes.
-MEASURED_TRAFFIC_BYTES = {"decode": 34.46e6, "qkv": 55.01e6, "gateup": 243.11e6, "prefill": 2014.1e6}
+MIN_REGION_MS = 50.0             # a timed region is the K-step graph replayed until it lasts at least this long
+# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), scaled by what the same
+# counters read for the plain copy kernel: profiles/hbm_traffic_pmc.md, which gives the commands.  Counters
+# cannot be read from inside this process, so every figure is stored with the launch it was measured on
+# (variant, columns per workgroup, K slabs, workgroups; rl_last_launch) and is reported only while the
+# library still launches that shape; otherwise `traffic` is null.
+MEASURED_TRAFFIC = {
+    # workload: (bytes per launch = 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE in KiB x 1024, launch the counters were read on)
+    "decode": (34.45e6, ("gemv", 128, 16, 512)),
+    "qkv": (55.05e6, ("skinny", 128, 4, 192)),
+    "gateup": (243.15e6, ("skinny", 128, 1, 224)),
+    "prefill": (2035.9e6, ("tile_pre", 256, 8, 1024)),      # both kernels: 268.9 MB + 1767.0 MB
+}
+TRAFFIC_SOURCE = "profiles/hbm_traffic_pmc.md"
 
 
-def _time_region(fn_enqueue, torch):
-    """Events on the current stream around fn_enqueue(); returns (event ms, wall ms)."""
+def _time_region(fn_enqueue, torch, min_ms=MIN_REGION_MS):
+    """Events on the current stream around enough calls of fn_enqueue() (one call = one replay of the
+    K-step graph) to last min_ms; returns (event ms per call, wall ms per call, calls)."""
     start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
     start.record()
     fn_enqueue()
     end.record()
     torch.cuda.synchronize()
+    once = max(start.elapsed_time(end), 1e-3)
+    calls = max(1, min(2000, int(np.ceil(min_ms / once))))
+    t0 = time.perf_counter()
+    start.record()
+    for _ in range(calls):
+        fn_enqueue()
+    end.record()
+    torch.cuda.synchronize()
     wall = (time.perf_counter() - t0) * 1e3
-    return start.elapsed_time(end), wall
+    return start.elapsed_time(end) / calls, wall / calls, calls
 
 
 def _workload(name):
@@ -61,7 +79,7 @@ def _workload(name):
 
 
 def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=True, gated=False, autotune=False,
-                 interleaved=False):
+                 interleaved=False, only_cold=False, ceilings=True):
     import workloads
     from tests.util import compare, compare_gated, to_device, to_host_f64
 
@@ -112,9 +130,14 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
         return lambda: [step_fn(i) for i in range(steps)]
 
     cold = make_runner(step)
-    ev_ms, wall_ms = min((_time_region(cold, torch) for _ in range(3)), key=lambda t: t[0])
+    ev_ms, wall_ms, replays = min((_time_region(cold, torch) for _ in range(3)), key=lambda t: t[0])
+    launch = rl.rl_last_launch()                 # (variant, columns, slabs, workgroups) of the timed call
+    if only_cold:
+        per = ev_ms / steps
+        return {"workload": name, "variant": used, "launch": launch, "us_per_step": per * 1e3, "replays": replays,
+                "copies_rotated": copies, "algorithmic_bytes": abytes, "flops": w.flops}, w
     warm = make_runner(lambda i: fused_call(Xs[0], gs[0], Wf[0], w.eps, Ys[0]))
-    warm_ms, _ = min((_time_region(warm, torch) for _ in range(3)), key=lambda t: t[0])
+    warm_ms, _, _ = min((_time_region(warm, torch) for _ in range(3)), key=lambda t: t[0])
 
     # the unfused pair from the same library, same rotation, for the fusion gain on this hardware
     # (gated block: the fused norm + products followed by the separate activation kernel)
@@ -132,7 +155,7 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
 
     pair(0)
     torch.cuda.synchronize()
-    pair_ms, _ = min((_time_region(make_runner(pair), torch) for _ in range(3)), key=lambda t: t[0])
+    pair_ms, _, _ = min((_time_region(make_runner(pair), torch) for _ in range(3)), key=lambda t: t[0])
 
     # where the automatic choice is the two-kernel tile form, the one fused kernel is timed beside it
     one_kernel_ms = None
@@ -140,7 +163,7 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
         rl.rl_set_variant("tile")
         step(0)
         torch.cuda.synchronize()
-        one_kernel_ms, _ = min((_time_region(make_runner(step), torch) for _ in range(3)), key=lambda t: t[0])
+        one_kernel_ms, _, _ = min((_time_region(make_runner(step), torch) for _ in range(3)), key=lambda t: t[0])
         rl.rl_set_variant("auto")
 
     parity = None
@@ -159,16 +182,39 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
 
     per_step_ms = ev_ms / steps
     mem_bound = w.M <= 64
+    # what a bare read of the same W, launched and timed the same way, takes: the workgroups' own access shape
+    # (256-byte strips, as many row parts as the launch has slabs) and one contiguous share per workgroup
+    ceiling = None
+    if ceilings and mem_bound and w.dtype != "f32" and (w.N * 2) % 256 == 0:
+        sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+        parts = max(1, launch[2]) if launch[0] in ("gemv", "skinny") else 1
+        wbytes = w.K * w.N * 2
+        strips = make_runner(lambda i: rl.rl_probe_read_strips(Ws[i % copies], w.K, w.N * 2, parts, sink))
+        t_strips, _, _ = min((_time_region(strips, torch) for _ in range(3)), key=lambda t: t[0])
+        flat = make_runner(lambda i: rl.rl_probe_read_flat(Ws[i % copies], wbytes, 512, sink))
+        t_flat, _, _ = min((_time_region(flat, torch) for _ in range(3)), key=lambda t: t[0])
+        ceiling = {"what": "a bare read of W alone (no X, no product, no exchange between workgroups), same graph, rotation and events",
+                   "strips_256B_us": t_strips / steps * 1e3, "strips_256B_GBps": wbytes / (t_strips / steps * 1e-3) / 1e9,
+                   "strips_row_parts": parts,
+                   "contiguous_us": t_flat / steps * 1e3, "contiguous_GBps": wbytes / (t_flat / steps * 1e-3) / 1e9}
+    elif ceilings and not mem_bound:
+        sink = torch.zeros(rl.lib().rl_probe_mfma_sink_floats(), dtype=torch.float32, device="cuda")
+        fl = rl.rl_probe_mfma(sink, 2000, tdt)
+        torch.cuda.synchronize()
+        t_m, _, _ = min((_time_region(lambda: rl.rl_probe_mfma(sink, 2000, tdt), torch) for _ in range(3)), key=lambda t: t[0])
+        ceiling = {"what": "register-only 32x32x16 matrix-core loop on pseudo-random operands, nothing else",
+                   "mfma_loop_TFLOPs": fl / (t_m * 1e-3) / 1e12}
     res = {
         "workload": name + ("+gate" if gated else "") + ("(interleaved W)" if gated and interleaved else ""), "M": w.M, "K": w.K, "N": w.N, "dtype": w.dtype, "variant": used,
-        "copies_rotated": copies, "us_per_step": per_step_ms * 1e3,
+        "launch": {"variant": launch[0], "columns": launch[1], "slabs": launch[2], "workgroups": launch[3]},
+        "copies_rotated": copies, "timed_replays_of_the_graph": replays, "us_per_step": per_step_ms * 1e3,
         "us_per_step_warm": warm_ms / steps * 1e3, "us_per_step_unfused_pair": pair_ms / steps * 1e3,
         "wall_us_per_step": wall_ms / steps * 1e3,
         "us_per_step_one_fused_kernel": None if one_kernel_ms is None else one_kernel_ms / steps * 1e3,
         "TBps": abytes / (per_step_ms * 1e-3) / 1e12, "TBps_warm": abytes / (warm_ms / steps * 1e-3) / 1e12,
         "TFLOPs": w.flops / (per_step_ms * 1e-3) / 1e12,
         "algorithmic_bytes": abytes, "flops": w.flops,
-        "max_err_over_rmsY": parity, "autotuned": tuned,
+        "max_err_over_rmsY": parity, "autotuned": tuned, "measured_ceiling": ceiling,
     }
     rl.rl_autotune_clear()
     if mem_bound:
@@ -203,7 +249,7 @@ def run_ntrans(rl, torch, steps, warmup, M=16384, D=2048, dtype="bf16", with_cpu
         for i in range(steps):
             step(i)
     graph.replay(); torch.cuda.synchronize()
-    ev_ms, _ = min((_time_region(graph.replay, torch) for _ in range(3)), key=lambda t: t[0])
+    ev_ms, _, _ = min((_time_region(graph.replay, torch) for _ in range(3)), key=lambda t: t[0])
     rows = np.arange(0, M, max(1, M // 64))
     Z = oracle.ntrans(x[rows], h[rows], a, dtype, eps)
     parity, _ = compare(to_host_f64(ys[0][torch.from_numpy(rows).cuda()], dtype), Z, dtype, "ntrans")
@@ -250,7 +296,7 @@ def run_qknorm(rl, torch, steps, warmup, B=8, H=32, S=4096, D=128, dtype="bf16",
         for i in range(steps):
             step(i)
     graph.replay(); torch.cuda.synchronize()
-    ev_ms, _ = min((_time_region(graph.replay, torch) for _ in range(3)), key=lambda t: t[0])
+    ev_ms, _, _ = min((_time_region(graph.replay, torch) for _ in range(3)), key=lambda t: t[0])
     us = ev_ms / steps * 1e3
     nb = min(B, 2)                                   # parity on the first samples
     want = oracle.qknorm_attention(c["Q"][:nb], c["K"][:nb], c["V"][:nb], c["gq"], c["bq"], c["gk"], c["bk"], dtype, eps)
@@ -267,13 +313,13 @@ def run_qknorm(rl, torch, steps, warmup, B=8, H=32, S=4096, D=128, dtype="bf16",
     for _ in range(3):
         unfused()
     torch.cuda.synchronize()
-    t_ms, _ = min((_time_region(lambda: [unfused() for _ in range(10)], torch) for _ in range(3)), key=lambda t: t[0])
+    t_ms, _, _ = min((_time_region(lambda: [unfused() for _ in range(10)], torch, min_ms=0.0) for _ in range(3)), key=lambda t: t[0])
     out = {"metric": "QKNorm + attention TB/s", "value": abytes / us / 1e6, "unit": "TB/s", "n_gpus": 1, "steps": steps,
            "warmup": warmup, "ms_per_step": us / 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": dtype, "data": "synthetic",
            "config": {"workload": f"qknorm: Q {B}x{H}x{D}, K and V {B}x{H}x{S}x{D}, {dtype}", "copies_rotated": copies},
            "roofline": {"bound": "hbm", "achieved": abytes / us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": abytes / us / 1e3 / HBM_PEAK_GBS, "traffic": 537.1e6 if (B, H, S, D) == (8, 32, 4096, 128) else None,
+                        "frac": abytes / us / 1e3 / HBM_PEAK_GBS, "traffic": None,
                         "kernel": "qkattn_kernel",
                         "us_per_launch": us},
            "detail": {"us_per_step": us, "algorithmic_bytes": abytes, "max_err_over_rms": parity,
@@ -287,6 +333,46 @@ def run_qknorm(rl, torch, steps, warmup, B=8, H=32, S=4096, D=128, dtype="bf16",
         out["cpu_baseline"] = {"value": abytes / B / sec / 1e12, "unit": "TB/s", "cores": oracle.num_threads(),
                                "kind": "oracle", "sample": f"{reps} run(s) of the fp64 oracle on 1 of {B} samples, {sec:.4f} s each"}
     return out
+
+
+def probe_strips(rl, torch, spec):
+    """Finish times of the workgroups of rl_probe_read_strips (one per 256-byte strip), by address class."""
+    shape, _, shift = spec.partition("+")
+    rows, row_bytes = (int(v) for v in shape.lower().split("x"))
+    shift = int(shift or 0)
+    strips = row_bytes // 256
+    nbytes = rows * row_bytes
+    copies = max(2, -(-ROTATE_BYTES // nbytes))
+    pool = torch.randint(0, 1 << 30, ((copies * nbytes + shift) // 4 + 64,), dtype=torch.int32, device="cuda")
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    slots = rl.rl_trace_slots()
+    buf = torch.zeros(strips * slots, dtype=torch.int64, device="cuda")
+    src = lambda i: pool.view(torch.uint8)[shift + (i % copies) * nbytes:][:nbytes]
+    for i in range(4):
+        rl.rl_probe_read_strips(src(i), rows, row_bytes, 1, sink)
+    torch.cuda.synchronize()
+    rl.rl_set_trace(buf)
+    sums, count = np.zeros(4), np.zeros(4)
+    last = 0.0
+    try:
+        for i in range(8):
+            buf.zero_()
+            s = src(i)
+            rl.rl_probe_read_strips(s, rows, row_bytes, 1, sink)
+            torch.cuda.synchronize()
+            t = buf.cpu().numpy().reshape(-1, slots).astype(np.float64)
+            fin = (t[:, 2] - t[:, 0].min()) * 10.0                      # ns after the first workgroup started
+            b = np.arange(strips)
+            strip = (b % 8) * (strips // 8) + b // 8 if strips % 8 == 0 else b
+            cls = ((s.data_ptr() + strip * 256) >> 8) & 3
+            for c in range(4):
+                sums[c] += fin[cls == c].sum(); count[c] += (cls == c).sum()
+            last += fin.max() / 8
+    finally:
+        rl.rl_set_trace(None)
+    return {"probe": "rl_probe_read_strips, one workgroup per 256-byte strip", "rows": rows, "row_bytes": row_bytes,
+            "base_shift": shift, "workgroups": strips, "last_finish_ns": last,
+            "mean_finish_ns_by_address_bits_9_8": {f"{c:02b}": (sums[c] / count[c] if count[c] else None) for c in range(4)}}
 
 
 def cpu_baseline(w, mem_bound, budget_s=12.0):
@@ -333,6 +419,11 @@ def main():
                     help="with --gated: W's gate and up columns interleaved in groups of 64 (rmsnorm_gated_mlp_interleaved)")
     ap.add_argument("--gated", action="store_true",
                     help="time the gated block (SiLU(gate) * up epilogue, W read as [gate | up]) on the workload")
+    ap.add_argument("--only-cold", action="store_true",
+                    help="time the rotating-buffer graph of the named workload only (for a kernel trace of one phase)")
+    ap.add_argument("--probe-strips", default="", metavar="ROWSxROW_BYTES[+SHIFT]",
+                    help="only read a matrix of that shape as 256-byte column strips, one workgroup each, and report "
+                         "when the strips finish, by bits [9:8] of their first byte's address (SHIFT bytes added to the base)")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="MiB",
                     help="only run the plain copy kernel on MiB of data ten times (memory-counter calibration)")
     args = ap.parse_args()
@@ -358,6 +449,10 @@ def main():
         print(json.dumps({"probe_copy_bytes_read": n, "probe_copy_bytes_written": n, "launches": 10}))
         return
 
+    if args.probe_strips:
+        print(json.dumps(probe_strips(rl, torch, args.probe_strips)))
+        return
+
     name = args.workload
     if name == "ntrans":
         print(json.dumps(run_ntrans(rl, torch, args.steps if args.steps is not None else 100, args.warmup,
@@ -373,42 +468,84 @@ def main():
         M, K, N = (int(v) for v in name.lower().split("x"))
         steps = 20 if 2.0 * M * K * N > 2e11 else 100
     res, w = run_workload(rl, torch, name, steps, args.warmup, args.variant, use_graph=not args.no_graph,
-                          gated=args.gated, autotune=args.autotune, interleaved=args.interleaved)
-    mem_bound = w.M <= 64
-    if mem_bound:
-        metric, unit, value = "fused RMSNorm+MatMul TB/s", "TB/s", res["TBps"]
-        roof = {"bound": "hbm", "achieved": res["TBps"] * 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
-    else:
-        metric, unit, value = "fused RMSNorm+MatMul TFLOP/s", "TFLOP/s", res["TFLOPs"]
-        roof = {"bound": "mfma", "achieved": res["TFLOPs"], "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s"}
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(name) if args.variant == "auto" and not args.gated else None
-    roof["kernel"] = res["variant"]
-    roof["us_per_launch"] = res["us_per_step"]
-
-    out = {
-        "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": steps, "warmup": args.warmup,
-        "ms_per_step": res["us_per_step"] / 1e3, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": f"{name}{' + gate' if args.gated else ''}: X {w.M}x{w.K}, W {w.K}x{w.N}, {w.dtype}",
-                   "variant": res["variant"],
-                   "copies_rotated": res["copies_rotated"], "graph": not args.no_graph},
-        "roofline": roof,
-        "detail": res,
-    }
+                          gated=args.gated, autotune=args.autotune, interleaved=args.interleaved,
+                          only_cold=args.only_cold)
+    if args.only_cold:
+        print(json.dumps(res))
+        return
+    out = headline(name, res, w, steps, args)
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(w, mem_bound)
+        out["cpu_baseline"] = cpu_baseline(w, w.M <= 64)
     if (args.others or name == "decode") and not args.no_others:
         import workloads
         others = []
         for other in workloads.CONFIG_NAMES:
             if other == name:
                 continue
-            r, _ = run_workload(rl, torch, other, 20 if other == "prefill" else 200, args.warmup, args.variant,
-                                use_graph=not args.no_graph)
+            r, wo = run_workload(rl, torch, other, 20 if other == "prefill" else 200, args.warmup, args.variant,
+                                 use_graph=not args.no_graph)
+            r["roofline"] = roofline_of(other, r, wo, args.variant == "auto")
             others.append(r)
+        # the widened rows of the path, each with its own roofline (no CPU leg: the headline carries one)
+        r, wo = run_workload(rl, torch, "gateup", 200, args.warmup, args.variant, use_graph=not args.no_graph,
+                             gated=True, interleaved=True, ceilings=False)
+        r["roofline"] = roofline_of("gateup+gate", r, wo, False)
+        others.append(r)
+        others.append(run_ntrans(rl, torch, 100, args.warmup, with_cpu=False))
+        others.append(run_qknorm(rl, torch, 100, args.warmup, B=8, with_cpu=False))
+        others.append(run_qknorm(rl, torch, 100, args.warmup, B=1, with_cpu=False))
         out["other_workloads"] = others
     print(json.dumps(out))
+
+
+def roofline_of(name, res, w, auto):
+    """The roofline object of one workload's dominant kernel."""
+    if w.M <= 64:
+        roof = {"bound": "hbm", "achieved": res["TBps"] * 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": res["TFLOPs"], "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    launch = [res["launch"][k] for k in ("variant", "columns", "slabs", "workgroups")]
+    rec = MEASURED_TRAFFIC.get(name)
+    if auto and rec is not None and list(rec[1]) == launch:
+        roof["traffic"] = rec[0]
+        roof["traffic_source"] = f"{TRAFFIC_SOURCE}: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE on this launch shape {launch}"
+    else:
+        roof["traffic"] = None
+        roof["traffic_source"] = ("not measured for the launch shape of this run " + str(launch) if rec is not None
+                                  else "not measured for this workload")
+    roof["kernel"] = res["variant"]
+    roof["us_per_launch"] = res["us_per_step"]
+    if res.get("measured_ceiling"):
+        roof["measured_ceiling"] = res["measured_ceiling"]
+    if res.get("us_per_step_one_fused_kernel"):
+        # the automatic choice at this size is two kernels (X-hat written once, then the product); the
+        # one fused kernel is timed beside it and priced the same way
+        one = res["us_per_step_one_fused_kernel"]
+        roof["form"] = "two kernels: X-hat and 1/rms written once by a first kernel, then the tile product scaled per row"
+        roof["one_fused_kernel"] = {"us_per_launch": one, "achieved": w.flops / one / 1e6, "frac": w.flops / one / 1e6 / MFMA_PEAK_TFLOPS}
+    return roof
+
+
+def headline(name, res, w, steps, args):
+    mem_bound = w.M <= 64
+    if mem_bound:
+        metric, unit, value = "fused RMSNorm+MatMul TB/s", "TB/s", res["TBps"]
+    else:
+        metric, unit, value = "fused RMSNorm+MatMul TFLOP/s", "TFLOP/s", res["TFLOPs"]
+    roof = roofline_of(name + ("+gate" if args.gated else ""), res, w, args.variant == "auto" and not args.gated)
+    return {
+        "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": res["us_per_step"] / 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{name}{' + gate' if args.gated else ''}: X {w.M}x{w.K}, W {w.K}x{w.N}, {w.dtype}",
+                   "variant": res["variant"], "launch": res["launch"],
+                   "copies_rotated": res["copies_rotated"], "graph": not args.no_graph,
+                   "timed_region": f"the {steps}-step graph replayed {res['timed_replays_of_the_graph']} times between two events "
+                                   f"(at least {MIN_REGION_MS:.0f} ms); ms_per_step = events / (replays x steps)"},
+        "roofline": roof,
+        "detail": res,
+    }
 
 
 if __name__ == "__main__":

@@ -329,7 +329,10 @@ rl_status rl_probe_mfma(void* sink, int iters, rl_dtype dt, void* stream);
  * 256-byte column strip and row part (`parts` of them, 1 <= parts <= rows), a wave-wide 16-byte load
  * covering 4 rows of 256 bytes.  rl_probe_read_flat: `workgroups` workgroups read contiguous shares of
  * `bytes` bytes, 1 KiB per wave-wide load.  Both read every byte once and write nothing
- * (`sink`: 4 bytes of DEVICE memory that are practically never written).
+ * (`sink`: 4 bytes of DEVICE memory that are practically never written).  While a stage trace is
+ * registered (rl_set_trace), workgroup b of the strips probe stamps slot 0 when it starts and slot 2
+ * when its rows have arrived; its strip is b / parts after the renumbering
+ * b -> (b mod 8) * (workgroups / 8) + b / 8 that applies when the workgroups divide by 8.
  */
 rl_status rl_probe_read_strips(const void* src, int64_t rows, int64_t row_bytes, int parts, void* sink, void* stream);
 rl_status rl_probe_read_flat(const void* src, size_t bytes, int workgroups, void* sink, void* stream);

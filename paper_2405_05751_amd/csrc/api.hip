@@ -748,7 +748,14 @@ rl_status rl_probe_read_strips(const void* src, int64_t rows, int64_t row_bytes,
     if (rows < 1 || row_bytes < 256 || row_bytes % 256 || parts < 1 || parts > rows ||
         (rows + 256) * row_bytes >= (int64_t(1) << 31) || (row_bytes / 256) * int64_t(parts) > (int64_t(1) << 20))
         return fail(RL_ERR_INVALID_ARG, "strips probe: row_bytes a multiple of 256, 1 <= parts <= rows, (rows + 256) * row_bytes < 2^31");
-    hipError_t e = launch_probe_strips(src, int(rows), int(row_bytes), parts, sink, static_cast<hipStream_t>(stream));
+    unsigned long long* trace;
+    int trace_groups;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        trace = g_trace; trace_groups = g_trace_groups;
+    }
+    hipError_t e = launch_probe_strips(src, int(rows), int(row_bytes), parts, sink, trace, trace_groups,
+                                       static_cast<hipStream_t>(stream));
     return e == hipSuccess ? RL_OK : fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
 }
 

@@ -360,8 +360,10 @@ hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStrea
 // range-checked buffer resource.  Flat: workgroup b of G reads the b-th contiguous share of the
 // buffer, 1 KiB per wave-wide load.
 __global__ __launch_bounds__(256) void probe_strips_kernel(const char* __restrict__ src, int rows, int row_bytes,
-                                                           int strips, int parts, uint32_t* __restrict__ sink)
+                                                           int strips, int parts, uint32_t* __restrict__ sink,
+                                                           unsigned long long* trace, int trace_groups)
 {
+    trace_stamp(trace, trace_groups, 0);                 // start (stage trace, if one is registered)
     int b = blockIdx.x;
     const int total = strips * parts;
     if ((total & 7) == 0) b = (b & 7) * (total >> 3) + (b >> 3);       // the parts of a strip share an XCD
@@ -395,6 +397,8 @@ __global__ __launch_bounds__(256) void probe_strips_kernel(const char* __restric
         }
     }
     if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = acc.x;   // practically never taken; keeps the loads alive
+    __syncthreads();
+    trace_stamp(trace, trace_groups, 2);                 // all of the workgroup's rows have arrived
 }
 
 __global__ __launch_bounds__(256) void probe_flat_kernel(const uint4_t* __restrict__ src, size_t n16, size_t share16,
@@ -429,10 +433,11 @@ __global__ __launch_bounds__(256) void probe_flat_kernel(const uint4_t* __restri
     if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = acc.x;
 }
 
-hipError_t launch_probe_strips(const void* src, int rows, int row_bytes, int parts, void* sink, hipStream_t s)
+hipError_t launch_probe_strips(const void* src, int rows, int row_bytes, int parts, void* sink,
+                               unsigned long long* trace, int trace_groups, hipStream_t s)
 {
     probe_strips_kernel<<<(row_bytes / 256) * parts, 256, 0, s>>>((const char*)src, rows, row_bytes, row_bytes / 256, parts,
-                                                                  (uint32_t*)sink);
+                                                                  (uint32_t*)sink, trace, trace_groups);
     return hipGetLastError();
 }
 
