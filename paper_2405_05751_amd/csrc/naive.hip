@@ -2,13 +2,17 @@
 // block, the stand-alone RMSNorm of the unfused A/B pair, and the measurement probes.
 #include "../../include/rmsnl.h"
 #include "common.hpp"
+#include <type_traits>
 
 namespace rmsnl {
 
 // ---------------------------------------------------------------------------------------------
 // Fallback: one workgroup = one row i and 64 consecutive columns; the K range is dealt to the four
 // waves (k = wave, wave+4, ...), so every thread carries two running sums -- A_i and B_in, the two
-// accumulators of the fused kernel -- and the four partials meet in LDS.  Works for every M, K, N.
+// accumulators of the fused kernel -- and the four partials meet in LDS.  Works for every M, K, N
+// (rows and column tiles share grid.x).  The 16-bit types accumulate in fp32 like the fast kernels;
+// the fp32 type, which exists for its 1e-5 bar and is served by this kernel alone, accumulates in
+// fp64, so that the bar holds for any K.
 // ---------------------------------------------------------------------------------------------
 template <typename T, bool FUSED, bool GATED>
 __global__ __launch_bounds__(256) void naive_kernel(const typename Elem<T>::store_t* __restrict__ X,
@@ -18,44 +22,53 @@ __global__ __launch_bounds__(256) void naive_kernel(const typename Elem<T>::stor
                                                     int M, int K, int N, float eps, float inv_K, int G)
 {
     // GATED: N = 2H; output column n < H needs its gate and its up column of W (gated_col)
+    typedef typename std::conditional<std::is_same<T, float>::value, double, float>::type acc_t;
     const int NO = GATED ? N / 2 : N;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int i = blockIdx.y;
-    const int n = blockIdx.x * 64 + lane;
+    const int tiles_n = (NO + 63) / 64;
+    const int i = blockIdx.x / tiles_n;
+    const int n = (blockIdx.x % tiles_n) * 64 + lane;
     const bool live = n < NO;
     const size_t xrow = size_t(i) * K;
 
-    float B = 0.f, U = 0.f, A = 0.f;
+    acc_t B = 0, U = 0, A = 0;
     for (int k = wave; k < K; k += 4) {
-        float x = Elem<T>::to_f32(X[xrow + k]);
-        float xg = x;
+        const acc_t x = Elem<T>::to_f32(X[xrow + k]);
+        acc_t xg = x;
         if (FUSED) {
-            A = __fmaf_rn(x, x, A);
-            xg = x * Elem<T>::to_f32(g[k]);
+            A = fma(x, x, A);
+            xg = x * acc_t(Elem<T>::to_f32(g[k]));
         }
-        float w = live ? Elem<T>::to_f32(W[size_t(k) * N + (GATED ? gated_col(n, false, NO, G) : n)]) : 0.f;
-        B = __fmaf_rn(xg, w, B);
+        const acc_t w = live ? Elem<T>::to_f32(W[size_t(k) * N + (GATED ? gated_col(n, false, NO, G) : n)]) : 0.f;
+        B = fma(xg, w, B);
         if (GATED) {
-            float wu = live ? Elem<T>::to_f32(W[size_t(k) * N + gated_col(n, true, NO, G)]) : 0.f;
-            U = __fmaf_rn(xg, wu, U);
+            const acc_t wu = live ? Elem<T>::to_f32(W[size_t(k) * N + gated_col(n, true, NO, G)]) : 0.f;
+            U = fma(xg, wu, U);
         }
     }
-    __shared__ float sB[4][64];
-    __shared__ float sU[4][64];
-    __shared__ float sA[4];
+    __shared__ acc_t sB[4][64];
+    __shared__ acc_t sU[4][64];
+    __shared__ acc_t sA[4];
     sB[wave][lane] = B;
     if (GATED) sU[wave][lane] = U;
     if (lane == 0) sA[wave] = A;
     __syncthreads();
     if (wave == 0 && live) {
-        float b = (sB[0][lane] + sB[1][lane]) + (sB[2][lane] + sB[3][lane]);
-        float u = GATED ? (sU[0][lane] + sU[1][lane]) + (sU[2][lane] + sU[3][lane]) : 0.f;
+        float b = float((sB[0][lane] + sB[1][lane]) + (sB[2][lane] + sB[3][lane]));
+        float u = GATED ? float((sU[0][lane] + sU[1][lane]) + (sU[2][lane] + sU[3][lane])) : 0.f;
         if (FUSED) {
-            float a = (sA[0] + sA[1]) + (sA[2] + sA[3]);
-            const float ri = row_scale(a, inv_K, eps);
-            b *= ri;
-            u *= ri;
+            const acc_t a = (sA[0] + sA[1]) + (sA[2] + sA[3]);
+            if (std::is_same<T, float>::value) {
+                // one rounding of the whole quotient instead of a rounded factor times a rounded sum
+                const double ri = 1.0 / sqrt(double(a) * (1.0 / double(K)) + double(eps));
+                b = float(double((sB[0][lane] + sB[1][lane]) + (sB[2][lane] + sB[3][lane])) * ri);
+                u = GATED ? float(double((sU[0][lane] + sU[1][lane]) + (sU[2][lane] + sU[3][lane])) * ri) : 0.f;
+            } else {
+                const float ri = row_scale(float(a), inv_K, eps);
+                b *= ri;
+                u *= ri;
+            }
         }
         if (GATED) b = silu(b) * u;
         Y[size_t(i) * NO + n] = Elem<T>::from_f32(b);
@@ -66,7 +79,7 @@ template <typename T, bool GATED>
 static hipError_t launch_naive_g(const Problem& p, hipStream_t s)
 {
     typedef typename Elem<T>::store_t S;
-    dim3 grid(((GATED ? p.N / 2 : p.N) + 63) / 64, p.M);
+    dim3 grid(unsigned(int64_t(((GATED ? p.N / 2 : p.N) + 63) / 64) * p.M));
     if (p.fused)
         naive_kernel<T, true, GATED><<<grid, 256, 0, s>>>((const S*)p.X, (const S*)p.g, (const S*)p.W, (S*)p.Y,
                                                           p.M, p.K, p.N, p.eps, 1.0f / float(p.K), p.gate_group);
@@ -134,8 +147,8 @@ hipError_t launch_interleave_gate_up(const void* W, void* Wi, int64_t K, int H, 
 
 hipError_t launch_naive(const Problem& p, hipStream_t s, const char** why)
 {
-    if (p.M > 65535) {          // grid.y limit
-        if (why) *why = "naive variant supports M <= 65535";
+    if (int64_t(((p.gated ? p.N / 2 : p.N) + 63) / 64) * p.M >= (int64_t(1) << 31)) {
+        if (why) *why = "naive variant supports ceil(N / 64) * M < 2^31 workgroups";
         return hipErrorInvalidValue;
     }
     switch (p.dt) {

@@ -147,7 +147,7 @@ template <> struct SqPair<Fp16> {
 // epilogue then forms SiLU(gate) * up in registers.  Only the column a lane fetches changes.
 // SPLIT (plain product only): the K range is split over workgroups, which leave fp32 partial tiles
 // for tile_reduce_kernel to add up, for shapes with too few tiles to fill the chip.
-template <typename T, bool FUSED, int NW, bool GATED, int SHAPE, bool SPLIT = false>
+template <typename T, bool FUSED, int NW, bool GATED, int SHAPE, bool SPLIT = false, bool BIGW = false>
 __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
 {
     static_assert(!SPLIT || (!FUSED && !GATED), "split-K runs the plain product");
@@ -231,22 +231,42 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
     // for a possible reader of the bytes in flight and waits for all outstanding loads first.  The
     // waits for these loads are therefore placed by hand (RL_WAIT_VM before the barriers).
     // (rows of W at or beyond Kend lie beyond the resource)
-    uint4_t wdesc = {uint32_t(uintptr_t(a.W)), uint32_t(uintptr_t(a.W) >> 32), uint32_t(Kend * a.N * 2),
+    uint4_t wdesc = {uint32_t(uintptr_t(a.W)), uint32_t(uintptr_t(a.W) >> 32), uint32_t(BIGW ? 0 : Kend * a.N * 2),
                            uint32_t(kTileFlags)};
+    // BIGW (K x N x 2 bytes >= 2^31, W may exceed 4 GiB): the resource of a load starts at the first row
+    // the load brings, so byte offsets inside it stay small; it ends with the slab's last row (rows at
+    // or beyond Kend read zero), or 2 GiB further on, whichever comes first; kTileOut lies beyond
+    // either.  Costs 1-2 % at 8192^3 (a 64-bit product per load), so only large W takes it.
+    const uint64_t wbase = uint64_t(uintptr_t(a.W));
+    const uint64_t wrow_bytes = uint64_t(a.N) * 2u;
     uint32_t bs_base = uint32_t(uintptr_t(Bs)) + uint32_t(wave) * 1024;         // LDS byte address of this wave's first KiB
     auto load_w = [&](auto checked, int buf, int k0, int p) {
-        const uint32_t dst = bs_base + uint32_t(buf * BK * BN * 2 + NW * p * 1024);
-        const unsigned rowoff = unsigned(kb + k0 + RPL * NW * p) * unsigned(a.N) * 2u;
-        int v = woff, so = int(rowoff);
-        if constexpr (decltype(checked)::value) {
-            v = woff == kTileOut ? kTileOut : int(unsigned(woff) + rowoff);
-            so = 0;
+        if constexpr (BIGW) {
+            const uint32_t dst = bs_base + uint32_t(buf * BK * BN * 2 + NW * p * 1024);
+            const int krow = kb + k0 + RPL * NW * p;             // first row of W this load brings
+            const uint64_t base = wbase + uint64_t(krow) * wrow_bytes;
+            const int64_t left = int64_t(Kend - krow) * int64_t(wrow_bytes);
+            const uint32_t nrec = left <= 0 ? 0u : left > 0x7fffffe0 ? 0x7fffffe0u : uint32_t(left);
+            const uint4_t desc = {uint32_t(base), uint32_t(base >> 32), nrec, uint32_t(kTileFlags)};
+            const int v = woff;
+            uint32_t keep;                       // M0 carries the LDS address; whatever it held is put back
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                         "buffer_load_dwordx4 %2, %3, 0 offen lds\n\ts_mov_b32 m0, %0"
+                         : "=&s"(keep) : "s"(dst), "v"(v), "s"(desc) : "memory");
+        } else {
+            const uint32_t dst = bs_base + uint32_t(buf * BK * BN * 2 + NW * p * 1024);
+            const unsigned rowoff = unsigned(kb + k0 + RPL * NW * p) * unsigned(a.N) * 2u;
+            int v = woff, so = int(rowoff);
+            if constexpr (decltype(checked)::value) {
+                v = woff == kTileOut ? kTileOut : int(unsigned(woff) + rowoff);
+                so = 0;
+            }
+            const uint4_t desc = wdesc;          // (operands of an asm inside a generic lambda must be its own locals)
+            uint32_t keep;                       // M0 carries the LDS address; whatever it held is put back
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                         "buffer_load_dwordx4 %2, %3, %4 offen lds\n\ts_mov_b32 m0, %0"
+                         : "=&s"(keep) : "s"(dst), "v"(v), "s"(desc), "s"(so) : "memory");
         }
-        const uint4_t desc = wdesc;          // (operands of an asm inside a generic lambda must be its own locals)
-        uint32_t keep;                       // M0 carries the LDS address; whatever it held is put back
-        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
-                     "buffer_load_dwordx4 %2, %3, %4 offen lds\n\ts_mov_b32 m0, %0"
-                     : "=&s"(keep) : "s"(dst), "v"(v), "s"(desc), "s"(so) : "memory");
     };
 
     float ssq[NJ];
@@ -467,19 +487,23 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void tile_kernel(TileArgs a)
 }
 
 // ------------------------------------------------------------------------------------------- host
-template <typename T, bool FUSED, int NW, bool GATED, int SHAPE>
+template <typename T, bool FUSED, int NW, bool GATED, int SHAPE, bool BIGW = false>
 static hipError_t tile_go(const TileArgs& a, dim3 grid, hipStream_t s)
 {
     static LdsOnce once;
-    hipError_t e = raise_lds_once(once, {(const void*)tile_kernel<T, FUSED, NW, GATED, SHAPE>}, int(tile_lds(SHAPE)));
+    hipError_t e = raise_lds_once(once, {(const void*)tile_kernel<T, FUSED, NW, GATED, SHAPE, false, BIGW>}, int(tile_lds(SHAPE)));
     if (e != hipSuccess) return e;
-    tile_kernel<T, FUSED, NW, GATED, SHAPE><<<grid, 64 * NW, tile_lds(SHAPE), s>>>(a);
+    tile_kernel<T, FUSED, NW, GATED, SHAPE, false, BIGW><<<grid, 64 * NW, tile_lds(SHAPE), s>>>(a);
     return hipGetLastError();
 }
 
+// W of 2 GiB or more: addressed row by row (see the kernel); the default tile shape only
+static bool tile_big_w(const Problem& p) { return int64_t(p.K) * p.N * 2 >= (int64_t(1) << 31); }
+
 template <typename T, bool FUSED, bool GATED>
-static hipError_t tile_nw(const TileArgs& a, dim3 grid, int nw, int shape, hipStream_t s)
+static hipError_t tile_nw(const TileArgs& a, dim3 grid, int nw, int shape, bool big, hipStream_t s)
 {
+    if (big) return tile_go<T, FUSED, 8, GATED, 0, true>(a, grid, s);
     if (shape) return nw == 8 ? tile_go<T, FUSED, 8, GATED, 1>(a, grid, s) : tile_go<T, FUSED, 4, GATED, 1>(a, grid, s);
     return nw == 8 ? tile_go<T, FUSED, 8, GATED, 0>(a, grid, s) : tile_go<T, FUSED, 4, GATED, 0>(a, grid, s);
 }
@@ -491,8 +515,13 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
         if (why) *why = "tile variant needs N % 8 == 0 and K % 8 == 0";
         return hipErrorInvalidValue;
     }
-    if (int64_t(p.K) * p.N * 2 >= (int64_t(1) << 31) || int64_t(256) * p.K * 2 >= (int64_t(1) << 31)) {
-        if (why) *why = "tile variant needs K*N < 2^30";
+    if (int64_t(256) * p.K * 2 >= (int64_t(1) << 31) || p.N >= (1 << 25)) {
+        if (why) *why = "tile variant needs K < 2^22 and N < 2^25";
+        return hipErrorInvalidValue;
+    }
+    const bool big = tile_big_w(p);
+    if (big && ((p.k_split != 0 && p.k_split != 8) || (p.n_tile != 0 && p.n_tile != 256))) {
+        if (why) *why = "tile variant: a W of 2 GiB or more runs 256x256 tiles with 8 waves only";
         return hipErrorInvalidValue;
     }
     // tuning: k_split carries the waves per workgroup for this variant (0 = default)
@@ -531,12 +560,12 @@ hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why)
     if (p.plan) { p.plan[0] = BN; p.plan[1] = nw; p.plan[2] = int(grid.x); }
     const bool fused = p.fused != 0;
     if (p.gated && !fused)                  // gate over a product of a materialised X-hat, scaled per row
-        return p.dt == F16 ? tile_nw<Fp16, false, true>(a, grid, nw, shape, s) : tile_nw<Bf16, false, true>(a, grid, nw, shape, s);
+        return p.dt == F16 ? tile_nw<Fp16, false, true>(a, grid, nw, shape, big, s) : tile_nw<Bf16, false, true>(a, grid, nw, shape, big, s);
     if (p.gated)
-        return p.dt == F16 ? tile_nw<Fp16, true, true>(a, grid, nw, shape, s) : tile_nw<Bf16, true, true>(a, grid, nw, shape, s);
+        return p.dt == F16 ? tile_nw<Fp16, true, true>(a, grid, nw, shape, big, s) : tile_nw<Bf16, true, true>(a, grid, nw, shape, big, s);
     if (p.dt == F16)
-        return fused ? tile_nw<Fp16, true, false>(a, grid, nw, shape, s) : tile_nw<Fp16, false, false>(a, grid, nw, shape, s);
-    return fused ? tile_nw<Bf16, true, false>(a, grid, nw, shape, s) : tile_nw<Bf16, false, false>(a, grid, nw, shape, s);
+        return fused ? tile_nw<Fp16, true, false>(a, grid, nw, shape, big, s) : tile_nw<Fp16, false, false>(a, grid, nw, shape, big, s);
+    return fused ? tile_nw<Bf16, true, false>(a, grid, nw, shape, big, s) : tile_nw<Bf16, false, false>(a, grid, nw, shape, big, s);
 }
 
 // --------------------------------------------------------- split-K product for shapes with few tiles
@@ -645,7 +674,7 @@ static void tile_rem_plan(const Problem& p, int* full, int* rem, int* S, int* k_
     const int64_t tiles = int64_t((p.M + 255) / 256) * ((p.N + 255) / 256);
     *full = int(tiles / 256 * 256);
     *rem = 0; *S = 1; *k_slab = p.K;
-    if (p.gated || tiles <= 256 || tiles > (int64_t(1) << 24)) return;
+    if (p.gated || tiles <= 256 || tiles > (int64_t(1) << 24) || tile_big_w(p)) return;
     const int r = int(tiles - *full);
     int s = r ? std::min(16, 256 / r) : 1;
     s = std::min(s, std::max(1, p.K / 256));
@@ -767,7 +796,7 @@ static void tile_pre_split(const Problem& p, int* S, int* k_slab)
         *S = (p.K + ks - 1) / ks;
         *k_slab = ks;
     }
-    if (p.N % 8 != 0 || (p.gated && p.N % 16 != 0)) { *S = 1; *k_slab = p.K; }
+    if (p.N % 8 != 0 || (p.gated && p.N % 16 != 0) || tile_big_w(p)) { *S = 1; *k_slab = p.K; }
 }
 
 size_t tile_pre_workspace_bytes(const Problem& p)
@@ -788,8 +817,8 @@ hipError_t launch_tile_pre(const Problem& p, hipStream_t s, const char** why)
         return hipErrorInvalidValue;
     }
     // check that the later kernels can run before the first is launched: all or none
-    if (int64_t(p.K) * p.N * 2 >= (int64_t(1) << 31) || int64_t(256) * p.K * 2 >= (int64_t(1) << 31)) {
-        if (why) *why = "tile variant needs K*N < 2^30";
+    if (int64_t(256) * p.K * 2 >= (int64_t(1) << 31) || p.N >= (1 << 25)) {
+        if (why) *why = "tile variant needs K < 2^22 and N < 2^25";
         return hipErrorInvalidValue;
     }
     int S, k_slab;
