@@ -233,3 +233,52 @@ def ff_rmsnorm_linear(X, g, W, p: int, reordered: bool):
                     acc = (acc + ((int(X[i, k]) * int(g[k]) % p) * rinv % p) * int(W[k, n])) % p
             Y[i, n] = acc * rinv % p if reordered else acc
     return Y
+
+
+# ---------------------------------------------------------------------------------------------
+# Random tests over TWO fields (Table 3 in full): every value is a pair (x_p, x_q) from Z_p x Z_q,
+# q a prime that divides p - 1.  Add, Sub, Mul, Div and Sqrt act on the two components
+# independently; Exp takes the q component into the exponent of a q-th root of unity omega of Z_p
+# and yields a p component only: (omega^{x_q} mod p, -).  An exponential may occur once on a path.
+# Arrays of pairs have a last axis of length 2, [..., 0] the p component and [..., 1] the q component.
+# ---------------------------------------------------------------------------------------------
+def ff_roots_of_unity(p: int, q: int):
+    """The q-th roots of unity of Z_p (all w with w^q = 1; there are q of them when q divides p - 1)."""
+    if (p - 1) % q:
+        raise ValueError("q must divide p - 1")
+    return [w for w in range(1, p) if pow(w, q, p) == 1]
+
+
+def ff_exp(x_q: int, omega: int, p: int, q: int) -> int:
+    """The Exp row of Table 3: omega^{x_q} mod p for x_q in Z_q."""
+    return pow(int(omega), int(x_q) % q, p)
+
+
+def ff_pair_rmsnorm_linear(X, g, W, p: int, q: int, reordered: bool):
+    """The block on pairs: each component is the block over its own field (Add, Mul, Div, Sqrt rows)."""
+    X = np.asarray(X, dtype=np.int64); g = np.asarray(g, dtype=np.int64); W = np.asarray(W, dtype=np.int64)
+    Zp = ff_rmsnorm_linear(X[..., 0], g[..., 0], W[..., 0], p, reordered)
+    Zq = ff_rmsnorm_linear(X[..., 1], g[..., 1], W[..., 1], q, reordered)
+    return np.stack([Zp, Zq], axis=-1)
+
+
+def ff_pair_gated_mlp(X, g, W, p: int, q: int, omega: int, reordered: bool):
+    """The gated block on pairs: Z = the block on W = [gate | up]; Y = SiLU(G) * U with
+    SiLU(v) = v / (1 + exp(-v)).  The exponential takes the q component of -G and leaves a p
+    component (Exp row); everything after it is arithmetic in Z_p, so Y has a p component only.
+    Where 1 + exp(-G) has no inverse (it is 0 in Z_p) the output is defined as 0.
+    reordered selects the graph Z is evaluated with (Eq. 1 first, or division after the product)."""
+    Z = ff_pair_rmsnorm_linear(X, g, W, p, q, reordered)
+    M, N, _ = Z.shape
+    H = N // 2
+    Y = np.zeros((M, H), dtype=np.int64)
+    for i in range(M):
+        for h in range(H):
+            G_p, G_q = int(Z[i, h, 0]), int(Z[i, h, 1])
+            U_p = int(Z[i, H + h, 0])
+            e = ff_exp((-G_q) % q, omega, p, q)
+            den = (1 + e) % p
+            if den == 0:
+                continue
+            Y[i, h] = G_p * pow(den, p - 2, p) % p * U_p % p
+    return Y
