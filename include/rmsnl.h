@@ -277,6 +277,30 @@ rl_status rl_ff_rmsnorm_linear(const void* X, const void* g, const void* W, void
                                int64_t M, int64_t K, int64_t N, uint32_t p, int reordered, void* stream);
 
 /*
+ * The paper's random tests in full (Table 3 with its Exp row; Theorems 2 and 3): the block, and the
+ * gated block with its exponential (SiLU), evaluated on PAIRS (x_p, x_q) over Z_p x Z_q with the primes
+ * of the paper's implementation, p = 227 and q = 113 (q divides p - 1).  X [M][K], g [K], W [K][N] and Y
+ * are DEVICE arrays of uint16, an element being x_p | x_q << 8 (x_p < 227, x_q < 113); 16-byte aligned.
+ * Add, Mul, Div and Sqrt act on both components (sqrt: the canonical root of rl_ff_rmsnorm_linear; a
+ * row whose mean square is 0 in a field gets 0 there); Exp maps a pair to omega^{x_q} mod p, with omega
+ * a q-th root of unity of Z_p that the caller samples, and leaves a p component only.
+ *   gated = 0: Y [M][N] pairs, the block.   gated = 1: N = 2H, W = [gate | up], Y [M][H] = G / (1 +
+ *   exp(-G)) * U in Z_p (q component 0; 0 where 1 + exp(-G) has no inverse).
+ *   schedule = 0: the graph as the paper starts from it -- Eq. 1 first, then the product, then the
+ *   activation -- one thread per output.
+ *   schedule = 1: the GEMV split-K kernel that rmsnorm_linear and rmsnorm_gated_mlp run, instantiated on
+ *   this element type: same column tiles, K slabs (`slabs`, 0 = the kernel's own choice), reduction
+ *   through LDS, partials in the workspace added by the last arriver in slab order, same pairing of
+ *   gate and up columns, same rewrite (division after the product).  M <= 16, K % 8 == 0, N % 8 == 0
+ *   (gated: N % 16 == 0), else RL_ERR_UNSUPPORTED.
+ * Equal outputs of the two schedules on random inputs certify the shipped schedule against the graph
+ * with the error bound of the paper's theorems; integer arithmetic throughout, results are exact.
+ * Neither 227 nor 113 may divide K.
+ */
+rl_status rl_ff_pairs(const void* X, const void* g, const void* W, void* Y, int64_t M, int64_t K, int64_t N,
+                      uint32_t omega, int gated, int schedule, int slabs, void* stream);
+
+/*
  * Workspace (split-K partial sums + arrival counters; X (.) g, 1/rms and partial tiles of the two-kernel
  * tile form, split merges of rl_qknorm_attention).  By default the library allocates
  * rl_workspace_default_bytes() per device on first need and switches to a larger allocation (at least

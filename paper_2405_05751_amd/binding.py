@@ -97,6 +97,9 @@ EXPORTS.update({
                                             ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                             ctypes.c_int, ctypes.c_int, ctypes.POINTER(LaunchOpts), ctypes.c_void_p]),
     "rl_last_launch": (ctypes.c_int, [ctypes.POINTER(ctypes.c_int)] * 4),
+    "rl_ff_pairs": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                                   ctypes.c_int64, ctypes.c_int64, ctypes.c_uint32, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                   ctypes.c_void_p]),
     "rl_probe_read_strips": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
                                             ctypes.c_void_p, ctypes.c_void_p]),
     "rl_probe_read_flat": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p,
@@ -385,6 +388,19 @@ def rl_ff_rmsnorm_linear(X: torch.Tensor, g: torch.Tensor, W: torch.Tensor, p: i
     Y = torch.empty((M, N), dtype=torch.int32, device=X.device)
     _check(lib().rl_ff_rmsnorm_linear(_dev(X, "X"), _dev(g, "g"), _dev(W, "W"), _dev(Y, "Y"), M, K, N, int(p),
                                       int(bool(reordered)), _stream(stream)))
+    return Y
+
+
+def rl_ff_pairs(X: torch.Tensor, g: torch.Tensor, W: torch.Tensor, omega: int, gated: bool, schedule: int,
+                slabs: int = 0, stream=None) -> torch.Tensor:
+    """The block (or the gated block) on pairs over Z_227 x Z_113: int16 device tensors holding x_p | x_q << 8."""
+    M, K = X.shape
+    K2, N = W.shape
+    if K2 != K or g.shape != (K,) or any(t.dtype != torch.int16 for t in (X, g, W)):
+        raise ValueError("shape or dtype mismatch (int16 tensors expected)")
+    Y = torch.empty((M, N // 2 if gated else N), dtype=torch.int16, device=X.device)
+    _check(lib().rl_ff_pairs(_dev(X, "X"), _dev(g, "g"), _dev(W, "W"), _dev(Y, "Y"), M, K, N, int(omega),
+                             int(bool(gated)), int(schedule), int(slabs), _stream(stream)))
     return Y
 
 

@@ -635,6 +635,46 @@ rl_status rl_ff_rmsnorm_linear(const void* X, const void* g, const void* W, void
     return RL_OK;
 }
 
+rl_status rl_ff_pairs(const void* X, const void* g, const void* W, void* Y, int64_t M, int64_t K, int64_t N,
+                      uint32_t omega, int gated, int schedule, int slabs, void* stream)
+{
+    if (!X || !g || !W || !Y) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (rl_status st = check_dims(M, K, N, RL_BF16)) return st;
+    if (!aligned16(X) || !aligned16(g) || !aligned16(W) || !aligned16(Y))
+        return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    if (schedule != 0 && schedule != 1) return fail(RL_ERR_INVALID_ARG, "schedule must be 0 (reference graph) or 1 (gemv split-K kernel)");
+    if (slabs < 0) return fail(RL_ERR_INVALID_ARG, "slabs must be >= 0");
+    if (gated && (N % 2)) return fail(RL_ERR_INVALID_ARG, "the gated block needs an even N (= 2H)");
+    if (K % int64_t(kFfP) == 0 || K % int64_t(kFfQ) == 0) return fail(RL_ERR_INVALID_ARG, "neither 227 nor 113 may divide K (the mean needs 1/K)");
+    uint64_t w = omega % kFfP, t = 1;
+    for (uint32_t i = 0; i < kFfQ; ++i) t = t * w % kFfP;
+    if (omega == 0 || omega >= kFfP || t != 1) return fail(RL_ERR_INVALID_ARG, "omega must be a 113th root of unity of Z_227");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (schedule == 0) {
+        if (M > 65535) return fail(RL_ERR_UNSUPPORTED, "the reference evaluation supports M <= 65535");
+        hipError_t e = launch_ff_pairs_ref(X, g, W, Y, int(M), int(K), int(N), omega, gated ? 1 : 0, s);
+        return e == hipSuccess ? RL_OK : fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+    }
+    Problem p{};
+    p.X = X; p.g = g; p.W = W; p.Y = Y;
+    p.M = int(M); p.K = int(K); p.N = int(N);
+    p.fused = 1; p.gated = gated ? 1 : 0; p.dt = BF16; p.n_tile = 128; p.k_split = slabs;
+    tl_last_plan[0] = tl_last_plan[1] = tl_last_plan[2] = 0;
+    p.plan = tl_last_plan;
+    const size_t need = gemv_workspace_bytes(p);
+    if (need) {
+        Workspace ws;
+        if (rl_status st = get_workspace(need, s, &ws)) return st;
+        carve(ws, p);
+    }
+    const char* why = "the gemv kernel cannot run this shape";
+    hipError_t e = launch_gemv_ff(p, omega, s, &why);
+    if (e == hipErrorInvalidValue) { (void)hipGetLastError(); return fail(RL_ERR_UNSUPPORTED, "%s", why); }
+    if (e != hipSuccess) return fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+    tl_last_variant = RL_GEMV_SPLITK;
+    return RL_OK;
+}
+
 rl_status rl_set_variant(rl_variant v)
 {
     if (v < RL_AUTO || v > RL_MFMA_TILE_PRE) return fail(RL_ERR_INVALID_ARG, "unknown variant");

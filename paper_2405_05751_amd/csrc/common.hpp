@@ -96,6 +96,12 @@ hipError_t launch_ntrans(const void* X, const void* Hh, const void* A, float eps
 hipError_t launch_ff_block(const void* X, const void* g, const void* W, void* Y, int M, int K, int N,
                            uint32_t p, int reordered, hipStream_t s);
 
+// the GEMV split-K kernel on pairs over Z_227 x Z_113 (X, g, W, Y: 16-bit elements x_p | x_q << 8)
+hipError_t launch_gemv_ff(const Problem& p, uint32_t omega, hipStream_t s, const char** why);
+// reference evaluation of the same graphs on pairs, one thread per output, Eq. 1 first
+hipError_t launch_ff_pairs_ref(const void* X, const void* g, const void* W, void* Y, int M, int K, int N,
+                               uint32_t omega, int gated, hipStream_t s);
+
 hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t s);
 hipError_t launch_probe_mfma(void* sink, int iters, DType dt, hipStream_t s);
@@ -166,6 +172,93 @@ template <> struct Elem<float> {
     typedef float store_t;
     static __device__ __forceinline__ float to_f32(float f) { return f; }
     static __device__ __forceinline__ float from_f32(float f) { return f; }
+};
+
+// ---- the paper's random tests over finite fields (Table 3), as an element type of the kernels.
+// A value is a pair (x_p, x_q) from Z_p x Z_q with the primes the paper's implementation uses,
+// p = 227 and q = 113 (q divides p - 1; the pair fits 16 bits).  Stored as x_p | x_q << 8 in the
+// 16 bits a bf16 element takes, so a kernel instantiated on this type moves exactly the bytes it
+// moves for bf16; in registers a pair rides in the 32 bits of a float as x_p | x_q << 16 (never
+// touched by floating-point arithmetic: moves, shuffles and LDS keep bits as they are).
+struct Ff {};
+constexpr uint32_t kFfP = 227, kFfQ = 113;
+
+template <> struct Elem<Ff> {
+    typedef u16 store_t;
+    static __device__ __forceinline__ float widen(uint32_t e) { return __uint_as_float((e & 0xffu) | ((e >> 8 & 0xffu) << 16)); }
+    static __device__ __forceinline__ float lo(uint32_t p) { return widen(p & 0xffffu); }
+    static __device__ __forceinline__ float hi(uint32_t p) { return widen(p >> 16); }
+    static __device__ __forceinline__ uint32_t narrow(float f) {
+        const uint32_t u = __float_as_uint(f);
+        return (u & 0xffu) | ((u >> 16 & 0xffu) << 8);
+    }
+    static __device__ __forceinline__ uint32_t pack(float a, float b) { return narrow(a) | (narrow(b) << 16); }
+};
+
+__device__ __forceinline__ uint32_t ff_pow_mod(uint32_t b, uint32_t e, uint32_t m) {
+    uint32_t r = 1;
+    b %= m;
+    while (e) { if (e & 1) r = r * b % m; b = b * b % m; e >>= 1; }
+    return r;
+}
+// canonical root: the smallest y with y^2 = x; for a non-residue x, the smallest y with y^2 = x n, n the least non-residue
+__device__ __forceinline__ uint32_t ff_root_mod(uint32_t x, uint32_t m) {
+    for (int pass = 0; pass < 2; ++pass) {
+        for (uint32_t y = 0; y < m; ++y)
+            if (y * y % m == x) return y;
+        uint32_t n = 2;
+        for (;; ++n) { bool res = false; for (uint32_t y = 1; y < m && !res; ++y) res = y * y % m == n; if (!res) break; }
+        x = x * n % m;
+    }
+    return 0;
+}
+
+// The arithmetic of a kernel instantiation: fp32 for the 16-bit floating types, pairs for Ff.
+// rinv: the row factor from the sum of squares (inv_K and eps as the kernels carry them: for Ff,
+// inv_K holds the pair (1/K mod p, 1/K mod q) and eps holds omega, the sampled q-th root of unity,
+// both as bits).  out: one output from its accumulated product(s) and the row factor.
+template <typename T> struct Arith {
+    static __device__ __forceinline__ float add(float a, float b) { return a + b; }
+    static __device__ __forceinline__ float mul(float a, float b) { return a * b; }
+    static __device__ __forceinline__ float fma(float a, float b, float c) { return __fmaf_rn(a, b, c); }
+    static __device__ __forceinline__ float4_t add4(float4_t a, float4_t b) { return a + b; }
+    static __device__ __forceinline__ float rinv(float sumsq, float inv_K, float eps) {
+        return 1.0f / __fsqrt_rn(__fmaf_rn(sumsq, inv_K, eps));
+    }
+    static __device__ __forceinline__ float out(float v, float ri, float) { return v * ri; }
+    static __device__ __forceinline__ float out_gated(float v, float u, float ri, float) {
+        const float gt = v * ri;
+        return gt / (1.0f + __expf(-gt)) * (u * ri);
+    }
+    static __device__ __forceinline__ float one() { return 1.f; }
+};
+
+template <> struct Arith<Ff> {
+    static __device__ __forceinline__ uint32_t P(float f) { return __float_as_uint(f) & 0xffffu; }
+    static __device__ __forceinline__ uint32_t Q(float f) { return __float_as_uint(f) >> 16; }
+    static __device__ __forceinline__ float make(uint32_t xp, uint32_t xq) { return __uint_as_float(xp | (xq << 16)); }
+    static __device__ __forceinline__ float add(float a, float b) { return make((P(a) + P(b)) % kFfP, (Q(a) + Q(b)) % kFfQ); }
+    static __device__ __forceinline__ float mul(float a, float b) { return make(P(a) * P(b) % kFfP, Q(a) * Q(b) % kFfQ); }
+    static __device__ __forceinline__ float fma(float a, float b, float c) {
+        return make((P(a) * P(b) + P(c)) % kFfP, (Q(a) * Q(b) + Q(c)) % kFfQ);
+    }
+    static __device__ __forceinline__ float4_t add4(float4_t a, float4_t b) {
+        return float4_t{add(a[0], b[0]), add(a[1], b[1]), add(a[2], b[2]), add(a[3], b[3])};
+    }
+    // 1 / sqrt(A / K) in each field (Div and Sqrt rows); a mean square of 0 has no inverse root: factor 0
+    static __device__ __forceinline__ float rinv(float sumsq, float inv_K, float) {
+        const uint32_t rp = ff_root_mod(P(sumsq) * P(inv_K) % kFfP, kFfP), rq = ff_root_mod(Q(sumsq) * Q(inv_K) % kFfQ, kFfQ);
+        return make(rp ? ff_pow_mod(rp, kFfP - 2, kFfP) : 0, rq ? ff_pow_mod(rq, kFfQ - 2, kFfQ) : 0);
+    }
+    static __device__ __forceinline__ float out(float v, float ri, float) { return mul(v, ri); }
+    // SiLU(G) * U = G / (1 + exp(-G)) * U: the exponential takes the q component (Exp row), the rest is Z_p
+    static __device__ __forceinline__ float out_gated(float v, float u, float ri, float omega) {
+        const float gt = mul(v, ri), up = mul(u, ri);
+        const uint32_t e = ff_pow_mod(__float_as_uint(omega), (kFfQ - Q(gt)) % kFfQ, kFfP);
+        const uint32_t den = (1 + e) % kFfP;
+        return make(den ? P(gt) * ff_pow_mod(den, kFfP - 2, kFfP) % kFfP * P(up) % kFfP : 0, 0);
+    }
+    static __device__ __forceinline__ float one() { return make(1, 1); }
 };
 
 // rinv = 1 / sqrt(A / K + eps), correctly rounded division and root (not the fast approximations)

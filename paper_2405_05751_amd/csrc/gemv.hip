@@ -18,6 +18,7 @@
 //     partials in slab order (so the result does not depend on arrival order), scales by
 //     1/sqrt(A/K + eps), rounds once and stores.
 #include <algorithm>
+#include <cstring>
 #include "common.hpp"
 #include "splitk.hpp"
 
@@ -183,10 +184,10 @@ __global__ __launch_bounds__(64 * gemv_waves(MT)) void gemv_splitk_kernel(
                     const float x0 = Elem<T>::lo(xv[m][e]), x1 = Elem<T>::hi(xv[m][e]);
                     h[2 * e] = x0; h[2 * e + 1] = x1;
                     if (FUSED) {
-                        ss[m] = __fmaf_rn(x0, x0, ss[m]);
-                        ss[m] = __fmaf_rn(x1, x1, ss[m]);
-                        h[2 * e] = x0 * Elem<T>::lo(gv[e]);
-                        h[2 * e + 1] = x1 * Elem<T>::hi(gv[e]);
+                        ss[m] = Arith<T>::fma(x0, x0, ss[m]);
+                        ss[m] = Arith<T>::fma(x1, x1, ss[m]);
+                        h[2 * e] = Arith<T>::mul(x0, Elem<T>::lo(gv[e]));
+                        h[2 * e + 1] = Arith<T>::mul(x1, Elem<T>::hi(gv[e]));
                     }
                 }
                 float4_t* dst = (float4_t*)(xs + m * a.k_slab + kk);
@@ -237,10 +238,10 @@ __global__ __launch_bounds__(64 * gemv_waves(MT)) void gemv_splitk_kernel(
                     const float x0 = Elem<T>::lo(xq[d][m][e]), x1 = Elem<T>::hi(xq[d][m][e]);
                     h[m][2 * e] = x0; h[m][2 * e + 1] = x1;
                     if (FUSED) {
-                        ss[m] = __fmaf_rn(x0, x0, ss[m]);
-                        ss[m] = __fmaf_rn(x1, x1, ss[m]);
-                        h[m][2 * e] = x0 * Elem<T>::lo(gq[d][e]);
-                        h[m][2 * e + 1] = x1 * Elem<T>::hi(gq[d][e]);
+                        ss[m] = Arith<T>::fma(x0, x0, ss[m]);
+                        ss[m] = Arith<T>::fma(x1, x1, ss[m]);
+                        h[m][2 * e] = Arith<T>::mul(x0, Elem<T>::lo(gq[d][e]));
+                        h[m][2 * e + 1] = Arith<T>::mul(x1, Elem<T>::hi(gq[d][e]));
                     }
                 }
         }
@@ -255,7 +256,7 @@ __global__ __launch_bounds__(64 * gemv_waves(MT)) void gemv_splitk_kernel(
 #pragma unroll
             for (int m = 0; m < MT; ++m)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[m][e] = __fmaf_rn(h[m][j], wf[e], acc[m][e]);
+                for (int e = 0; e < 8; ++e) acc[m][e] = Arith<T>::fma(h[m][j], wf[e], acc[m][e]);
         }
     };
 
@@ -279,16 +280,20 @@ __global__ __launch_bounds__(64 * gemv_waves(MT)) void gemv_splitk_kernel(
 #pragma unroll
         for (int m = 0; m < MT; ++m)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[m][e] += __shfl_xor(acc[m][e], off, 64);
+            for (int e = 0; e < 8; ++e) acc[m][e] = Arith<T>::add(acc[m][e], __shfl_xor(acc[m][e], off, 64));
         if (FUSED && !XLDS) {
 #pragma unroll
-            for (int m = 0; m < MT; ++m) ss[m] += __shfl_xor(ss[m], off, 64);
+            for (int m = 0; m < MT; ++m) ss[m] = Arith<T>::add(ss[m], __shfl_xor(ss[m], off, 64));
         }
     }
     if (FUSED) {
 #pragma unroll
         for (int m = 0; m < MT; ++m) {
-            const float v = XLDS ? wave_sum(ss[m]) : ss[m];
+            float v = ss[m];
+            if (XLDS) {
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) v = Arith<T>::add(v, __shfl_xor(v, off, 64));
+            }
             if (lane == 0) s_sumsq[wave][m] = v;
         }
     }
@@ -409,6 +414,69 @@ static hipError_t gemv_mt(const GemvArgs& a, bool fused, bool gated, const GemvP
     case 4:  return gemv_lpr<T, 4>(a, fused, gated, pl, s);
     case 8:  return gemv_lpr<T, 8>(a, fused, gated, pl, s);
     default: return gemv_lpr<T, 16>(a, fused, gated, pl, s);
+    }
+}
+
+// ---- the same kernel on pairs over Z_227 x Z_113 (the paper's random tests over finite fields): the
+// schedule that ships -- column tiles, K slabs, lane groups, the reduction through LDS, partials in the
+// workspace, the last arriver adding them in slab order, the pairing of gate and up columns -- with the
+// arithmetic of Table 3 in place of fp32.  128 columns per workgroup (the automatic choice); W through
+// LDS up to four rows, as for the floating types.
+template <int MT>
+static hipError_t gemv_go_ff(const GemvArgs& a, bool gated, const GemvPlan& pl, hipStream_t s)
+{
+    dim3 grid(pl.n_tiles * pl.S);
+    static LdsOnce once;
+    hipError_t e = raise_lds_once(once, {(const void*)gemv_splitk_kernel<Ff, MT, 16, true, false>,
+                                         (const void*)gemv_splitk_kernel<Ff, MT, 16, true, true>}, 128 * 1024);
+    if (e != hipSuccess) return e;
+    const int nt = 64 * gemv_waves(MT);
+    const GemvCold c{a.Y, a.eps, a.inv_K, a.H, a.G, a.ws_partial, a.ws_sumsq, a.counter, a.trace, a.trace_groups};
+    if (gated) gemv_splitk_kernel<Ff, MT, 16, true, true><<<grid, nt, pl.lds, s>>>(a.W, a.X, a.g, a.M, a.K, a.N, a.k_slab, a.S, a.n_tiles, c);
+    else       gemv_splitk_kernel<Ff, MT, 16, true, false><<<grid, nt, pl.lds, s>>>(a.W, a.X, a.g, a.M, a.K, a.N, a.k_slab, a.S, a.n_tiles, c);
+    return hipGetLastError();
+}
+
+static uint32_t host_pow_mod(uint32_t b, uint32_t e, uint32_t m)
+{
+    uint64_t r = 1, x = b % m;
+    while (e) { if (e & 1) r = r * x % m; x = x * x % m; e >>= 1; }
+    return uint32_t(r);
+}
+
+// p: the problem as for the 16-bit floating types (dt is ignored); omega: a 113th root of unity of Z_227
+hipError_t launch_gemv_ff(const Problem& p, uint32_t omega, hipStream_t s, const char** why)
+{
+    Problem q = p;
+    q.dt = BF16;
+    q.n_tile = 128;
+    GemvPlan pl = gemv_plan(q);
+    if (!pl.ok) { if (why) *why = pl.why; return hipErrorInvalidValue; }
+    if (pl.LPR != 16) { if (why) *why = "field instantiation of the gemv kernel runs 128 columns per workgroup"; return hipErrorInvalidValue; }
+    if (pl.S > 1 && (!p.ws_partial || !p.ws_sumsq || !p.ws_counter)) {
+        if (why) *why = "split-K needs the workspace";
+        return hipErrorInvalidValue;
+    }
+    if (p.plan) { p.plan[0] = 128; p.plan[1] = pl.S; p.plan[2] = pl.n_tiles * pl.S; }
+    GemvArgs a;
+    a.X = (const u16*)p.X; a.g = (const u16*)p.g; a.W = (const uint4_t*)p.W; a.Y = (u16*)p.Y;
+    a.M = p.M; a.K = p.K; a.N = p.N;
+    // the two float fields carry field constants as bits: omega, and the pair (1/K mod p, 1/K mod q)
+    const uint32_t inv_k = host_pow_mod(uint32_t(p.K % int(kFfP)), kFfP - 2, kFfP) | (host_pow_mod(uint32_t(p.K % int(kFfQ)), kFfQ - 2, kFfQ) << 16);
+    memcpy(&a.eps, &omega, 4);
+    memcpy(&a.inv_K, &inv_k, 4);
+    a.k_slab = pl.k_slab; a.S = pl.S; a.n_tiles = pl.n_tiles;
+    a.H = p.gated ? p.N / 2 : 0;
+    a.G = p.gate_group;
+    a.ws_partial = p.ws_partial; a.ws_sumsq = p.ws_sumsq; a.counter = p.ws_counter;
+    a.trace = p.trace; a.trace_groups = p.trace_groups;
+    const bool gated = p.gated != 0;
+    switch (pl.MT) {
+    case 1:  return gemv_go_ff<1>(a, gated, pl, s);
+    case 2:  return gemv_go_ff<2>(a, gated, pl, s);
+    case 4:  return gemv_go_ff<4>(a, gated, pl, s);
+    case 8:  return gemv_go_ff<8>(a, gated, pl, s);
+    default: return gemv_go_ff<16>(a, gated, pl, s);
     }
 }
 

@@ -321,6 +321,41 @@ hipError_t launch_ff_block(const void* X, const void* g, const void* W, void* Y,
     return hipGetLastError();
 }
 
+// The block and the gated block on pairs over Z_227 x Z_113 (Table 3 in full, with the Exp row), in the
+// graph form the paper starts from: Eq. 1 first (every X-hat divided by the root), then the product,
+// then the activation as a step of its own.  One thread per output; elements are x_p | x_q << 8.
+__global__ __launch_bounds__(256) void ff_pairs_ref_kernel(const u16* __restrict__ X, const u16* __restrict__ g,
+                                                           const u16* __restrict__ W, u16* __restrict__ Y,
+                                                           int M, int K, int N, uint32_t omega, int gated)
+{
+    typedef Arith<Ff> Ar;
+    const int NO = gated ? N / 2 : N;
+    const int n = blockIdx.x * 256 + threadIdx.x, i = blockIdx.y;
+    if (n >= NO) return;
+    const u16* xi = X + size_t(i) * K;
+    float a = Ar::make(0, 0);
+    for (int k = 0; k < K; ++k) { const float x = Elem<Ff>::widen(xi[k]); a = Ar::fma(x, x, a); }
+    const float inv_k = Ar::make(ff_pow_mod(uint32_t(K) % kFfP, kFfP - 2, kFfP), ff_pow_mod(uint32_t(K) % kFfQ, kFfQ - 2, kFfQ));
+    const float ri = Ar::rinv(a, inv_k, 0.f);
+    float z = Ar::make(0, 0), u = Ar::make(0, 0);
+    for (int k = 0; k < K; ++k) {
+        const float t = Ar::mul(Ar::mul(Elem<Ff>::widen(xi[k]), Elem<Ff>::widen(g[k])), ri);   // Eq. 1
+        z = Ar::fma(t, Elem<Ff>::widen(W[size_t(k) * N + n]), z);
+        if (gated) u = Ar::fma(t, Elem<Ff>::widen(W[size_t(k) * N + NO + n]), u);
+    }
+    const float one = Ar::make(1, 1);
+    const float y = gated ? Ar::out_gated(z, u, one, __uint_as_float(omega)) : z;
+    Y[size_t(i) * NO + n] = u16(Elem<Ff>::narrow(y));
+}
+
+hipError_t launch_ff_pairs_ref(const void* X, const void* g, const void* W, void* Y, int M, int K, int N,
+                               uint32_t omega, int gated, hipStream_t s)
+{
+    dim3 grid(((gated ? N / 2 : N) + 255) / 256, M);
+    ff_pairs_ref_kernel<<<grid, 256, 0, s>>>((const u16*)X, (const u16*)g, (const u16*)W, (u16*)Y, M, K, N, omega, gated);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------------------
 // Probes
 // ---------------------------------------------------------------------------------------------

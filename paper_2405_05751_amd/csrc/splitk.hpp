@@ -42,17 +42,19 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
     constexpr int WSTR = MT * N_TILE / 4;    // float4 stride between the waves' copies in red
     constexpr int kDev = 16;                 // buffer cache policy sc1: device scope, across XCDs
     float asum = 0.f;
+    typedef Arith<T> Ar;                     // fp32 for the floating types; pairs over two fields for Ff
     if (FUSED && tid < MT) {
-        asum = (s_sumsq[tid] + s_sumsq[MT + tid]) + (s_sumsq[2 * MT + tid] + s_sumsq[3 * MT + tid]);
+        asum = Ar::add(Ar::add(s_sumsq[tid], s_sumsq[MT + tid]), Ar::add(s_sumsq[2 * MT + tid], s_sumsq[3 * MT + tid]));
         if (NW == 8)
-            asum += (s_sumsq[4 * MT + tid] + s_sumsq[5 * MT + tid]) + (s_sumsq[6 * MT + tid] + s_sumsq[7 * MT + tid]);
+            asum = Ar::add(asum, Ar::add(Ar::add(s_sumsq[4 * MT + tid], s_sumsq[5 * MT + tid]),
+                                         Ar::add(s_sumsq[6 * MT + tid], s_sumsq[7 * MT + tid])));
     }
 
     // sum of the waves' copies of a quad of the tile, in a fixed order
     auto wg_sum = [&](int m, int c) {
         const float4_t* q = (const float4_t*)(red + m * N_TILE + c);
-        float4_t v = (q[0] + q[WSTR]) + (q[2 * WSTR] + q[3 * WSTR]);
-        if (NW == 8) v += (q[4 * WSTR] + q[5 * WSTR]) + (q[6 * WSTR] + q[7 * WSTR]);
+        float4_t v = Ar::add4(Ar::add4(q[0], q[WSTR]), Ar::add4(q[2 * WSTR], q[3 * WSTR]));
+        if (NW == 8) v = Ar::add4(v, Ar::add4(Ar::add4(q[4 * WSTR], q[5 * WSTR]), Ar::add4(q[6 * WSTR], q[7 * WSTR])));
         return v;
     };
     // tile-local quad (m, c): is it inside the problem, and where are its columns in W
@@ -69,14 +71,14 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
     auto store_y = [&](int m, int c, float4_t v, float4_t u, float ri) {
         float y[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) y[e] = GATED ? silu(v[e] * ri) * (u[e] * ri) : v[e] * ri;
+        for (int e = 0; e < 4; ++e) y[e] = GATED ? Ar::out_gated(v[e], u[e], ri, a.eps) : Ar::out(v[e], ri, a.eps);
         uint2_t o = {Elem<T>::pack(y[0], y[1]), Elem<T>::pack(y[2], y[3])};
         *(uint2_t*)(a.Y + size_t(m) * (GATED ? a.H : a.N) + n0 + c) = o;
     };
     const float4_t kZero4 = {0.f, 0.f, 0.f, 0.f};
 
     if (a.S == 1) {
-        if (tid < MT) s_rinv[tid] = FUSED ? row_scale(asum, a.inv_K, a.eps) : 1.f;
+        if (tid < MT) s_rinv[tid] = FUSED ? Ar::rinv(asum, a.inv_K, a.eps) : Ar::one();
         __syncthreads();
         if (GATED && 2 * a.half == N_TILE) {
             // full-width gated tile: one thread per output quad, so that no thread sits out on an up quad
@@ -180,8 +182,8 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
 #pragma unroll
                 for (int j = 0; j < B; ++j) {
 #pragma unroll
-                    for (int h = 0; h < NQ; ++h) yv[qi][h] += __builtin_bit_cast(float4_t, q[qi][h][j]);
-                    if (FUSED) asq[qi] += u[qi][j];
+                    for (int h = 0; h < NQ; ++h) yv[qi][h] = Ar::add4(yv[qi][h], __builtin_bit_cast(float4_t, q[qi][h][j]));
+                    if (FUSED) asq[qi] = Ar::add(asq[qi], u[qi][j]);
                 }
         }
     };
@@ -201,7 +203,7 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
         const int p = tid + qi * NT;
         const int m = p / (N_TILE / 4), c = (p % (N_TILE / 4)) * 4;
         if (poff[qi][0] != kNowhere)
-            store_y(m, c, yv[qi][0], yv[qi][NQ - 1], FUSED ? row_scale(asq[qi], a.inv_K, a.eps) : 1.f);
+            store_y(m, c, yv[qi][0], yv[qi][NQ - 1], FUSED ? Ar::rinv(asq[qi], a.inv_K, a.eps) : Ar::one());
     }
     trace_stamp(a.trace, a.trace_groups, 7);         // Y stored
     if (tid == 0)                            // ready for the next call on this stream
