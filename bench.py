@@ -98,16 +98,15 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
         Xs.append(X0.clone()); gs.append(g0.clone()); Ws.append(W0.clone()); Ys.append(torch.empty_like(Ys[0]))
 
     rl.rl_set_variant(variant)
-    tuned = None
-    if autotune:
-        rl.rl_autotune(X0, g0, W0, w.eps, Ys[0], gated=gated, reps=20)
-        tuned = rl.rl_autotune_get(w.M, w.K, w.N, tdt, gated)
-
     fused_call = rl.rmsnorm_gated_mlp if gated else rl.rmsnorm_linear
     Wf = Ws                                      # what the fused call reads
     if gated and interleaved:                    # gate and up columns interleaved in groups of 64, repacked once
         fused_call = rl.rmsnorm_gated_mlp_interleaved
         Wf = [rl.rl_interleave_gate_up(W) for W in Ws]
+    tuned = None
+    if autotune:                                 # the library's search over launch shapes, on the rotating copies
+        rl.rl_autotune_rotating(X0, g0, Wf, w.eps, Ys[0], gated=gated, interleaved=gated and interleaved, reps=3 * len(Wf))
+        tuned = rl.rl_autotune_get(w.M, w.K, w.N, tdt, gated, gated and interleaved)
 
     def step(i):
         j = i % copies

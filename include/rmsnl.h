@@ -5,7 +5,10 @@
  * current device) owned by the caller; the library reads or writes them on the given
  * stream and never frees or keeps them.  `stream` is a hipStream_t passed as void*
  * (NULL = the default stream).  Every entry point only enqueues work and returns; it
- * performs no host synchronisation.  Matrices are dense and row-major:
+ * performs no host synchronisation, with two exceptions: the first call on a device that needs
+ * the library's own workspace (and a later one that needs a larger one) allocates it and clears
+ * its counters with a synchronous memset (see rl_set_workspace for how to avoid that), and
+ * rl_autotune waits for its timing events.  Matrices are dense and row-major:
  *
  *     X [M][K]   activations        g [K]      gain
  *     W [K][N]   weight, N fastest  Y [M][N]   output
@@ -223,11 +226,14 @@ rl_status rl_ntrans(const void* X, const void* H, const void* alpha, float eps, 
  * split that stands in for its for-loop dimension), restricted to this library's kernel family;
  * the paper reports that the choice of grid dimensions alone is worth part of its gain.
  *
- * rl_autotune runs every launch shape the library has for the call (variant x columns per
- * workgroup x K slabs, or waves per workgroup for the tile variant) on the caller's own device
+ * rl_autotune runs every launch shape the library has for the call, generated from the shape
+ * (variant x columns per workgroup x every K slab count that leaves each lane group a batch of rows,
+ * launches that come out the same timed once; tile shape x waves per workgroup for the tile
+ * variant; the two-kernel form with and without its K split) on the caller's own device
  * buffers: two warm-up launches, then `reps` (1..1000) timed ones between HIP events on `stream`.
  * The fastest is remembered for (M, K, N, dt, gated) and used by later RL_AUTO calls of exactly
- * that shape; forced variants are not affected.  `gated` != 0 tunes rmsnorm_gated_mlp (N = 2H, Y is
+ * that shape; forced variants are not affected; a tuned shape that finds no room in the workspace
+ * gives way to the built-in one.  `gated` != 0 tunes rmsnorm_gated_mlp (N = 2H, Y is
  * [M][H]), else rmsnorm_linear.  Y is overwritten by every candidate (all compute the same block).
  * This is the one entry point that synchronises with the stream (it waits on its events); it
  * times on the buffers as they are, so a W that fits the 256 MB last-level cache is timed warm.
@@ -238,6 +244,18 @@ rl_status rl_ntrans(const void* X, const void* H, const void* alpha, float eps, 
 rl_status rl_autotune(const void* X, const void* g, const void* W, float eps, void* Y,
                       int64_t M, int64_t K, int64_t N, rl_dtype dt, int gated, int reps,
                       void* stream, float* best_us);
+/*
+ * The same search on cold data: the timed launches rotate through n_copies DEVICE copies of W
+ * (W_copies: host array of n_copies device pointers; enough of them that they exceed the 256 MB
+ * last-level cache, e.g. ceil(512 MiB / bytes of W)), so a small W is timed as it comes from HBM and
+ * not as it lies in the cache (where more, smaller slabs look better than they are).  interleaved != 0
+ * (with gated != 0) tunes rmsnorm_gated_mlp_interleaved on copies of Wi.  The choice is remembered per
+ * (M, K, N, dt, gated, interleaved); rl_autotune_get's `gated` takes 1 for the two-halves layout and 3
+ * for the interleaved one.
+ */
+rl_status rl_autotune_rotating(const void* X, const void* g, const void* const* W_copies, int n_copies, float eps, void* Y,
+                               int64_t M, int64_t K, int64_t N, rl_dtype dt, int gated, int interleaved, int reps,
+                               void* stream, float* best_us);
 rl_status rl_autotune_get(int64_t M, int64_t K, int64_t N, rl_dtype dt, int gated,
                           rl_variant* variant, int* n_tile, int* k_split);
 void rl_autotune_clear(void);

@@ -13,8 +13,8 @@
  *   followed by the matrix product of the computation graph in Fig. 2a:
  *       Z[i][n] = sum_j Yn[i][j] * W[j][n]
  *
- * The fused kernel the paper discovers (Fig. 2b, "reorders MatMul and the
- * division") reaches the same value up to rounding order, so the definition
+ * The fused kernel the paper discovers (Fig. 2b: the division moved behind
+ * the product) reaches the same value up to rounding order, so the definition
  * itself is the reference; the rewrite is NOT used here.
  *
  * Reading taken where the paper is silent: Eq. 1 has no epsilon.  The

@@ -97,6 +97,10 @@ EXPORTS.update({
                                             ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                             ctypes.c_int, ctypes.c_int, ctypes.POINTER(LaunchOpts), ctypes.c_void_p]),
     "rl_last_launch": (ctypes.c_int, [ctypes.POINTER(ctypes.c_int)] * 4),
+    "rl_autotune_rotating": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
+                                            ctypes.c_float, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                            ctypes.POINTER(ctypes.c_float)]),
     "rl_ff_pairs": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
                                    ctypes.c_int64, ctypes.c_int64, ctypes.c_uint32, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                    ctypes.c_void_p]),
@@ -337,11 +341,26 @@ def rl_autotune(X: torch.Tensor, g: torch.Tensor, W: torch.Tensor, eps: float, Y
     return float(best.value)
 
 
-def rl_autotune_get(M: int, K: int, N: int, dtype: torch.dtype, gated: bool = False):
+def rl_autotune_rotating(X: torch.Tensor, g: torch.Tensor, Ws, eps: float, Y: torch.Tensor, gated: bool = False,
+                         interleaved: bool = False, reps: int = 20, stream=None) -> float:
+    """rl_autotune on cold data: Ws is a list of device copies of W (of Wi when interleaved) to rotate through."""
+    M, K = X.shape
+    K2, N = Ws[0].shape
+    if K2 != K or g.shape != (K,) or Y.shape != (M, N // 2 if gated else N) or any(w.shape != Ws[0].shape for w in Ws):
+        raise ValueError("shape mismatch")
+    ptrs = (ctypes.c_void_p * len(Ws))(*[_dev(w, "W copy") for w in Ws])
+    best = ctypes.c_float(0.0)
+    _check(lib().rl_autotune_rotating(_dev(X, "X"), _dev(g, "g"), ptrs, len(Ws), float(eps), _dev(Y, "Y"), M, K, N,
+                                      _DTYPES[X.dtype], int(bool(gated)), int(bool(interleaved)), int(reps),
+                                      _stream(stream), ctypes.byref(best)))
+    return float(best.value)
+
+
+def rl_autotune_get(M: int, K: int, N: int, dtype: torch.dtype, gated: bool = False, interleaved: bool = False):
     """(variant name, n_tile, k_split) remembered for the shape; variant "auto" if none."""
     v, nt, ks = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
-    _check(lib().rl_autotune_get(M, K, N, _DTYPES[dtype], int(bool(gated)), ctypes.byref(v), ctypes.byref(nt),
-                                 ctypes.byref(ks)))
+    _check(lib().rl_autotune_get(M, K, N, _DTYPES[dtype], int(bool(gated)) | (2 if interleaved else 0), ctypes.byref(v),
+                                 ctypes.byref(nt), ctypes.byref(ks)))
     return VARIANT_NAMES[v.value], nt.value, ks.value
 
 

@@ -239,8 +239,8 @@ rl_status run(Problem& p, void* stream, const Workspace* fixed = nullptr, const 
         p.trace = g_trace;
         p.trace_groups = g_trace_groups;
         if (forced == RL_AUTO) {
-            auto it = g_tuned.find(TuneKey(p.M, p.K, p.N, int(p.dt), p.gated));
-            if (it != g_tuned.end() && p.fused && !p.gate_group) tuned = it->second;   // (tuned on the two-halves layout)
+            auto it = g_tuned.find(TuneKey(p.M, p.K, p.N, int(p.dt), p.gated | (p.gate_group ? 2 : 0)));
+            if (it != g_tuned.end() && p.fused) tuned = it->second;
         }
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -272,8 +272,10 @@ rl_status run(Problem& p, void* stream, const Workspace* fixed = nullptr, const 
         rl_status ws_status;
         hipError_t e = launch_variant(v, p, s, &why, &ws_status, fixed);
         if (ws_status != RL_OK) {
-            // the two-kernel form is an optimisation: without room for it the fused kernel runs
-            if (forced == RL_AUTO && v == RL_MFMA_TILE_PRE && ws_status == RL_ERR_WORKSPACE) continue;
+            // the two-kernel form is an optimisation: without room for it the fused kernel runs; a
+            // tuned launch shape likewise gives way to the built-in one
+            if (forced == RL_AUTO && ws_status == RL_ERR_WORKSPACE &&
+                (v == RL_MFMA_TILE_PRE || (i == 0 && tuned.variant != RL_AUTO))) continue;
             return ws_status;
         }
         if (e == hipSuccess) { tl_last_variant = v; return RL_OK; }
@@ -479,31 +481,42 @@ rl_status rmsnorm(const void* X, const void* g, float eps, void* Xn, int64_t M, 
     return RL_OK;
 }
 
-rl_status rl_autotune(const void* X, const void* g, const void* W, float eps, void* Y,
-                      int64_t M, int64_t K, int64_t N, rl_dtype dt, int gated, int reps,
-                      void* stream, float* best_us)
+// The tuner's core: every launch shape the library has for the call, timed on `stream` while the
+// launches rotate through n_w copies of W (one copy: W is timed as it lies in the caches).
+static rl_status autotune_core(const void* X, const void* g, const void* const* Ws, int n_w, float eps, void* Y,
+                               int64_t M, int64_t K, int64_t N, rl_dtype dt, int gated, int interleaved, int reps,
+                               void* stream, float* best_us)
 {
-    if (!X || !g || !W || !Y) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    if (!X || !g || !Ws || !Y || n_w < 1) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    for (int i = 0; i < n_w; ++i)
+        if (!Ws[i] || !aligned16(Ws[i])) return fail(RL_ERR_INVALID_ARG, "every copy of W must be a 16-byte aligned device pointer");
     if (rl_status st = check_dims(M, K, N, dt)) return st;
     if (gated && (N % 2)) return fail(RL_ERR_INVALID_ARG, "the gated block needs an even N (= 2H)");
+    if (interleaved && (!gated || (N / 2) % 64)) return fail(RL_ERR_INVALID_ARG, "the interleaved layout is the gated block's, H % 64 == 0");
     if (reps < 1 || reps > 1000) return fail(RL_ERR_INVALID_ARG, "reps must be in [1, 1000]");
     if (!std::isfinite(eps) || eps < 0.f) return fail(RL_ERR_INVALID_ARG, "eps must be finite and >= 0");
-    if (!aligned16(X) || !aligned16(g) || !aligned16(W) || !aligned16(Y))
+    if (!aligned16(X) || !aligned16(g) || !aligned16(Y))
         return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
     Problem base{};
-    base.X = X; base.g = g; base.W = W; base.Y = Y;
+    base.X = X; base.g = g; base.W = Ws[0]; base.Y = Y;
     base.M = int(M); base.K = int(K); base.N = int(N);
-    base.eps = eps; base.fused = 1; base.gated = gated ? 1 : 0; base.dt = DType(dt);
+    base.eps = eps; base.fused = 1; base.gated = gated ? 1 : 0; base.gate_group = interleaved ? 64 : 0; base.dt = DType(dt);
 
-    // the launch shapes worth trying: (variant, n_tile, k_split); 0 = that kernel's own default
+    // The launch shapes worth trying, generated from the shape: (variant, n_tile, k_split); 0 = that
+    // kernel's own default.  GEMV and skinny: every slab count that keeps at least one batch (run) of
+    // rows per lane group (wave), at each column width; slab counts that round to the same slabs are
+    // launched once.
     struct Cand { rl_variant v; int n_tile, k_split; };
     std::vector<Cand> cands;
     if (dt != RL_F32) {
         if (M <= 16)
-            for (int nt : {128, 256, 512})
-                for (int ks : {0, 4, 8, 16, 32}) cands.push_back({RL_GEMV_SPLITK, nt, ks});
+            for (int nt : {128, 256, 512}) {
+                cands.push_back({RL_GEMV_SPLITK, nt, 0});
+                for (int ks = 1; ks <= 32; ++ks) cands.push_back({RL_GEMV_SPLITK, nt, ks});
+            }
         if (M <= 1024)
-            for (int ks = 1; ks <= 16; ++ks) cands.push_back({RL_MFMA_SKINNY, 0, ks});
+            for (int nt : {0, 64})
+                for (int ks = 1; ks <= 16; ++ks) cands.push_back({RL_MFMA_SKINNY, nt, ks});
         if (M > 16)
             for (int shape : {256, 512})
                 for (int nw : {4, 8}) cands.push_back({RL_MFMA_TILE, shape, nw});
@@ -523,18 +536,28 @@ rl_status rl_autotune(const void* X, const void* g, const void* W, float eps, vo
     Tuned best{RL_AUTO, 0, 0};
     float best_ms = 0.f;
     rl_status result = RL_OK;
+    std::vector<std::tuple<int, int, int, int>> seen;           // (variant, columns, slabs, workgroups) already timed
+    int plan[3];
     for (const Cand& c : cands) {
         if (c.v == RL_NAIVE && best.variant != RL_AUTO) break;      // the fallback only if nothing else runs
         Problem p = base;
         p.n_tile = c.n_tile; p.k_split = c.k_split;
+        p.plan = plan;
         const char* why = nullptr;
         rl_status ws_status;
         bool ok = true;
         for (int i = 0; i < 2 + reps && ok; ++i) {
             if (i == 2) he = hipEventRecord(e0, s);
+            p.W = Ws[i % n_w];
+            plan[0] = plan[1] = plan[2] = 0;
             hipError_t le = launch_variant(c.v, p, s, &why, &ws_status);
             if (ws_status != RL_OK || le == hipErrorInvalidValue) { (void)hipGetLastError(); ok = false; break; }
             if (le != hipSuccess) { result = fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(le)); ok = false; }
+            if (i == 0) {                                           // the same launch as an earlier candidate: once is enough
+                const auto key = std::make_tuple(int(c.v), plan[0], plan[1], plan[2]);
+                if (plan[2] != 0 && std::find(seen.begin(), seen.end(), key) != seen.end()) { ok = false; break; }
+                seen.push_back(key);
+            }
         }
         if (result != RL_OK) break;
         if (!ok) continue;
@@ -551,10 +574,26 @@ rl_status rl_autotune(const void* X, const void* g, const void* W, float eps, vo
     if (best.variant == RL_AUTO) return fail(RL_ERR_UNSUPPORTED, "no variant runs this shape");
     {
         std::lock_guard<std::mutex> lk(g_mu);
-        g_tuned[TuneKey(base.M, base.K, base.N, int(base.dt), base.gated)] = best;
+        g_tuned[TuneKey(base.M, base.K, base.N, int(base.dt), base.gated | (base.gate_group ? 2 : 0))] = best;
     }
     if (best_us) *best_us = best_ms * 1000.f / float(reps);
     return RL_OK;
+}
+
+rl_status rl_autotune(const void* X, const void* g, const void* W, float eps, void* Y,
+                      int64_t M, int64_t K, int64_t N, rl_dtype dt, int gated, int reps,
+                      void* stream, float* best_us)
+{
+    if (!W) return fail(RL_ERR_INVALID_ARG, "null pointer");
+    return autotune_core(X, g, &W, 1, eps, Y, M, K, N, dt, gated, 0, reps, stream, best_us);
+}
+
+rl_status rl_autotune_rotating(const void* X, const void* g, const void* const* W_copies, int n_copies, float eps, void* Y,
+                               int64_t M, int64_t K, int64_t N, rl_dtype dt, int gated, int interleaved, int reps,
+                               void* stream, float* best_us)
+{
+    if (n_copies < 1 || n_copies > 4096) return fail(RL_ERR_INVALID_ARG, "n_copies must be in [1, 4096]");
+    return autotune_core(X, g, W_copies, n_copies, eps, Y, M, K, N, dt, gated, interleaved, reps, stream, best_us);
 }
 
 rl_status rl_autotune_get(int64_t M, int64_t K, int64_t N, rl_dtype dt, int gated,
@@ -563,7 +602,7 @@ rl_status rl_autotune_get(int64_t M, int64_t K, int64_t N, rl_dtype dt, int gate
     if (!variant || !n_tile || !k_split) return fail(RL_ERR_INVALID_ARG, "null pointer");
     if (rl_status st = check_dims(M, K, N, dt)) return st;
     std::lock_guard<std::mutex> lk(g_mu);
-    auto it = g_tuned.find(TuneKey(int(M), int(K), int(N), int(dt), gated ? 1 : 0));
+    auto it = g_tuned.find(TuneKey(int(M), int(K), int(N), int(dt), gated & 3));     // bit 1: the interleaved layout
     if (it == g_tuned.end()) { *variant = RL_AUTO; *n_tile = 0; *k_split = 0; return RL_OK; }
     *variant = it->second.variant; *n_tile = it->second.n_tile; *k_split = it->second.k_split;
     return RL_OK;
@@ -747,20 +786,36 @@ size_t rl_workspace_bytes(int64_t M, int64_t K, int64_t N, rl_dtype dt)
     Problem p{};
     p.M = int(M); p.K = int(K); p.N = int(N); p.dt = DType(dt); p.fused = 1;
     rl_variant v;
+    Tuned tuned{RL_AUTO, 0, 0};
     {
         std::lock_guard<std::mutex> lk(g_mu);
         read_env_locked();
         v = g_variant;
         if (v != RL_AUTO) { p.n_tile = g_n_tile; p.k_split = g_k_split; }
+        else {
+            auto it = g_tuned.find(TuneKey(p.M, p.K, p.N, int(p.dt), 0));
+            if (it != g_tuned.end()) tuned = it->second;
+        }
     }
+    auto need_of = [](rl_variant var, const Problem& q) -> size_t {
+        if (var == RL_GEMV_SPLITK) return gemv_workspace_bytes(q);
+        if (var == RL_MFMA_SKINNY) return skinny_workspace_bytes(q);
+        if (var == RL_MFMA_TILE_PRE) return tile_pre_workspace_bytes(q);
+        return 0;
+    };
+    size_t need = 0;
     if (v == RL_AUTO) {
         v = choose_auto(p);
         if (v == RL_MFMA_TILE && prefers_two_kernels(p)) v = RL_MFMA_TILE_PRE;   // optional: without it the fused kernel runs
+        need = need_of(v, p);
+        if (tuned.variant != RL_AUTO) {        // a shape found by rl_autotune runs first: room for whichever needs more
+            Problem q = p;
+            q.n_tile = tuned.n_tile; q.k_split = tuned.k_split;
+            need = std::max(need, need_of(tuned.variant, q));
+        }
+    } else {
+        need = need_of(v, p);
     }
-    size_t need = 0;
-    if (v == RL_GEMV_SPLITK) need = gemv_workspace_bytes(p);
-    else if (v == RL_MFMA_SKINNY) need = skinny_workspace_bytes(p);
-    else if (v == RL_MFMA_TILE_PRE) need = tile_pre_workspace_bytes(p);
     return need ? need + kHeadBytes : 0;
 }
 

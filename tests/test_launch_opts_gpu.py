@@ -201,3 +201,40 @@ def test_read_probes_run_and_reject(rl):
     assert L.rl_probe_read_strips(src.data_ptr(), 1 << 20, 8192, 1, sink.data_ptr(), None) == 1   # beyond 2^31 bytes
     assert L.rl_probe_read_flat(src.data_ptr(), 24, 1, sink.data_ptr(), None) == 1
     assert L.rl_probe_read_flat(src.data_ptr(), 1024, 0, sink.data_ptr(), None) == 1
+
+
+def test_autotune_on_rotating_copies_and_the_interleaved_layout(rl):
+    """rl_autotune_rotating: the search runs on copies of W in rotation, remembers its pick per layout,
+    RL_AUTO then launches exactly that shape, and the result is still the block."""
+    import torch
+    w = workloads.make(16, 1024, 2 * 640, "bf16", 1e-5, 9950)
+    X, g, W = upload(w)
+    Ws = [W] + [W.clone() for _ in range(3)]
+    Wis = [rl.rl_interleave_gate_up(v) for v in Ws]
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+    rl.rl_autotune_clear()
+    try:
+        Y = torch.empty((w.M, w.N), dtype=torch.bfloat16, device="cuda")
+        us = rl.rl_autotune_rotating(X, g, Ws, w.eps, Y, reps=8)
+        assert 1.0 < us < 1000.0
+        v, nt, ks = rl.rl_autotune_get(w.M, w.K, w.N, torch.bfloat16)
+        assert v in ("gemv", "skinny", "tile")
+        assert rl.rl_autotune_get(w.M, w.K, w.N, torch.bfloat16, gated=True) == ("auto", 0, 0)     # other layouts untouched
+        Y = rl.rmsnorm_linear(X, g, W, w.eps)
+        torch.cuda.synchronize()
+        used, cols, slabs, _ = rl.rl_last_launch()
+        assert used == v and (nt == 0 or cols == nt) and (ks == 0 or slabs == ks)
+        compare(to_host_f64(Y, w.dtype), Z, w.dtype, "tuned plain block")
+        Yg = torch.empty((w.M, w.N // 2), dtype=torch.bfloat16, device="cuda")
+        rl.rl_autotune_rotating(X, g, Wis, w.eps, Yg, gated=True, interleaved=True, reps=8)
+        vi, nti, ksi = rl.rl_autotune_get(w.M, w.K, w.N, torch.bfloat16, gated=True, interleaved=True)
+        assert vi in ("gemv", "skinny", "tile")
+        assert rl.rl_autotune_get(w.M, w.K, w.N, torch.bfloat16, gated=True) == ("auto", 0, 0)
+        Yi = rl.rmsnorm_gated_mlp_interleaved(X, g, Wis[0], w.eps)
+        torch.cuda.synchronize()
+        assert rl.rl_last_launch()[0] == vi
+        compare_gated(to_host_f64(Yi, w.dtype), Z, w.dtype, "tuned interleaved gated block")
+    finally:
+        rl.rl_autotune_clear()
+    with pytest.raises(rl.RmsnlError):
+        rl.rl_autotune_rotating(X, g, Ws, w.eps, Y, interleaved=True, reps=4)        # interleaved is the gated block's

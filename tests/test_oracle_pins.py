@@ -179,7 +179,7 @@ def test_not_symmetric_in_operands():
 
 # ---------------------------------------------------------------- the paper's rewrite is an identity
 def test_reordered_division_identity():
-    """B = (X*g) @ W, A = sum x^2 (case study, 'reorders MatMul and the division'): Z = B / sqrt(A/K + eps)."""
+    """B = (X*g) @ W, A = sum x^2 (case study: the form with the division moved behind the product): Z = B / sqrt(A/K + eps)."""
     for dtype, seed in (("f16", 21), ("bf16", 22), ("f32", 23)):
         w = workloads.make(9, 200, 33, dtype, 1e-5, seed, outlier_frac=0.2)
         Z = oracle.rmsnorm_linear(w.X, w.g, w.W, dtype, w.eps)
