@@ -44,6 +44,9 @@ struct SkinnyArgs {
 #ifndef RL_SKINNY_TWO_PART
 #define RL_SKINNY_TWO_PART 1
 #endif
+#ifndef RL_SKINNY_TWO_MAX_MB
+#define RL_SKINNY_TWO_MAX_MB 2
+#endif
 constexpr int kSkinnyTile = 128;     // most columns per workgroup (16 lanes x 8)
 constexpr int kSkAux = 2;            // W loads: nt
 constexpr int kSkOut = 0x7ffffff0;
@@ -220,7 +223,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(
     // carries no rounding of X-hat at all, only the final one of Y.  From 33 rows on the second
     // instruction is not free any more (64 x 4096 x 28672: +5 %; several row blocks: +20 %), and
     // X-hat is rounded once, as the tile kernels round it.
-    constexpr bool TWO = FUSED && RL_SKINNY_TWO_PART && MB <= 2;
+    constexpr bool TWO = FUSED && RL_SKINNY_TWO_PART && MB <= RL_SKINNY_TWO_MAX_MB;
     auto consume = [&](int d, int h) {
         // A operands: X-hat = X (.) g in the storage type (see above); squares of the raw X
         uint4_t aop[MB], alo[TWO ? MB : 1], gq;
@@ -251,9 +254,10 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(
                 bop[t] = __builtin_amdgcn_perm(w[d][2 * t + 1][c >> 1], w[d][2 * t][c >> 1],
                                                (c & 1) ? 0x07060302u : 0x05040100u);
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                acc[mb][c] = Mfma16<T>::run(aop[mb], bop, acc[mb][c]);
-                if (TWO) acc[mb][c] = Mfma16<T>::run(alo[mb], bop, acc[mb][c]);
+            for (int mb = 0; mb < MB; ++mb) acc[mb][c] = Mfma16<T>::run(aop[mb], bop, acc[mb][c]);
+            if (TWO) {                       // (after all the first parts: no instruction waits for the one before it)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) acc[mb][c] = Mfma16<T>::run(alo[mb], bop, acc[mb][c]);
             }
         }
     };
