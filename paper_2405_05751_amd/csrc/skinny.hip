@@ -44,6 +44,9 @@ struct SkinnyArgs {
 #ifndef RL_SKINNY_TWO_PART
 #define RL_SKINNY_TWO_PART 1
 #endif
+#ifndef RL_SKINNY_X_LDS
+#define RL_SKINNY_X_LDS 1
+#endif
 #ifndef RL_SKINNY_TWO_MAX_MB
 #define RL_SKINNY_TWO_MAX_MB 2
 #endif
@@ -164,9 +167,29 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(
     const int st_w1 = r8 * 128 + ((c8 ^ (r8 >> 1) ^ 4) << 4);        // odd j
     const int st_r0 = i * 128 + (((2 * q) ^ (i >> 1)) << 4);         // step 0 (+ 2048 mb); step 1 is ^ 16
     const int st_g = MT * 128;
+    // XLDS: the lines of X (and g) go straight from memory into that corner of LDS (direct loads; data
+    // that lands in LDS does not queue for the register file, and a line from L2 arrives at 99
+    // instead of 68 GB/s per compute unit).  A direct load writes lane l's 16 bytes at byte 16 l of its
+    // KiB, so lane l = (r8, c8) of load j fetches the chunk that belongs in slot c8 of row 8j + r8:
+    // chunk c8 ^ ((row / 2) % 8).  Two stage buffers, one per parity of the run; the wait for a run
+    // is placed by hand (the 16 loads of W of the run before it were issued after it).
+    constexpr bool XLDS = RL_SKINNY_X_LDS != 0;
+    constexpr int STG = MT * 128 + 1024;     // a run of X, and the KiB that g's load writes (128 bytes of it used)
+    static_assert(2 * STG <= MT * N_TILE * 4, "two stage buffers fit the wave's part of the reduction buffer");
+    const uint32_t stage_lds = __builtin_amdgcn_readfirstlane(uint32_t(uintptr_t(stage)));
+    const uint4_t xdesc = {uint32_t(uintptr_t(Xb)), uint32_t(uintptr_t(Xb) >> 32), uint32_t(Mh * a.K * 2), uint32_t(kSkFlags)};
+    const uint4_t gdesc = {uint32_t(uintptr_t(FUSED ? a.g : a.X)), uint32_t(uintptr_t(FUSED ? a.g : a.X) >> 32),
+                           uint32_t(a.K * 2), uint32_t(kSkFlags)};
+    auto load_lds = [&](const uint4_t& rsrc, uint32_t dst, int v) {
+        const uint4_t desc = rsrc;
+        uint32_t keep;                       // M0 carries the LDS address; whatever it held is put back
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                     "buffer_load_dwordx4 %2, %3, 0 offen lds\n\ts_mov_b32 m0, %0"
+                     : "=&s"(keep) : "s"(dst), "v"(v), "s"(desc) : "memory");
+    };
 
     uint4_t w[D][8];                         // D steps of W in flight
-    uint4_t xr[2 * MB], gr;                  // the next run of X (and g), as lines
+    uint4_t xr[XLDS ? 1 : 2 * MB], gr;       // register mode: the next run of X (and g), as lines
     // Load j of a run takes row 8j + r8 of X.  Where there is no such row (8 j >= rlim) it takes the
     // last row again: the repeated line costs nothing, nothing computed from those rows is ever
     // stored, and no instruction has part of its lanes out of range (measured the same as reading
@@ -175,6 +198,20 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(
     const int xlane = r8 * a.K * 2;          // used only where r8 < M
     const int xlast = (Mh - 1) * a.K * 2;
     auto issue_x = [&](int t) {
+        if constexpr (XLDS) {
+            const uint32_t sb = stage_lds + uint32_t(t & 1) * STG;
+            const int krun = (NW * t + wave) * 64;                  // slab-relative k of the run
+            if (FUSED) {
+                const int kr = krun + c8 * 8;
+                load_lds(gdesc, sb + st_g, (r8 == 0 && kr < klen) ? (k0 + kr) * 2 : kSkOut);
+            }
+#pragma unroll
+            for (int j = 0; j < 2 * MB; ++j) {
+                const int kr = krun + ((c8 ^ (r8 >> 1) ^ (4 * (j & 1))) << 3);   // the chunk that belongs in this lane's slot
+                load_lds(xdesc, sb + 1024 * j,
+                         kr < klen ? (k0 + kr) * 2 + (8 * j < rlim ? xlane + 8 * j * a.K * 2 : xlast) : kSkOut);
+            }
+        } else {
         const int kr = (NW * t + wave) * 64 + c8 * 8;               // slab-relative k of this lane's chunk
         const int koff = (k0 + kr) * 2;
         const bool kin = kr < klen;
@@ -183,6 +220,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(
         for (int j = 0; j < 2 * MB; ++j)
             xr[j] = __builtin_amdgcn_raw_buffer_load_b128(
                 xrs, kin ? koff + (8 * j < rlim ? xlane + 8 * j * a.K * 2 : xlast) : kSkOut, 0, 0);
+        }
     };
     auto issue_w = [&](int s, int d) {
         const int t = s >> 1, h = s & 1;
@@ -224,7 +262,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(
     // instruction is not free any more (64 x 4096 x 28672: +5 %; several row blocks: +20 %), and
     // X-hat is rounded once, as the tile kernels round it.
     constexpr bool TWO = FUSED && RL_SKINNY_TWO_PART && MB <= RL_SKINNY_TWO_MAX_MB;
-    auto consume = [&](int d, int h) {
+    auto consume = [&](int d, int h, const char* stage) {     // stage: the buffer that holds this run of X
         // A operands: X-hat = X (.) g in the storage type (see above); squares of the raw X
         uint4_t aop[MB], alo[TWO ? MB : 1], gq;
         if (FUSED) gq = *reinterpret_cast<const uint4_t*>(stage + st_g + ((2 * q + h) << 4));
@@ -268,12 +306,17 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(
         for (int p = 0; p < PU; ++p) {
             const int t = t0 + p;
             const bool there = t < nPairs;   // uniform over the workgroup; only the arithmetic is skipped
-            if (there) {
+            const char* stg = stage + (XLDS ? (t & 1) * STG : 0);
+            if (XLDS) {
+                // this run's X was asked for a run ago; the 16 loads of W issued since are younger
+                __builtin_amdgcn_s_waitcnt((16 & 15) | ((16 >> 4) << 14) | (7 << 4) | (15 << 8));
+                asm volatile("" ::: "memory");
+            } else if (there) {
                 // the wave's LDS operations execute in order: these writes land after the previous
                 // run's reads and before the reads below
 #pragma unroll
                 for (int j = 0; j < 2 * MB; ++j)
-                    *reinterpret_cast<uint4_t*>(stage + ((j & 1) ? st_w1 : st_w0) + 1024 * j) = xr[j];
+                    *reinterpret_cast<uint4_t*>(stage + ((j & 1) ? st_w1 : st_w0) + 1024 * j) = xr[XLDS ? 0 : j];
                 if (FUSED && r8 == 0) *reinterpret_cast<uint4_t*>(stage + st_g + (c8 << 4)) = gr;
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
@@ -285,7 +328,7 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                if (there) consume((2 * p + h) % D, h);
+                if (there) consume((2 * p + h) % D, h, stg);
                 __builtin_amdgcn_sched_barrier(0);
                 issue_w(2 * t + h + D, (2 * p + h) % D);
                 asm volatile("" ::: "memory");
@@ -294,6 +337,12 @@ __global__ __launch_bounds__(64 * skinny_waves(MB)) void skinny_kernel(
         }
     }
     trace_stamp(a.trace, a.trace_groups, 2);
+    if (XLDS) {
+        // the loads issued for the run past the end still write (zeros) into this wave's stage buffers,
+        // which the reduction buffer below lies over: nothing may be in flight any more
+        __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
+        asm volatile("" ::: "memory");
+    }
 
     // ---- A_i: add the four k groups of the wave (lanes i, i+16, i+32, i+48 hold row i's shares)
     if (FUSED) {
