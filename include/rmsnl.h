@@ -43,14 +43,20 @@ typedef enum {
 typedef enum { RL_F16 = 0, RL_BF16 = 1, RL_F32 = 2 } rl_dtype;
 
 typedef enum {
-    RL_AUTO = 0,          /* pick by shape: GEMV for M = 1 and N < 10240, and for M <= 4 while K N <= 6e6; M <= 64 skinny, and up to M = 1024 while
-                             ceil(M / 64) K N <= 1.4e8 (0.9e8 for N > 6144 and M > 128); else the two-kernel tile form, or the fused tile kernel
-                             when the workspace has no room for it */
-    RL_GEMV_SPLITK = 1,   /* M <= 16, no matrix cores, K split over workgroups */
-    RL_MFMA_SKINNY = 2,   /* matrix cores, 64 rows per workgroup (M <= 1024: a row block per 64 rows in the same
-                             launch), K split over the waves of a workgroup and over workgroups */
-    RL_MFMA_TILE = 3,     /* large M: 256x256 output tiles on matrix cores, one fused kernel */
-    RL_NAIVE = 4,         /* any shape and type, fp32 arithmetic, slow */
+    RL_AUTO = 0,          /* pick by shape: fp32, or K or N not a multiple of 8 (gated: N not of 16): the plain kernel.  Else GEMV
+                             for M = 1 and N < 10240, and for M <= 4 while K N <= 6e6; M <= 64 skinny, and up to M = 1024 while
+                             ceil(M / 64) K N <= 1.4e8 (0.9e8 for N > 6144 and M > 128); else the two-kernel tile form, or the
+                             fused tile kernel when the workspace has no room for it.  A shape remembered by rl_autotune is
+                             tried first */
+    RL_GEMV_SPLITK = 1,   /* M <= 16, 16-bit types, no matrix cores: 64 to 512 columns of W per workgroup, K split into slabs over
+                             workgroups; up to 4 rows W goes through LDS by direct loads, above that through registers */
+    RL_MFMA_SKINNY = 2,   /* 16-bit types, matrix cores, 64 rows per workgroup (M <= 1024: a row block per 64 rows in the same
+                             launch), K split over the waves of a workgroup and into 1 to 16 slabs over workgroups; 128
+                             columns of W per workgroup, 64 when that leaves half the chip idle */
+    RL_MFMA_TILE = 3,     /* 16-bit types, large M: 256x256 (or 128x512) output tiles on matrix cores, one fused kernel; K < 2^22,
+                             N < 2^25; a W of 2 GiB or more is addressed row by row */
+    RL_NAIVE = 4,         /* any shape and type, slow (no matrix cores, no split over workgroups): fp32 arithmetic for the
+                             16-bit types, fp64 accumulation for fp32 */
     RL_MFMA_TILE_PRE = 5  /* M > 64: X (.) g and 1/rms written once by a first kernel (workspace of 2 M K + 4 M bytes),
                              then the tile kernel as a product scaled per row; with few 256x256 tiles the product is
                              split over K into fp32 partials (up to 64 MiB more) that a third kernel adds up */
@@ -176,7 +182,7 @@ rl_status silu_mul(const void* Z, void* Y, int64_t M, int64_t H, rl_dtype dt, vo
  * A workgroup that owns a run of outputs then reads one contiguous run of columns per row of W, as
  * in the plain block, instead of two runs half as long that lie H columns apart.  The result is the
  * one rmsnorm_gated_mlp gives on the two-halves W (same kernels, only the column a lane fetches
- * differs).  Not covered by rl_autotune.  rl_interleave_gate_up writes Wi from W = [gate | up] (both
+ * differs).  Tuned by rl_autotune_rotating with interleaved != 0, not by rl_autotune.  rl_interleave_gate_up writes Wi from W = [gate | up] (both
  * [K][2H] DEVICE arrays of type dt, 16-byte aligned, not the same buffer), on `stream`.
  */
 rl_status rmsnorm_gated_mlp_interleaved(const void* X, const void* g, const void* Wi, float eps, void* Y,
