@@ -405,7 +405,8 @@ def main():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="decode",
-                    help="decode, tiny, qkv, gateup, prefill, ntrans, qknorm (batch 8; qknorm1, qknorm16), "
+                    help="decode, tiny, qkv, gateup, prefill, ntrans, qknorm (batch 8; qknorm1, qknorm16; a head "
+                         "size other than 128 as qknorm:64 or qknorm1:256), "
                          "or MxKxN (a bf16 workload of that shape)")
     ap.add_argument("--variant", default="auto")
     ap.add_argument("--no-graph", action="store_true", help="enqueue the timed steps one by one")
@@ -457,9 +458,10 @@ def main():
         print(json.dumps(run_ntrans(rl, torch, args.steps if args.steps is not None else 100, args.warmup,
                                     with_cpu=not args.no_cpu)))
         return
-    if name in ("qknorm", "qknorm1", "qknorm16"):
-        B = {"qknorm": 8, "qknorm1": 1, "qknorm16": 16}[name]
-        print(json.dumps(run_qknorm(rl, torch, args.steps if args.steps is not None else 100, args.warmup, B=B,
+    if name.split(":")[0] in ("qknorm", "qknorm1", "qknorm16"):
+        B = {"qknorm": 8, "qknorm1": 1, "qknorm16": 16}[name.split(":")[0]]
+        D = int(name.split(":")[1]) if ":" in name else 128
+        print(json.dumps(run_qknorm(rl, torch, args.steps if args.steps is not None else 100, args.warmup, B=B, D=D,
                                     with_cpu=not args.no_cpu)))
         return
     steps = args.steps if args.steps is not None else (20 if name == "prefill" else 200)

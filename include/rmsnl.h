@@ -277,9 +277,9 @@ void rl_autotune_clear(void);
  *     O = sum_t softmax(s)_t v_t
  *
  * The paper names the operation but not its constants: the usual layer normalisation, the usual
- * 1/sqrt(D), eps as given.  Fast path: D = 128 and a 16-bit type (keys read once, their mean, variance
- * and dot product from the same registers, online softmax, the sequence split over workgroups); any
- * other D (<= 4096) or type runs a slow plain kernel.  May use the library workspace like
+ * 1/sqrt(D), eps as given.  Fast path: D = 64, 128 or 256 and a 16-bit type (keys read once, their mean,
+ * variance and dot product from the same registers, online softmax, the sequence split over workgroups); any
+ * other D (<= 4096) or type, and S D >= 2^30, runs a slow plain kernel.  May use the library workspace like
  * rmsnorm_linear.  Pointers 16-byte aligned; O must not overlap the inputs.
  */
 rl_status rl_qknorm_attention(const void* Q, const void* K, const void* V, const void* gq, const void* bq,

@@ -10,10 +10,10 @@
 // so a key is read once, raw, and its mean, variance and dot product with qn (.) gk come out of the
 // same registers.  The kernel is bound by streaming K and V once.
 //
-// Fast path (D = 128, 16-bit types): 16 lanes share a key (8 elements each; a wave-wide load is four
-// consecutive keys, 1 KiB contiguous), the three sums over D are rotations inside a 16-lane row
-// (DPP, no LDS), every group of 16 lanes keeps its own running maximum, denominator and 8 output
-// sums (online softmax), and the groups, the waves and
+// Fast path (D = 64, 128 or 256, 16-bit types): D / 8 lanes share a key (8 elements each; a wave-wide
+// load is 8, 4 or 2 consecutive keys, 1 KiB contiguous), the three sums over D are exchanges inside
+// that lane group (DPP and, for D = 256, a swap of 16-lane rows: no LDS), every group keeps its own running
+// maximum, denominator and 8 output sums (online softmax), and the groups, the waves and
 // the splits of the sequence (by the last of them to arrive, through the workspace) are merged at
 // the end.  Any other D or type: a slow plain kernel.
 #include <algorithm>
@@ -21,7 +21,6 @@
 
 namespace rmsnl {
 
-constexpr int kQkD = 128;
 constexpr int kQkOut = 0x7ffffff0;
 constexpr int kQkFlags = 0x00020000;
 constexpr int kQkRing = 6;           // iterations (one K and one V load per lane each) in flight
@@ -35,18 +34,34 @@ struct QkArgs {
     unsigned* counter;               // one arrival counter per (sample, head), zero between calls; or null:
                                      // then a second kernel merges the splits
     float eps, scale_log2e;          // scores are kept in units of log2: s * log2(e) / sqrt(D)
-    int S, SP, chunk;                // positions, splits, positions per split (a multiple of 16)
+    int S, SP, chunk;                // positions, splits, positions per split (a multiple of 32)
 };
 
-// sum over the 16 lanes of a row, in every lane of the row
-__device__ __forceinline__ float row_sum16(float v)
+// sum over a group of LPK = 8, 16 or 32 consecutive lanes (aligned to LPK), in every lane of the group
+template <int LPK>
+__device__ __forceinline__ float group_sum(float v)
 {
-#define RL_ROR(n) __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + (n), 0xf, 0xf, false))
-    v += RL_ROR(8);
-    v += RL_ROR(4);
-    v += RL_ROR(2);
-    v += RL_ROR(1);
-#undef RL_ROR
+#define RL_DPP(ctrl) __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), (ctrl), 0xf, 0xf, false))
+    if constexpr (LPK == 8) {
+        v += RL_DPP(0xB1);                   // lanes 1 0 3 2 of each four
+        v += RL_DPP(0x4E);                   // lanes 2 3 0 1 of each four: the four now agree
+        v += RL_DPP(0x141);                  // lane 7 - i of each eight: the other four's sum
+    } else {
+        v += RL_DPP(0x128);                  // rotations inside a row of 16 lanes
+        v += RL_DPP(0x124);
+        v += RL_DPP(0x122);
+        v += RL_DPP(0x121);
+        if constexpr (LPK == 32) {
+            // v_permlane16_swap exchanges rows 1 and 3 (of 16 lanes) of its first operand with rows 0 and 2 of
+            // its second: with v in both they become (row 0, row 0, row 2, row 2) and (row 1, row 1, row 3,
+            // row 3), whose sum is the sum over each pair of rows.  Written out, waits included, because the
+            // compiler's builtin adds the first result to itself.
+            float t;
+            asm volatile("v_mov_b32 %1, %0\n\ts_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1\n\tv_add_f32 %0, %0, %1"
+                         : "+v"(v), "=&v"(t));
+        }
+    }
+#undef RL_DPP
     return v;
 }
 
@@ -57,15 +72,18 @@ __device__ __forceinline__ void unpack8(uint4_t p, float* x)
     for (int e = 0; e < 4; ++e) { x[2 * e] = Elem<T>::lo(p[e]); x[2 * e + 1] = Elem<T>::hi(p[e]); }
 }
 
-template <typename T>
+template <typename T, int D>
 __global__ __launch_bounds__(256) void qkattn_kernel(QkArgs a)
 {
-    constexpr int D = kQkD, R = kQkRing;
+    constexpr int R = kQkRing;
+    constexpr int LPK = D / 8;               // lanes that share a key
+    constexpr int KPW = 64 / LPK;            // keys in a wave-wide load
+    constexpr int PPI = 4 * KPW;             // positions the workgroup takes per iteration (4 KiB of K and of V)
     __shared__ float s_m[4], s_l[4];
     __shared__ float s_acc[4][D];
     __shared__ int s_last;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int kq = lane >> 4, c = lane & 15;
+    const int kq = lane / LPK, c = lane % LPK;
     const int bh = blockIdx.x / a.SP, sp = blockIdx.x % a.SP;
     const int t0 = sp * a.chunk, t1 = min(a.S, t0 + a.chunk);
 
@@ -81,11 +99,11 @@ __global__ __launch_bounds__(256) void qkattn_kernel(QkArgs a)
         float s = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) s += q[e];
-        const float mu = row_sum16(s) * (1.0f / D);
+        const float mu = group_sum<LPK>(s) * (1.0f / D);
         float v = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) { q[e] -= mu; v = __fmaf_rn(q[e], q[e], v); }
-        const float rinv = 1.0f / __fsqrt_rn(row_sum16(v) * (1.0f / D) + a.eps);
+        const float rinv = 1.0f / __fsqrt_rn(group_sum<LPK>(v) * (1.0f / D) + a.eps);
         float t = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -93,17 +111,17 @@ __global__ __launch_bounds__(256) void qkattn_kernel(QkArgs a)
             qg[e] = qn * gk8[e];
             t = __fmaf_rn(qn, bk8[e], t);
         }
-        qb = row_sum16(t);
+        qb = group_sum<LPK>(t);
     }
 
     const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<u16*>(a.K + size_t(bh) * a.S * D), 0, a.S * D * 2, kQkFlags);
     const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<u16*>(a.V + size_t(bh) * a.S * D), 0, a.S * D * 2, kQkFlags);
-    // iteration i of this wave: position t0 + 16 i + 4 wave + kq (the workgroup reads 4 KiB of K
+    // iteration i of this wave: position t0 + PPI i + KPW wave + kq (the workgroup reads 4 KiB of K
     // and of V, contiguous, per iteration); a position outside the split is not fetched
-    const int nIter = (t1 - t0 + 15) >> 4;   // uniform
-    const int tl = t0 + 4 * wave + kq;
+    const int nIter = (t1 - t0 + PPI - 1) / PPI;   // uniform
+    const int tl = t0 + KPW * wave + kq;
     const int off0 = (tl * D + 8 * c) * 2;
 
     uint4_t kx[R], vx[R];
@@ -111,8 +129,8 @@ __global__ __launch_bounds__(256) void qkattn_kernel(QkArgs a)
     // through the range check, at no memory traffic) and the issues are pinned in program order, so that the compiler
     // can count the loads younger than the one it waits for.
     auto issue = [&](int i, int r) {
-        const int t = tl + 16 * i;
-        const int off = t < t1 ? off0 + i * (16 * D * 2) : kQkOut;
+        const int t = tl + PPI * i;
+        const int off = t < t1 ? off0 + i * (PPI * D * 2) : kQkOut;
         __builtin_amdgcn_sched_barrier(0);
         kx[r] = __builtin_amdgcn_raw_buffer_load_b128(krs, off, 0, 2);
         vx[r] = __builtin_amdgcn_raw_buffer_load_b128(vrs, off, 0, 2);
@@ -132,7 +150,7 @@ __global__ __launch_bounds__(256) void qkattn_kernel(QkArgs a)
         float s1 = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) s1 += x[e];
-        const float mu = row_sum16(s1) * (1.0f / D);
+        const float mu = group_sum<LPK>(s1) * (1.0f / D);
         float s2 = 0.f, dot = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -140,11 +158,11 @@ __global__ __launch_bounds__(256) void qkattn_kernel(QkArgs a)
             s2 = __fmaf_rn(x[e], x[e], s2);
             dot = __fmaf_rn(qg[e], x[e], dot);
         }
-        s2 = row_sum16(s2);
-        dot = row_sum16(dot);
+        s2 = group_sum<LPK>(s2);
+        dot = group_sum<LPK>(dot);
         const float rinv = 1.0f / __fsqrt_rn(s2 * (1.0f / D) + a.eps);
         const float s = __fmaf_rn(dot, rinv, qb) * a.scale_log2e;
-        const bool valid = tl + 16 * i < t1;
+        const bool valid = tl + PPI * i < t1;
         const float m_new = valid ? fmaxf(m, s) : m;
         const float corr = __builtin_amdgcn_exp2f(m - m_new);
         const float p = valid ? __builtin_amdgcn_exp2f(s - m_new) : 0.f;
@@ -163,9 +181,9 @@ __global__ __launch_bounds__(256) void qkattn_kernel(QkArgs a)
         }
     }
 
-    // ---- merge the four key groups of the wave (lanes l, l^16, l^32, l^48)
+    // ---- merge the key groups of the wave (lanes l, l ^ LPK, l ^ 2 LPK, ...)
 #pragma unroll
-    for (int off = 16; off < 64; off <<= 1) {
+    for (int off = LPK; off < 64; off <<= 1) {
         const float m_o = __shfl_xor(m, off, 64), l_o = __shfl_xor(l, off, 64);
         const float m_n = fmaxf(m, m_o);
         const float w_s = __builtin_amdgcn_exp2f(m - m_n), w_o = __builtin_amdgcn_exp2f(m_o - m_n);
@@ -240,10 +258,9 @@ __global__ __launch_bounds__(256) void qkattn_kernel(QkArgs a)
 }
 
 // splits of one (sample, head) -> O; thread j owns output dimension j
-template <typename T>
-__global__ __launch_bounds__(kQkD) void qkattn_combine_kernel(const float* __restrict__ part, u16* __restrict__ O, int SP)
+template <typename T, int D>
+__global__ __launch_bounds__(D) void qkattn_combine_kernel(const float* __restrict__ part, u16* __restrict__ O, int SP)
 {
-    constexpr int D = kQkD;
     const float* src = part + size_t(blockIdx.x) * SP * (D + 2);
     float mm = -1.0e30f;
     for (int s = 0; s < SP; ++s) mm = fmaxf(mm, src[s * (D + 2) + D]);
@@ -334,15 +351,22 @@ static void qk_plan(int64_t BH, int S, int force, int* SP, int* chunk)
     sp = std::min<int64_t>(sp, std::max(1, S / 256));
     if (force > 0) sp = std::min<int64_t>(force, std::max(1, S / 64));
     sp = std::min<int64_t>(sp, 64);
-    int ch = int(((S + sp - 1) / sp + 15) / 16 * 16);
+    int ch = int(((S + sp - 1) / sp + 31) / 32 * 32);
     *chunk = ch;
     *SP = (S + ch - 1) / ch;
 }
 
+// the fast kernel: 16-bit types, D of 64, 128 or 256, and a (sample, head)'s keys short of the byte
+// offset that stands for "not fetched"
+static bool qk_fast(int64_t S, int64_t D, DType dt)
+{
+    return dt != F32 && (D == 64 || D == 128 || D == 256) && S * D * 2 < kQkOut;
+}
+
 size_t qkattn_workspace_bytes(int64_t B, int64_t H, int64_t S, int64_t D, DType dt)
 {
-    if (dt == F32 || D != kQkD) return size_t(B) * H * S * 4;       // the plain kernel's scores
-    return size_t(B) * H * 64 * (kQkD + 2) * 4;                      // room for the most splits there can be
+    if (!qk_fast(S, D, dt)) return size_t(B) * H * S * 4;           // the plain kernel's scores
+    return size_t(B) * H * 64 * (D + 2) * 4;                         // room for the most splits there can be
 }
 
 template <typename T>
@@ -356,13 +380,23 @@ static hipError_t qk_plain_go(const void* Q, const void* K, const void* V, const
     return hipGetLastError();
 }
 
+template <typename T, int D>
+static hipError_t qk_fast_go(const QkArgs& a, int64_t BH, hipStream_t s)
+{
+    qkattn_kernel<T, D><<<dim3((unsigned)(BH * a.SP)), 256, 0, s>>>(a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || a.SP == 1 || a.counter) return e;
+    qkattn_combine_kernel<T, D><<<dim3((unsigned)BH), D, 0, s>>>(a.part, a.O, a.SP);
+    return hipGetLastError();
+}
+
 hipError_t launch_qkattn(const void* Q, const void* K, const void* V, const void* gq, const void* bq,
                          const void* gk, const void* bk, float eps, void* O,
                          int64_t B, int64_t H, int64_t S, int64_t D, DType dt, float* ws, unsigned* counters,
                          int splits, hipStream_t s)
 {
     const int64_t BH = B * H;
-    if (dt == F32 || D != kQkD) {
+    if (!qk_fast(S, D, dt)) {
         if (dt == F32) return qk_plain_go<float>(Q, K, V, gq, bq, gk, bk, O, ws, eps, BH, int(S), int(D), s);
         if (dt == F16) return qk_plain_go<Fp16>(Q, K, V, gq, bq, gk, bk, O, ws, eps, BH, int(S), int(D), s);
         return qk_plain_go<Bf16>(Q, K, V, gq, bq, gk, bk, O, ws, eps, BH, int(S), int(D), s);
@@ -371,18 +405,12 @@ hipError_t launch_qkattn(const void* Q, const void* K, const void* V, const void
     a.Q = (const u16*)Q; a.K = (const u16*)K; a.V = (const u16*)V;
     a.gq = (const u16*)gq; a.bq = (const u16*)bq; a.gk = (const u16*)gk; a.bk = (const u16*)bk;
     a.O = (u16*)O; a.part = ws; a.eps = eps;
-    a.scale_log2e = kLog2e / sqrtf(float(kQkD));
+    a.scale_log2e = kLog2e / sqrtf(float(D));
     a.S = int(S);
     qk_plan(BH, int(S), splits, &a.SP, &a.chunk);
     a.counter = (BH <= kMaxCounters) ? counters : nullptr;
-    dim3 grid((unsigned)(BH * a.SP));
-    if (dt == F16) qkattn_kernel<Fp16><<<grid, 256, 0, s>>>(a);
-    else           qkattn_kernel<Bf16><<<grid, 256, 0, s>>>(a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || a.SP == 1 || a.counter) return e;
-    if (dt == F16) qkattn_combine_kernel<Fp16><<<dim3((unsigned)BH), kQkD, 0, s>>>(ws, (u16*)O, a.SP);
-    else           qkattn_combine_kernel<Bf16><<<dim3((unsigned)BH), kQkD, 0, s>>>(ws, (u16*)O, a.SP);
-    return hipGetLastError();
+    if (dt == F16) return D == 64 ? qk_fast_go<Fp16, 64>(a, BH, s) : D == 128 ? qk_fast_go<Fp16, 128>(a, BH, s) : qk_fast_go<Fp16, 256>(a, BH, s);
+    return D == 64 ? qk_fast_go<Bf16, 64>(a, BH, s) : D == 128 ? qk_fast_go<Bf16, 128>(a, BH, s) : qk_fast_go<Bf16, 256>(a, BH, s);
 }
 
 }  // namespace rmsnl

@@ -51,7 +51,32 @@ def test_fast_path(rl, B, H, S, dtype):
     print(f"{B}x{H}x{S}x128 {dtype}: max|err|/rms = {worst:.3e}")
 
 
-@pytest.mark.parametrize("dtype,D", [("f32", 128), ("f32", 64), ("bf16", 64), ("f16", 80), ("bf16", 256), ("f32", 7)])
+# the same kernel with 8 and with 32 lanes to a key (D = 64: 32 positions per iteration, D = 256: 8):
+# lengths around one iteration, around the ring of six, ragged splits, one and many splits
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("D", [64, 256])
+@pytest.mark.parametrize("B,H,S", [(1, 1, 1), (1, 2, 7), (1, 3, 8), (2, 2, 9), (1, 2, 31), (1, 1, 32), (2, 1, 33),
+                                   (1, 1, 191), (1, 3, 193), (1, 4, 1000), (2, 3, 1031), (1, 32, 4096), (8, 32, 300),
+                                   (3, 5, 4100), (1, 1, 8192)])
+def test_fast_path_other_head_sizes(rl, B, H, S, D, dtype):
+    c = workloads.make_attention(B, H, S, D, dtype, 9200 + B * 7 + H * 3 + S + D)
+    worst = _check(rl, c, dtype, 1e-5, f"qknorm attention {B}x{H}x{S}x{D} {dtype}")
+    print(f"{B}x{H}x{S}x{D} {dtype}: max|err|/rms = {worst:.3e}")
+
+
+@pytest.mark.parametrize("D", [64, 256])
+def test_fast_path_forced_splits(rl, D):
+    """Every split count the tuning knob allows, on a length that leaves a ragged last split."""
+    c = workloads.make_attention(1, 2, 1500, D, "bf16", 9250 + D)
+    try:
+        for splits in (1, 2, 3, 7, 16, 23):
+            rl.rl_set_tuning(0, splits)
+            _check(rl, c, "bf16", 1e-5, f"D = {D}, {splits} splits")
+    finally:
+        rl.rl_set_tuning(0, 0)
+
+
+@pytest.mark.parametrize("dtype,D", [("f32", 128), ("f32", 64), ("bf16", 96), ("f16", 80), ("bf16", 512), ("f32", 7)])
 @pytest.mark.parametrize("B,H,S", [(1, 1, 1), (2, 3, 300), (1, 2, 1025)])
 def test_plain_path(rl, B, H, S, D, dtype):
     c = workloads.make_attention(B, H, S, D, dtype, 9300 + B + H + S + D)
