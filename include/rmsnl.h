@@ -287,6 +287,23 @@ rl_status rl_qknorm_attention(const void* Q, const void* K, const void* V, const
                               int64_t B, int64_t H, int64_t S, int64_t D, rl_dtype dt, void* stream);
 
 /*
+ * The tuner for rl_qknorm_attention (the paper's search over grid dimensions, for this kernel: how many
+ * workgroups share a (sample, head)'s sequence).  Times the library's own rule and every number of
+ * sequence splits that leaves a split at least 64 positions (counts that come out the same launched once),
+ * two warm-up launches and `reps` (1..1000) timed ones each, between HIP events on `stream`, rotating
+ * through n_copies DEVICE copies of K and V (host arrays of device pointers; one copy times the cache-warm
+ * case).  The fastest is remembered for (B H, S, D, dt) and used by later rl_qknorm_attention calls of that
+ * shape unless rl_set_tuning forces a count; rl_autotune_clear forgets it.  *best_splits (may be NULL)
+ * receives the number of splits chosen, *best_us its time per launch.  Shapes that run the plain kernel have
+ * nothing to search: RL_OK, *best_splits = 0.  O is overwritten by every candidate.  Synchronises with the
+ * stream (it waits on its events).
+ */
+rl_status rl_autotune_qknorm(const void* Q, const void* const* K_copies, const void* const* V_copies, int n_copies,
+                             const void* gq, const void* bq, const void* gk, const void* bk, float eps, void* O,
+                             int64_t B, int64_t H, int64_t S, int64_t D, rl_dtype dt, int reps, void* stream,
+                             int* best_splits, float* best_us);
+
+/*
  * The block over a prime field, for the paper's way of certifying a rewrite (random tests over
  * finite fields, Table 3: add, mul, div and sqrt as modular operations): X [M][K], g [K], W [K][N],
  * Y [M][N] are DEVICE arrays of uint32 with entries in [0, p), p a prime in [3, 32749] that does not

@@ -47,6 +47,10 @@ EXPORTS = {
                                              ctypes.c_int, ctypes.c_void_p]),
     "rl_qknorm_attention": (ctypes.c_int, [ctypes.c_void_p] * 7 + [ctypes.c_float, ctypes.c_void_p] +
                             [ctypes.c_int64] * 4 + [ctypes.c_int, ctypes.c_void_p]),
+    "rl_autotune_qknorm": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int] +
+                           [ctypes.c_void_p] * 4 + [ctypes.c_float, ctypes.c_void_p] + [ctypes.c_int64] * 4 +
+                           [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.POINTER(ctypes.c_int),
+                            ctypes.POINTER(ctypes.c_float)]),
     "silu_mul": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                 ctypes.c_int, ctypes.c_void_p]),
     "rl_autotune": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
@@ -395,6 +399,24 @@ def rl_qknorm_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, gq: t
                                      _dev(gk, "gk"), _dev(bk, "bk"), float(eps), _dev(O, "O"), B, H, S, D,
                                      _DTYPES[Q.dtype], _stream(stream)))
     return O
+
+
+def rl_autotune_qknorm(Q: torch.Tensor, Ks, Vs, gq: torch.Tensor, bq: torch.Tensor, gk: torch.Tensor, bk: torch.Tensor,
+                       eps: float, O: torch.Tensor, reps: int = 20, stream=None):
+    """Search over the sequence splits of rl_qknorm_attention; Ks and Vs are lists of device copies of K and V
+    to rotate through.  Returns (splits chosen, microseconds per launch); splits 0 = nothing to search."""
+    B, H, D = Q.shape
+    S = Ks[0].shape[2]
+    if len(Ks) != len(Vs) or not Ks or any(t.shape != (B, H, S, D) or t.dtype != Q.dtype for t in list(Ks) + list(Vs)) \
+            or any(t.shape != (D,) or t.dtype != Q.dtype for t in (gq, bq, gk, bk)) or O.shape != Q.shape:
+        raise ValueError("shape or dtype mismatch")
+    kp = (ctypes.c_void_p * len(Ks))(*[_dev(t, "K copy") for t in Ks])
+    vp = (ctypes.c_void_p * len(Vs))(*[_dev(t, "V copy") for t in Vs])
+    splits, best = ctypes.c_int(0), ctypes.c_float(0.0)
+    _check(lib().rl_autotune_qknorm(_dev(Q, "Q"), kp, vp, len(Ks), _dev(gq, "gq"), _dev(bq, "bq"), _dev(gk, "gk"),
+                                    _dev(bk, "bk"), float(eps), _dev(O, "O"), B, H, S, D, _DTYPES[Q.dtype], int(reps),
+                                    _stream(stream), ctypes.byref(splits), ctypes.byref(best)))
+    return splits.value, float(best.value)
 
 
 def rl_ff_rmsnorm_linear(X: torch.Tensor, g: torch.Tensor, W: torch.Tensor, p: int, reordered: bool,

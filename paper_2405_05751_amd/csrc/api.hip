@@ -37,6 +37,8 @@ Workspace g_lent[kMaxDevices] = {};
 struct Tuned { rl_variant variant; int n_tile, k_split; };
 typedef std::tuple<int, int, int, int, int> TuneKey;
 std::map<TuneKey, Tuned> g_tuned;
+// sequence splits found by rl_autotune_qknorm, by (B H, S, D, dtype)
+std::map<std::tuple<int64_t, int64_t, int, int>, int> g_tuned_qk;
 
 rl_status fail(rl_status st, const char* fmt, const char* a = "", const char* b = "")
 {
@@ -612,6 +614,7 @@ void rl_autotune_clear(void)
 {
     std::lock_guard<std::mutex> lk(g_mu);
     g_tuned.clear();
+    g_tuned_qk.clear();
 }
 
 rl_status rl_ntrans(const void* X, const void* H, const void* alpha, float eps, void* Y,
@@ -627,18 +630,25 @@ rl_status rl_ntrans(const void* X, const void* H, const void* alpha, float eps, 
     return RL_OK;
 }
 
-rl_status rl_qknorm_attention(const void* Q, const void* K, const void* V, const void* gq, const void* bq,
-                              const void* gk, const void* bk, float eps, void* O,
-                              int64_t B, int64_t H, int64_t S, int64_t D, rl_dtype dt, void* stream)
+static rl_status qknorm_check(const void* Q, const void* K, const void* V, const void* gq, const void* bq,
+                              const void* gk, const void* bk, float eps, const void* O,
+                              int64_t B, int64_t H, int64_t S, int64_t D, rl_dtype dt)
 {
     if (!Q || !K || !V || !gq || !bq || !gk || !bk || !O) return fail(RL_ERR_INVALID_ARG, "null pointer");
     if (dt != RL_F16 && dt != RL_BF16 && dt != RL_F32) return fail(RL_ERR_INVALID_ARG, "unknown dtype");
     if (B < 1 || H < 1 || S < 1 || D < 1 || B * H > (int64_t(1) << 24) || S > (int64_t(1) << 22) || D > 4096)
         return fail(RL_ERR_INVALID_ARG, "need 1 <= B*H <= 2^24, 1 <= S <= 2^22, 1 <= D <= 4096");
     if (!std::isfinite(eps) || eps < 0.f) return fail(RL_ERR_INVALID_ARG, "eps must be finite and >= 0");
-    for (const void* ptr : {Q, K, V, gq, bq, gk, bk, (const void*)O})
+    for (const void* ptr : {Q, K, V, gq, bq, gk, bk, O})
         if (!aligned16(ptr)) return fail(RL_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    return RL_OK;
+}
+
+// splits: 0 = the library's rule, else that many sequence splits
+static rl_status qknorm_launch(const void* Q, const void* K, const void* V, const void* gq, const void* bq,
+                               const void* gk, const void* bk, float eps, void* O,
+                               int64_t B, int64_t H, int64_t S, int64_t D, rl_dtype dt, int splits, hipStream_t s)
+{
     float* ws = nullptr;
     unsigned* counters = nullptr;
     const size_t need = qkattn_workspace_bytes(B, H, S, D, DType(dt));
@@ -648,13 +658,86 @@ rl_status rl_qknorm_attention(const void* Q, const void* K, const void* V, const
         counters = static_cast<unsigned*>(w.ptr);
         ws = reinterpret_cast<float*>(static_cast<char*>(w.ptr) + kHeadBytes);
     }
+    hipError_t e = launch_qkattn(Q, K, V, gq, bq, gk, bk, eps, O, B, H, S, D, DType(dt), ws, counters, splits, s);
+    if (e != hipSuccess) return fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+    return RL_OK;
+}
+
+rl_status rl_qknorm_attention(const void* Q, const void* K, const void* V, const void* gq, const void* bq,
+                              const void* gk, const void* bk, float eps, void* O,
+                              int64_t B, int64_t H, int64_t S, int64_t D, rl_dtype dt, void* stream)
+{
+    if (rl_status st = qknorm_check(Q, K, V, gq, bq, gk, bk, eps, O, B, H, S, D, dt)) return st;
     int splits;
     {
         std::lock_guard<std::mutex> lk(g_mu);
         splits = g_k_split;                  // rl_set_tuning(., k_split): sequence splits of this kernel
+        if (splits == 0) {
+            auto it = g_tuned_qk.find(std::make_tuple(B * H, S, int(D), int(dt)));
+            if (it != g_tuned_qk.end()) splits = it->second;
+        }
     }
-    hipError_t e = launch_qkattn(Q, K, V, gq, bq, gk, bk, eps, O, B, H, S, D, DType(dt), ws, counters, splits, s);
-    if (e != hipSuccess) return fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+    return qknorm_launch(Q, K, V, gq, bq, gk, bk, eps, O, B, H, S, D, dt, splits, static_cast<hipStream_t>(stream));
+}
+
+rl_status rl_autotune_qknorm(const void* Q, const void* const* K_copies, const void* const* V_copies, int n_copies,
+                             const void* gq, const void* bq, const void* gk, const void* bk, float eps, void* O,
+                             int64_t B, int64_t H, int64_t S, int64_t D, rl_dtype dt, int reps, void* stream,
+                             int* best_splits, float* best_us)
+{
+    if (!K_copies || !V_copies || n_copies < 1 || n_copies > 4096)
+        return fail(RL_ERR_INVALID_ARG, "need 1 to 4096 copies of K and V");
+    if (reps < 1 || reps > 1000) return fail(RL_ERR_INVALID_ARG, "reps must be in [1, 1000]");
+    for (int i = 0; i < n_copies; ++i)
+        if (rl_status st = qknorm_check(Q, K_copies[i], V_copies[i], gq, bq, gk, bk, eps, O, B, H, S, D, dt)) return st;
+    if (best_splits) *best_splits = 0;
+    if (best_us) *best_us = 0.f;
+    const int automatic = qkattn_splits(B, H, S, D, DType(dt), 0);
+    if (automatic == 0) return RL_OK;                    // the plain kernel has no launch shape to search
+    // every split count that leaves at least 64 positions to a split; counts that round to the same
+    // number of splits are launched once; the library's own rule goes first and wins ties
+    std::vector<int> cands{0};
+    std::vector<int> seen{automatic};
+    for (int sp = 1; sp <= 64; ++sp) {
+        const int got = qkattn_splits(B, H, S, D, DType(dt), sp);
+        if (std::find(seen.begin(), seen.end(), got) != seen.end()) continue;
+        seen.push_back(got);
+        cands.push_back(sp);
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t he = hipEventCreate(&e0);
+    if (he == hipSuccess) he = hipEventCreate(&e1);
+    if (he != hipSuccess) {
+        if (e0) (void)hipEventDestroy(e0);
+        return fail(RL_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(he));
+    }
+    int best = -1;
+    float best_ms = 0.f;
+    rl_status result = RL_OK;
+    for (int sp : cands) {
+        for (int i = 0; i < 2 + reps && result == RL_OK; ++i) {
+            if (i == 2) he = hipEventRecord(e0, s);
+            result = qknorm_launch(Q, K_copies[i % n_copies], V_copies[i % n_copies], gq, bq, gk, bk, eps, O, B, H, S, D, dt, sp, s);
+        }
+        if (result != RL_OK) break;
+        if (he == hipSuccess) he = hipEventRecord(e1, s);
+        if (he == hipSuccess) he = hipEventSynchronize(e1);
+        float ms = 0.f;
+        if (he == hipSuccess) he = hipEventElapsedTime(&ms, e0, e1);
+        if (he != hipSuccess) { result = fail(RL_ERR_HIP, "timing: %s", hipGetErrorString(he)); break; }
+        if (best < 0 || ms < best_ms) { best = sp; best_ms = ms; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (result != RL_OK) return result;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (best > 0) g_tuned_qk[std::make_tuple(B * H, S, int(D), int(dt))] = best;
+        else g_tuned_qk.erase(std::make_tuple(B * H, S, int(D), int(dt)));
+    }
+    if (best_splits) *best_splits = best > 0 ? qkattn_splits(B, H, S, D, DType(dt), best) : automatic;
+    if (best_us) *best_us = best_ms * 1000.f / float(reps);
     return RL_OK;
 }
 

@@ -88,6 +88,8 @@ hipError_t launch_qkattn(const void* Q, const void* K, const void* V, const void
                          int64_t B, int64_t H, int64_t S, int64_t D, DType dt, float* ws, unsigned* counters,
                          int splits, hipStream_t s);
 size_t qkattn_workspace_bytes(int64_t B, int64_t H, int64_t S, int64_t D, DType dt);
+// sequence splits the fast kernel would launch for `splits` (0 = automatic); 0 where the plain kernel runs
+int qkattn_splits(int64_t B, int64_t H, int64_t S, int64_t D, DType dt, int splits);
 hipError_t launch_silu_mul(const void* Z, void* Y, int M, int H, DType dt, hipStream_t s);
 hipError_t launch_interleave_gate_up(const void* W, void* Wi, int64_t K, int H, DType dt, hipStream_t s);
 

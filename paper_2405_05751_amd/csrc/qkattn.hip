@@ -363,6 +363,14 @@ static bool qk_fast(int64_t S, int64_t D, DType dt)
     return dt != F32 && (D == 64 || D == 128 || D == 256) && S * D * 2 < kQkOut;
 }
 
+int qkattn_splits(int64_t B, int64_t H, int64_t S, int64_t D, DType dt, int splits)
+{
+    if (!qk_fast(S, D, dt)) return 0;
+    int SP, chunk;
+    qk_plan(B * H, int(S), splits, &SP, &chunk);
+    return SP;
+}
+
 size_t qkattn_workspace_bytes(int64_t B, int64_t H, int64_t S, int64_t D, DType dt)
 {
     if (!qk_fast(S, D, dt)) return size_t(B) * H * S * 4;           // the plain kernel's scores

@@ -83,6 +83,32 @@ def test_plain_path(rl, B, H, S, D, dtype):
     _check(rl, c, dtype, 1e-5, f"qknorm attention {B}x{H}x{S}x{D} {dtype}")
 
 
+def test_split_tuner(rl):
+    """The tuner over sequence splits: it picks a count, later calls of that shape run it and still match
+    the oracle; a shape of the plain kernel has nothing to search."""
+    import torch
+    for D, B, H, S in ((128, 1, 8, 2048), (64, 2, 3, 1100), (256, 1, 2, 640)):
+        c = workloads.make_attention(B, H, S, D, "bf16", 9800 + D)
+        dev = {k: to_device(v, "bf16") for k, v in c.items()}
+        Ks = [dev["K"], dev["K"].clone()]
+        Vs = [dev["V"], dev["V"].clone()]
+        O = torch.empty_like(dev["Q"])
+        try:
+            splits, us = rl.rl_autotune_qknorm(dev["Q"], Ks, Vs, dev["gq"], dev["bq"], dev["gk"], dev["bk"], 1e-5, O, reps=5)
+            assert 1 <= splits <= max(1, S // 64) and us > 0, (splits, us)
+            print(f"D = {D}, {B}x{H}x{S}: {splits} splits, {us:.1f} us")
+            _check(rl, c, "bf16", 1e-5, f"after tuning, D = {D}")
+        finally:
+            rl.rl_autotune_clear()
+        _check(rl, c, "bf16", 1e-5, f"after forgetting, D = {D}")
+    c = workloads.make_attention(1, 2, 100, 80, "f16", 9810)
+    dev = {k: to_device(v, "f16") for k, v in c.items()}
+    O = torch.empty_like(dev["Q"])
+    assert rl.rl_autotune_qknorm(dev["Q"], [dev["K"]], [dev["V"]], dev["gq"], dev["bq"], dev["gk"], dev["bk"], 1e-5, O)[0] == 0
+    with pytest.raises(rl.RmsnlError):
+        rl.rl_autotune_qknorm(dev["Q"], [dev["K"]], [dev["V"]], dev["gq"], dev["bq"], dev["gk"], dev["bk"], 1e-5, O, reps=0)
+
+
 def test_eps_zero_and_peaked_scores(rl):
     """eps = 0, and keys whose gain makes the scores span a wide range (a sharply peaked softmax)."""
     c = workloads.make_attention(2, 4, 777, 128, "bf16", 9500)
