@@ -30,6 +30,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0        # MI355X dense bf16/fp16 matrix, published (2.5 PFLOP/s)
+MFMA_PEAK_TFLOPS_F32 = 157.3     # MI355X fp32 matrix, published
+
+
+def mfma_peak(dtype):
+    return MFMA_PEAK_TFLOPS_F32 if dtype == "f32" else MFMA_PEAK_TFLOPS
 ROTATE_BYTES = 512 << 20
 MIN_REGION_MS = 50.0             # a timed region is the K-step graph replayed until it lasts at least this long
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), scaled by what the same
@@ -69,12 +74,14 @@ def _time_region(fn_enqueue, torch, min_ms=MIN_REGION_MS):
 
 
 def _workload(name):
-    """One of the five configurations by name, or "MxKxN": a bf16 workload of that shape (same recipe)."""
+    """One of the five configurations by name, or "MxKxN" ("MxKxN:f32", ":f16"): a workload of that shape
+    (same recipe), bf16 unless a type is named."""
     import workloads
     if name in workloads.CONFIG_NAMES:
         return workloads.config(name)
-    M, K, N = (int(v) for v in name.lower().split("x"))
-    return workloads.make(M, K, N, "bf16", 1e-5, 4242 + M + K + N, name=name, outlier_frac=0.05,
+    shape, _, dtype = name.lower().partition(":")
+    M, K, N = (int(v) for v in shape.split("x"))
+    return workloads.make(M, K, N, dtype or "bf16", 1e-5, 4242 + M + K + N, name=name, outlier_frac=0.05,
                           n_check_rows=min(M, 64))
 
 
@@ -196,7 +203,7 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
                    "strips_256B_us": t_strips / steps * 1e3, "strips_256B_GBps": wbytes / (t_strips / steps * 1e-3) / 1e9,
                    "strips_row_parts": parts,
                    "contiguous_us": t_flat / steps * 1e3, "contiguous_GBps": wbytes / (t_flat / steps * 1e-3) / 1e9}
-    elif ceilings and not mem_bound:
+    elif ceilings and not mem_bound and w.dtype != "f32":
         sink = torch.zeros(rl.lib().rl_probe_mfma_sink_floats(), dtype=torch.float32, device="cuda")
         fl = rl.rl_probe_mfma(sink, 2000, tdt)
         torch.cuda.synchronize()
@@ -219,7 +226,7 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
     if mem_bound:
         res["roofline_frac"] = res["TBps"] * 1e3 / HBM_PEAK_GBS
     else:
-        res["roofline_frac"] = res["TFLOPs"] / MFMA_PEAK_TFLOPS
+        res["roofline_frac"] = res["TFLOPs"] / mfma_peak(w.dtype)
     return res, w
 
 
@@ -407,7 +414,7 @@ def main():
     ap.add_argument("--workload", default="decode",
                     help="decode, tiny, qkv, gateup, prefill, ntrans, qknorm (batch 8; qknorm1, qknorm16; a head "
                          "size other than 128 as qknorm:64 or qknorm1:256), "
-                         "or MxKxN (a bf16 workload of that shape)")
+                         "or MxKxN (a bf16 workload of that shape; MxKxN:f32 or :f16 for another type)")
     ap.add_argument("--variant", default="auto")
     ap.add_argument("--no-graph", action="store_true", help="enqueue the timed steps one by one")
     ap.add_argument("--others", action="store_true", help="(default) also time the other four configurations")
@@ -466,8 +473,8 @@ def main():
         return
     steps = args.steps if args.steps is not None else (20 if name == "prefill" else 200)
     if args.steps is None and "x" in name and name != "prefill":
-        M, K, N = (int(v) for v in name.lower().split("x"))
-        steps = 20 if 2.0 * M * K * N > 2e11 else 100
+        M, K, N = (int(v) for v in name.lower().partition(":")[0].split("x"))
+        steps = 20 if 2.0 * M * K * N > (1e10 if name.lower().endswith(":f32") else 2e11) else 100
     res, w = run_workload(rl, torch, name, steps, args.warmup, args.variant, use_graph=not args.no_graph,
                           gated=args.gated, autotune=args.autotune, interleaved=args.interleaved,
                           only_cold=args.only_cold)
@@ -504,7 +511,7 @@ def roofline_of(name, res, w, auto):
     if w.M <= 64:
         roof = {"bound": "hbm", "achieved": res["TBps"] * 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
-        roof = {"bound": "mfma", "achieved": res["TFLOPs"], "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s"}
+        roof = {"bound": "mfma", "achieved": res["TFLOPs"], "peak": mfma_peak(w.dtype), "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     launch = [res["launch"][k] for k in ("variant", "columns", "slabs", "workgroups")]
     rec = MEASURED_TRAFFIC.get(name)
@@ -524,7 +531,7 @@ def roofline_of(name, res, w, auto):
         # one fused kernel is timed beside it and priced the same way
         one = res["us_per_step_one_fused_kernel"]
         roof["form"] = "two kernels: X-hat and 1/rms written once by a first kernel, then the tile product scaled per row"
-        roof["one_fused_kernel"] = {"us_per_launch": one, "achieved": w.flops / one / 1e6, "frac": w.flops / one / 1e6 / MFMA_PEAK_TFLOPS}
+        roof["one_fused_kernel"] = {"us_per_launch": one, "achieved": w.flops / one / 1e6, "frac": w.flops / one / 1e6 / mfma_peak(w.dtype)}
     return roof
 
 

@@ -43,7 +43,8 @@ typedef enum {
 typedef enum { RL_F16 = 0, RL_BF16 = 1, RL_F32 = 2 } rl_dtype;
 
 typedef enum {
-    RL_AUTO = 0,          /* pick by shape: fp32, or K or N not a multiple of 8 (gated: N not of 16): the plain kernel.  Else GEMV
+    RL_AUTO = 0,          /* pick by shape: fp32: its matrix-core kernel, or the plain kernel for what that one does not run.  K or N not
+                             a multiple of 8 (gated: N not of 16): the plain kernel.  Else GEMV
                              for M = 1 and N < 10240, and for M <= 4 while K N <= 6e6; M <= 64 skinny, and up to M = 1024 while
                              ceil(M / 64) K N <= 1.4e8 (0.9e8 for N > 6144 and M > 128); else the two-kernel tile form, or the
                              fused tile kernel when the workspace has no room for it.  A shape remembered by rl_autotune is
@@ -57,9 +58,12 @@ typedef enum {
                              N < 2^25; a W of 2 GiB or more is addressed row by row */
     RL_NAIVE = 4,         /* any shape and type, slow (no matrix cores, no split over workgroups): fp32 arithmetic for the
                              16-bit types, fp64 accumulation for fp32 */
-    RL_MFMA_TILE_PRE = 5  /* M > 64: X (.) g and 1/rms written once by a first kernel (workspace of 2 M K + 4 M bytes),
+    RL_MFMA_TILE_PRE = 5, /* M > 64: X (.) g and 1/rms written once by a first kernel (workspace of 2 M K + 4 M bytes),
                              then the tile kernel as a product scaled per row; with few 256x256 tiles the product is
                              split over K into fp32 partials (up to 64 MiB more) that a third kernel adds up */
+    RL_MFMA_F32 = 6       /* fp32 only, any M, K % 4 == 0 and N % 4 == 0, W below 4 GiB: matrix cores on fp32 operands
+                             (fp32 products and sums, two levels of accumulators), 64 rows x 64 columns per workgroup,
+                             K split over its waves and into 1 to 16 slabs over workgroups; no gated epilogue */
 } rl_variant;
 
 /*
@@ -108,9 +112,9 @@ size_t rl_noalloc_scratch_bytes(void);
  *
  *   struct_size    sizeof(rl_launch_opts), checked
  *   variant        RL_AUTO or a forced variant (then no fallback, as with rl_set_variant)
- *   columns        GEMV: columns of W per workgroup, 64, 128, 256 or 512; skinny: a multiple of 8 up to 128;
+ *   columns        GEMV: columns of W per workgroup, 64, 128, 256 or 512; skinny: a multiple of 8 up to 128; fp32: 64;
  *                  fused tile kernel: 256 (256 x 256 tiles) or 512 (128 x 512 tiles)
- *   slabs          K slabs: GEMV, skinny (1..16), and the product of the two-kernel tile form (1 = unsplit)
+ *   slabs          K slabs: GEMV, skinny and fp32 (1..16), and the product of the two-kernel tile form (1 = unsplit)
  *   waves          fused tile kernel: waves per workgroup, 4 or 8
  *   rem_slabs      two-kernel tile form: K slabs for the tiles left over after the last full round of 256
  *   workspace      DEVICE buffer of workspace_bytes for this call alone (16-byte aligned, its first 256 KiB
@@ -191,7 +195,7 @@ rl_status rl_interleave_gate_up(const void* W, void* Wi, int64_t K, int64_t H, r
 
 /*
  * Variant control (process-wide).  RL_AUTO is the default; the environment variable
- * RL_VARIANT (auto|gemv|skinny|tile|tile_pre|naive) sets the initial value.  A forced variant that
+ * RL_VARIANT (auto|gemv|skinny|tile|tile_pre|naive|f32) sets the initial value.  A forced variant that
  * cannot run a shape makes the call return RL_ERR_UNSUPPORTED instead of falling back.
  * rl_last_variant() reports what the most recent successful call on this thread ran.
  */

@@ -18,9 +18,9 @@ LIB_PATH = os.environ.get("RMSNL_LIB") or os.path.join(_HERE, "librmsnl.so")
 
 RL_OK, RL_ERR_INVALID_ARG, RL_ERR_UNSUPPORTED, RL_ERR_HIP, RL_ERR_WORKSPACE = range(5)
 RL_F16, RL_BF16, RL_F32 = range(3)
-RL_AUTO, RL_GEMV_SPLITK, RL_MFMA_SKINNY, RL_MFMA_TILE, RL_NAIVE, RL_MFMA_TILE_PRE = range(6)
+RL_AUTO, RL_GEMV_SPLITK, RL_MFMA_SKINNY, RL_MFMA_TILE, RL_NAIVE, RL_MFMA_TILE_PRE, RL_MFMA_F32 = range(7)
 VARIANTS = {"auto": RL_AUTO, "gemv": RL_GEMV_SPLITK, "skinny": RL_MFMA_SKINNY,
-            "tile": RL_MFMA_TILE, "naive": RL_NAIVE, "tile_pre": RL_MFMA_TILE_PRE}
+            "tile": RL_MFMA_TILE, "naive": RL_NAIVE, "tile_pre": RL_MFMA_TILE_PRE, "f32": RL_MFMA_F32}
 VARIANT_NAMES = {v: k for k, v in VARIANTS.items()}
 _DTYPES = {torch.float16: RL_F16, torch.bfloat16: RL_BF16, torch.float32: RL_F32}
 

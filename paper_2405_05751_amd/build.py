@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "librmsnl.so")
-SOURCES = ["api.hip", "naive.hip", "gemv.hip", "skinny.hip", "tile.hip", "ntrans.hip", "qkattn.hip"]
+SOURCES = ["api.hip", "naive.hip", "gemv.hip", "skinny.hip", "tile.hip", "f32.hip", "ntrans.hip", "qkattn.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

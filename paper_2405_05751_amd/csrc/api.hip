@@ -57,6 +57,7 @@ void read_env_locked()
     else if (!strcmp(e, "tile")) g_variant = RL_MFMA_TILE;
     else if (!strcmp(e, "tile_pre")) g_variant = RL_MFMA_TILE_PRE;
     else if (!strcmp(e, "naive")) g_variant = RL_NAIVE;
+    else if (!strcmp(e, "f32")) g_variant = RL_MFMA_F32;
     else g_variant = RL_AUTO;
 }
 
@@ -160,7 +161,7 @@ rl_status get_scratch(hipStream_t s, Workspace* out)
 
 rl_variant choose_auto(const Problem& p)
 {
-    if (p.dt == F32) return RL_NAIVE;
+    if (p.dt == F32) return RL_MFMA_F32;     // what it cannot run (gated, odd sizes) falls through to the plain kernel
     if (p.N % 8 != 0 || p.K % 8 != 0) return RL_NAIVE;
     if (p.gated && p.N % 16 != 0) return RL_NAIVE;
     // one row: the GEMV kernel is ahead by 2 to 8 % while W needs a deep split over K to fill the chip
@@ -202,6 +203,7 @@ hipError_t launch_variant(rl_variant v, Problem& p, hipStream_t s, const char** 
     if (v == RL_GEMV_SPLITK) need = gemv_workspace_bytes(p);
     else if (v == RL_MFMA_SKINNY) need = skinny_workspace_bytes(p);
     else if (v == RL_MFMA_TILE_PRE) need = tile_pre_workspace_bytes(p);
+    else if (v == RL_MFMA_F32) need = f32_workspace_bytes(p);
     p.ws_partial = nullptr; p.ws_sumsq = nullptr; p.ws_counter = nullptr;
     if (need) {
         Workspace ws;
@@ -221,6 +223,7 @@ hipError_t launch_variant(rl_variant v, Problem& p, hipStream_t s, const char** 
     case RL_MFMA_TILE:   return launch_tile(p, s, why);
     case RL_MFMA_TILE_PRE: return launch_tile_pre(p, s, why);
     case RL_NAIVE:       return launch_naive(p, s, why);
+    case RL_MFMA_F32:    return launch_f32(p, s, why);
     default:             return hipErrorInvalidValue;
     }
 }
@@ -332,12 +335,12 @@ static rl_status translate_opts(const rl_launch_opts* o, CallOpts* c, Workspace*
     c->variant = RL_AUTO; c->n_tile = 0; c->k_split = 0;
     if (!o) return RL_OK;
     if (o->struct_size != sizeof(rl_launch_opts)) return fail(RL_ERR_INVALID_ARG, "rl_launch_opts.struct_size must be sizeof(rl_launch_opts)");
-    if (o->variant < RL_AUTO || o->variant > RL_MFMA_TILE_PRE) return fail(RL_ERR_INVALID_ARG, "unknown variant");
+    if (o->variant < RL_AUTO || o->variant > RL_MFMA_F32) return fail(RL_ERR_INVALID_ARG, "unknown variant");
     if (o->columns < 0 || o->slabs < 0 || o->waves < 0 || o->rem_slabs < 0)
         return fail(RL_ERR_INVALID_ARG, "launch options must be >= 0");
     c->variant = o->variant;
     switch (o->variant) {
-    case RL_GEMV_SPLITK: case RL_MFMA_SKINNY: c->n_tile = o->columns; c->k_split = o->slabs; break;
+    case RL_GEMV_SPLITK: case RL_MFMA_SKINNY: case RL_MFMA_F32: c->n_tile = o->columns; c->k_split = o->slabs; break;
     case RL_MFMA_TILE: c->n_tile = o->columns; c->k_split = o->waves; break;
     case RL_MFMA_TILE_PRE:
         if (o->slabs) { c->n_tile = 1; c->k_split = o->slabs; }
@@ -525,6 +528,8 @@ static rl_status autotune_core(const void* X, const void* g, const void* const* 
         if (M > 64)                        // two-kernel form: the library's own K split, none, 2 to 16 slabs
             for (int ks : {0, 1, 2, 4, 8, 16}) cands.push_back({RL_MFMA_TILE_PRE, ks ? 1 : 0, ks});
     }
+    if (dt == RL_F32)
+        for (int ks = 0; ks <= 16; ++ks) cands.push_back({RL_MFMA_F32, 0, ks});
     cands.push_back({RL_NAIVE, 0, 0});
 
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -799,7 +804,7 @@ rl_status rl_ff_pairs(const void* X, const void* g, const void* W, void* Y, int6
 
 rl_status rl_set_variant(rl_variant v)
 {
-    if (v < RL_AUTO || v > RL_MFMA_TILE_PRE) return fail(RL_ERR_INVALID_ARG, "unknown variant");
+    if (v < RL_AUTO || v > RL_MFMA_F32) return fail(RL_ERR_INVALID_ARG, "unknown variant");
     std::lock_guard<std::mutex> lk(g_mu);
     g_env_read = true;
     g_variant = v;
@@ -884,6 +889,7 @@ size_t rl_workspace_bytes(int64_t M, int64_t K, int64_t N, rl_dtype dt)
         if (var == RL_GEMV_SPLITK) return gemv_workspace_bytes(q);
         if (var == RL_MFMA_SKINNY) return skinny_workspace_bytes(q);
         if (var == RL_MFMA_TILE_PRE) return tile_pre_workspace_bytes(q);
+        if (var == RL_MFMA_F32) return f32_workspace_bytes(q);
         return 0;
     };
     size_t need = 0;

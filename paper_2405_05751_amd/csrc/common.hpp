@@ -53,6 +53,7 @@ hipError_t launch_rmsnorm(const void* X, const void* g, float eps, void* Xn, int
 hipError_t launch_gemv(const Problem& p, hipStream_t s, const char** why);
 hipError_t launch_skinny(const Problem& p, hipStream_t s, const char** why);
 hipError_t launch_tile(const Problem& p, hipStream_t s, const char** why);
+hipError_t launch_f32(const Problem& p, hipStream_t s, const char** why);
 // two kernels: X-hat and 1/rms per row into the workspace (at ws_partial), then the tile kernel as a
 // plain product of X-hat scaled per row
 hipError_t launch_tile_pre(const Problem& p, hipStream_t s, const char** why);
@@ -62,6 +63,7 @@ void tile_order_at(int b, int tiles_m, int tiles_n, int* tm, int* tn);
 // bytes of partial-B workspace the launch of this problem would use (0 = no split)
 size_t gemv_workspace_bytes(const Problem& p);
 size_t skinny_workspace_bytes(const Problem& p);
+size_t f32_workspace_bytes(const Problem& p);
 
 // Kernels that use more than 64 KiB of dynamic LDS have the limit raised once per device (the
 // attribute belongs to the device's copy of the kernel); one LdsOnce per group of kernels.

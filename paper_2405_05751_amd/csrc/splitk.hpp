@@ -15,7 +15,7 @@ namespace rmsnl {
 constexpr int kSumsqStride = 64;     // floats per (tile, slab) in ws_sumsq: room for 64 rows
 
 struct TailArgs {
-    u16* Y;
+    u16* Y;          // (floats behind it when the kernel's type is float)
     int M, N;        // N: columns of W (= row length of the partial workspace, and of Y unless gated)
     int n_live;      // columns of the tile that belong to it (<= N_TILE)
     int half;        // gated block: the tile's first `half` columns are gate columns hn0.., the next `half` the
@@ -72,8 +72,12 @@ __device__ __forceinline__ void splitk_tail(const TailArgs& a, const float* red,
         float y[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) y[e] = GATED ? Ar::out_gated(v[e], u[e], ri, a.eps) : Ar::out(v[e], ri, a.eps);
-        uint2_t o = {Elem<T>::pack(y[0], y[1]), Elem<T>::pack(y[2], y[3])};
-        *(uint2_t*)(a.Y + size_t(m) * (GATED ? a.H : a.N) + n0 + c) = o;
+        if constexpr (std::is_same<T, float>::value) {      // 4-byte elements: Y points at floats
+            *(float4_t*)((float*)a.Y + size_t(m) * (GATED ? a.H : a.N) + n0 + c) = float4_t{y[0], y[1], y[2], y[3]};
+        } else {
+            uint2_t o = {Elem<T>::pack(y[0], y[1]), Elem<T>::pack(y[2], y[3])};
+            *(uint2_t*)(a.Y + size_t(m) * (GATED ? a.H : a.N) + n0 + c) = o;
+        }
     };
     const float4_t kZero4 = {0.f, 0.f, 0.f, 0.f};
 

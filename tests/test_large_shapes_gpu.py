@@ -98,9 +98,10 @@ def test_four_gib_w_one_fused_tile_kernel_and_plain_product(rl, big_w):
 
 
 def test_more_rows_than_a_grid_dimension(rl):
-    """M > 65535 on the fallback (fp32 type) and on the tile kernels (bf16)."""
+    """M > 65535 on the fp32 kernel (a row block per 64 rows), on the fallback (fp32, N not a multiple of 4) and on
+    the tile kernels (bf16)."""
     import torch
-    for dt, K, N in (("f32", 24, 40), ("bf16", 64, 256)):
+    for dt, K, N in (("f32", 24, 40), ("f32", 24, 42), ("bf16", 64, 256)):
         M = 70001
         w = workloads.make(M, K, N, dt, 1e-5, 9300, n_check_rows=48)
         X, g, W = to_device(w.X, dt), to_device(w.g, dt), to_device(w.W, dt)
@@ -110,7 +111,7 @@ def test_more_rows_than_a_grid_dimension(rl):
         rows = np.concatenate([w.check_rows, [M - 1]])
         Z = oracle.rmsnorm_linear(w.X, w.g, w.W, dt, w.eps, rows=rows)
         compare(to_host_f64(Y[torch.from_numpy(rows).cuda()], dt), Z, dt, f"{M} rows {dt}->{used}")
-        assert used == ("naive" if dt == "f32" else "tile_pre"), used
+        assert used == ("tile_pre" if dt == "bf16" else "f32" if N % 4 == 0 else "naive"), used
 
 
 @pytest.mark.parametrize("M,K,N", [(4, 16384, 256), (3, 28672, 264), (2, 65536, 64)])
