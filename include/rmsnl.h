@@ -63,7 +63,7 @@ typedef enum {
                              split over K into fp32 partials (up to 64 MiB more) that a third kernel adds up */
     RL_MFMA_F32 = 6       /* fp32 only, any M, K % 4 == 0 and N % 4 == 0, W below 4 GiB: matrix cores on fp32 operands
                              (fp32 products and sums, two levels of accumulators), 64 rows x 64 columns per workgroup,
-                             K split over its waves and into 1 to 16 slabs over workgroups; no gated epilogue */
+                             K split over its waves and into 1 to 16 slabs over workgroups */
 } rl_variant;
 
 /*

@@ -33,10 +33,13 @@ struct F32Args {
     int M, K, N;
     float eps, inv_K;
     int k_slab, S, n_tiles, RB;       // rows of W per slab (a multiple of 64), slabs, column tiles, row blocks
+    int H, G;                         // gated block: outputs (N = 2 H) and the layout of W, see gated_col()
     float* ws_partial; float* ws_sumsq; unsigned* counter;
 };
 
-template <int MB, bool FUSED>
+// GATED (the GatedMLP block on top): the tile's first 32 columns are the gate columns of 32 outputs, the
+// next 32 their up columns; the epilogue forms SiLU(gate) * up.  Only the column a lane fetches changes.
+template <int MB, bool FUSED, bool GATED>
 __global__ __launch_bounds__(256) void f32_kernel(F32Args a)
 {
     constexpr int MT = 16 * MB, D = kF32Ring;
@@ -63,7 +66,7 @@ __global__ __launch_bounds__(256) void f32_kernel(F32Args a)
     idx /= pw;
     const int rb = idx % a.RB;
     const int slab = idx / a.RB;
-    const int n0 = tile * kF32Tile, m0 = rb * 64;
+    const int n0 = tile * (GATED ? kF32Tile / 2 : kF32Tile), m0 = rb * 64;   // gated: first output of the tile
     const int Mh = min(a.M - m0, 64);                   // rows of this row block
     const int k0 = slab * a.k_slab, Kend = min(a.K, k0 + a.k_slab);
     const int nIter = (Kend - k0 + 63) >> 6;            // uniform: runs per wave
@@ -74,7 +77,11 @@ __global__ __launch_bounds__(256) void f32_kernel(F32Args a)
         const_cast<float*>(FUSED ? a.g : a.X), 0, a.K * 4, kF32Flags);
     const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float*>(a.W), 0, int(unsigned(Kend) * unsigned(a.N) * 4u), kF32Flags);
-    const bool col_ok = n0 + 4 * c < a.N;               // N % 4 == 0: a lane's four columns lie inside together
+    // N % 4 == 0 (gated: H % 4 == 0): a lane's four columns lie inside together, next to each other in W
+    const bool up = GATED && 4 * c >= kF32Tile / 2;
+    const int hcol = n0 + (up ? 4 * c - kF32Tile / 2 : 4 * c);
+    const bool col_ok = hcol < (GATED ? a.H : a.N);
+    const int wcol = GATED ? gated_col(hcol, up, a.H, a.G) : hcol;
     unsigned xrow[MB];                                  // byte offset of the lane's row inside the row block
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) xrow[mb] = unsigned(16 * mb + c) * unsigned(a.K) * 4u;
@@ -89,7 +96,7 @@ __global__ __launch_bounds__(256) void f32_kernel(F32Args a)
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const unsigned off = (unsigned(kk + t) * unsigned(a.N) + unsigned(n0 + 4 * c)) * 4u;
+            const unsigned off = (unsigned(kk + t) * unsigned(a.N) + unsigned(wcol)) * 4u;
             wv[r][t] = __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(
                 wrs, kin && col_ok ? int(off) : kF32Out, 0, 0));
         }
@@ -167,7 +174,7 @@ __global__ __launch_bounds__(256) void f32_kernel(F32Args a)
             if (q == 0) s_sumsq[wave][mb * 16 + c] = v;
         }
     }
-    // ---- B: element i of accumulator (mb, j) is row 16 mb + 4 q + i, column n0 + 4 c + j
+    // ---- B: element i of accumulator (mb, j) is row 16 mb + 4 q + i, column 4 c + j of the tile
     float* red = smem;                                  // [4][MT][64]
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
@@ -178,11 +185,12 @@ __global__ __launch_bounds__(256) void f32_kernel(F32Args a)
     __syncthreads();
 
     // every row block is a problem of its own to the epilogue: its rows of Y, its share of the workspace
-    TailArgs ta{(u16*)(a.Y + size_t(m0) * a.N), Mh, a.N, kF32Tile, 0, 0, 0, a.eps, a.inv_K, a.S,
+    TailArgs ta{(u16*)(a.Y + size_t(m0) * (GATED ? a.H : a.N)), Mh, a.N, kF32Tile, GATED ? kF32Tile / 2 : 0, a.H, a.G,
+                a.eps, a.inv_K, a.S,
                 a.ws_partial ? a.ws_partial + size_t(rb) * a.S * 64 * a.N : nullptr,
                 a.ws_sumsq ? a.ws_sumsq + size_t(rb) * a.n_tiles * a.S * kSumsqStride : nullptr,
                 a.counter ? a.counter + size_t(rb) * a.n_tiles * kCounterStride : nullptr, nullptr, 0};
-    splitk_tail<float, MT, kF32Tile, FUSED, 4, false>(ta, red, &s_sumsq[0][0], s_rinv, &s_last, tile, slab, n0);
+    splitk_tail<float, MT, kF32Tile, FUSED, 4, GATED>(ta, red, &s_sumsq[0][0], s_rinv, &s_last, tile, slab, n0);
 }
 
 // ------------------------------------------------------------------------------------------- host
@@ -193,7 +201,7 @@ static F32Plan f32_plan(const Problem& p)
     F32Plan pl{};
     pl.ok = false;
     if (p.dt != F32) { pl.why = "the fp32 matrix-core variant handles fp32 only"; return pl; }
-    if (p.gated) { pl.why = "the fp32 matrix-core variant has no gated epilogue"; return pl; }
+    if (p.gated && (!p.fused || p.N % 8 != 0)) { pl.why = "gated block: the fp32 matrix-core variant needs H % 4 == 0"; return pl; }
     if (p.rscale) { pl.why = "the fp32 matrix-core variant takes no row factors"; return pl; }
     if (p.N % 4 != 0 || p.K % 4 != 0) { pl.why = "the fp32 matrix-core variant needs N % 4 == 0 and K % 4 == 0"; return pl; }
     if (p.n_tile != 0 && p.n_tile != kF32Tile) { pl.why = "the fp32 matrix-core variant has 64-column tiles"; return pl; }
@@ -205,7 +213,7 @@ static F32Plan f32_plan(const Problem& p)
     }
     pl.RB = (p.M + 63) / 64;
     pl.MB = pl.RB > 1 ? 4 : (p.M + 15) / 16;
-    pl.n_tiles = (p.N + kF32Tile - 1) / kF32Tile;
+    pl.n_tiles = p.gated ? (p.N / 2 + kF32Tile / 2 - 1) / (kF32Tile / 2) : (p.N + kF32Tile - 1) / kF32Tile;
     const int runs = (p.K + 63) / 64;                    // 64 rows of W: one run for each wave
     const int Mb = std::min(p.M, 64);
     int S = p.k_split;
@@ -214,7 +222,7 @@ static F32Plan f32_plan(const Problem& p)
         const int64_t wgs = int64_t(pl.n_tiles) * pl.RB;
         S = int(std::min<int64_t>(16, std::max<int64_t>(1, (512 + wgs - 1) / wgs)));
         S = std::min(S, std::max(1, runs / 4));
-        while (S > 1 && int64_t(S) * pl.RB * 64 * p.N * 4 > (int64_t(48) << 20)) --S;
+        while (S > 1 && int64_t(S) * pl.RB * Mb * p.N * 4 > (int64_t(48) << 20)) --S;
     }
     S = std::min(S, runs);
     // arrival counters and partial sums of squares exist per (row block, column tile): a launch with more of
@@ -239,18 +247,20 @@ size_t f32_workspace_bytes(const Problem& p)
 {
     F32Plan pl = f32_plan(p);
     if (!pl.ok || pl.S <= 1) return 0;
-    return size_t(pl.RB) * pl.S * 64 * p.N * 4;          // [row block][slab][64 rows][N]
+    return size_t(pl.RB) * pl.S * std::min(p.M, 64) * p.N * 4;    // [row block][slab][rows][N]
 }
 
 template <int MB>
-static hipError_t f32_go(const F32Args& a, bool fused, const F32Plan& pl, hipStream_t s)
+static hipError_t f32_go(const F32Args& a, bool fused, bool gated, const F32Plan& pl, hipStream_t s)
 {
     dim3 grid(unsigned(pl.n_tiles) * pl.S * pl.RB);
     static LdsOnce once;                                 // 64 KiB of dynamic LDS at MB = 4
-    hipError_t e = raise_lds_once(once, {(const void*)f32_kernel<MB, true>, (const void*)f32_kernel<MB, false>}, 80 * 1024);
+    hipError_t e = raise_lds_once(once, {(const void*)f32_kernel<MB, true, false>, (const void*)f32_kernel<MB, false, false>,
+                                         (const void*)f32_kernel<MB, true, true>}, 80 * 1024);
     if (e != hipSuccess) return e;
-    if (fused) f32_kernel<MB, true><<<grid, 256, pl.lds, s>>>(a);
-    else       f32_kernel<MB, false><<<grid, 256, pl.lds, s>>>(a);
+    if (gated)      f32_kernel<MB, true, true><<<grid, 256, pl.lds, s>>>(a);
+    else if (fused) f32_kernel<MB, true, false><<<grid, 256, pl.lds, s>>>(a);
+    else            f32_kernel<MB, false, false><<<grid, 256, pl.lds, s>>>(a);
     return hipGetLastError();
 }
 
@@ -267,13 +277,14 @@ hipError_t launch_f32(const Problem& p, hipStream_t s, const char** why)
     a.X = (const float*)p.X; a.g = (const float*)p.g; a.W = (const float*)p.W; a.Y = (float*)p.Y;
     a.M = p.M; a.K = p.K; a.N = p.N; a.eps = p.eps; a.inv_K = 1.0f / float(p.K);
     a.k_slab = pl.k_slab; a.S = pl.S; a.n_tiles = pl.n_tiles; a.RB = pl.RB;
+    a.H = p.gated ? p.N / 2 : 0; a.G = p.gate_group;
     a.ws_partial = p.ws_partial; a.ws_sumsq = p.ws_sumsq; a.counter = p.ws_counter;
-    const bool fused = p.fused != 0;
+    const bool fused = p.fused != 0, gated = p.gated != 0;
     switch (pl.MB) {
-    case 1:  return f32_go<1>(a, fused, pl, s);
-    case 2:  return f32_go<2>(a, fused, pl, s);
-    case 3:  return f32_go<3>(a, fused, pl, s);
-    default: return f32_go<4>(a, fused, pl, s);
+    case 1:  return f32_go<1>(a, fused, gated, pl, s);
+    case 2:  return f32_go<2>(a, fused, gated, pl, s);
+    case 3:  return f32_go<3>(a, fused, gated, pl, s);
+    default: return f32_go<4>(a, fused, gated, pl, s);
     }
 }
 

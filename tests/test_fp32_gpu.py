@@ -9,7 +9,7 @@ import pytest
 
 import oracle
 import workloads
-from util import compare, to_device, to_host_f64, upload
+from util import compare, compare_gated, to_device, to_host_f64, upload
 
 pytestmark = pytest.mark.gpu
 
@@ -84,8 +84,8 @@ def test_fp32_large_m_sampled_rows(rl):
 
 
 def test_fp32_plain_product_and_fallbacks(rl):
-    """matmul in fp32 takes the same kernel without the norm; sizes it does not run (not multiples of 4) and
-    the gated block go to the plain kernel; forcing it on a 16-bit type is refused."""
+    """matmul in fp32 takes the same kernel without the norm; sizes it does not run (not multiples of 4) go to
+    the plain kernel; forcing it on a 16-bit type is refused."""
     import torch
     w = workloads.make(70, 516, 260, "f32", 1e-5, 4500)
     X, g, W = upload(w)
@@ -104,6 +104,31 @@ def test_fp32_plain_product_and_fallbacks(rl):
     with pytest.raises(rl.RmsnlError) as ei:
         rl.rmsnorm_linear_ex(Xb, gb, Wb, wb.eps, torch.empty(8, 64, dtype=torch.bfloat16, device="cuda"), variant="f32")
     assert ei.value.status == 2
+
+
+@pytest.mark.parametrize("M,K,H", [(1, 64, 4), (3, 516, 36), (16, 1024, 512), (50, 260, 100), (64, 2048, 192),
+                                   (70, 516, 64), (200, 1028, 320)])
+def test_fp32_gated_block(rl, M, K, H):
+    """The gated block in fp32 on the same kernel: a tile is 32 gate and 32 up columns; both layouts of W."""
+    import torch
+    w = workloads.make(M, K, 2 * H, "f32", 1e-5, 4800 + M + H)
+    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, "f32", w.eps)
+    X, g, W = upload(w)
+    Y = rl.rmsnorm_gated_mlp(X, g, W, w.eps)
+    torch.cuda.synchronize()
+    assert rl.rl_last_variant() == "f32"
+    worst = compare_gated(to_host_f64(Y, "f32"), Z, "f32", f"fp32 gated {M}x{K}x2*{H}")
+    print(f"fp32 gated {M}x{K}x2*{H}: worst err/bound {worst:.3f}")
+    for slabs in (2, 5):
+        Ys = rl.rmsnorm_gated_mlp_ex(X, g, W, w.eps, variant="f32", slabs=slabs)
+        torch.cuda.synchronize()
+        compare_gated(to_host_f64(Ys, "f32"), Z, "f32", f"fp32 gated, {slabs} slabs")
+    if H % 64 == 0:
+        Wi = rl.rl_interleave_gate_up(W)
+        Yi = rl.rmsnorm_gated_mlp_interleaved(X, g, Wi, w.eps)
+        torch.cuda.synchronize()
+        assert rl.rl_last_variant() == "f32"
+        assert torch.equal(Yi, Y), "the interleaved layout reads other addresses, not other values"
 
 
 def test_fp32_eps_zero_and_zero_row(rl):

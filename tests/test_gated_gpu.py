@@ -273,11 +273,12 @@ def test_gated_interleaved_launch_shapes(rl, variant, tuning):
 
 
 def test_gated_interleaved_f32_and_bad_h(rl):
-    w = workloads.make(7, 100, 2 * 64, "f32", 1e-5, 7690)
-    Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
-    Y, used, _ = _run_interleaved(rl, w)
-    assert used == "naive"
-    compare_gated(Y, Z, "f32", "gated interleaved f32")
+    for K, expect in ((100, "f32"), (102, "naive")):       # the fp32 kernel, and the plain one where K % 4 != 0
+        w = workloads.make(7, K, 2 * 64, "f32", 1e-5, 7690)
+        Z = oracle.rmsnorm_linear(w.X, w.g, w.W, w.dtype, w.eps)
+        Y, used, _ = _run_interleaved(rl, w)
+        assert used == expect
+        compare_gated(Y, Z, "f32", f"gated interleaved f32, K = {K}")
     w = workloads.make(2, 64, 2 * 96, "bf16", 1e-5, 7691)            # H % 64 != 0
     X, g, W = upload(w)
     with pytest.raises(rl.RmsnlError):

@@ -50,13 +50,15 @@ def _both(rl, w, oracle_rows=None):
     return Y_ref, Y, used_ref, used, to_host_f64(Y[sel], w.dtype), Z
 
 
-# (first call, second and smaller call): GEMV split over K; skinny split over K; fp16; a ragged shape
+# (first call, second and smaller call): GEMV split over K; skinny split over K; fp16; a ragged shape;
+# the fp32 kernel split over K
 PAIRS = [
     ((1, 4096, 4096, "bf16"), (1, 1024, 2048, "bf16")),
     ((16, 4096, 6144, "bf16"), (8, 2048, 2048, "f16")),
     ((64, 2048, 4096, "f16"), (3, 520, 264, "bf16")),
     ((130, 1024, 2056, "bf16"), (33, 4096, 1024, "bf16")),
     ((8, 512, 512, "f16"), (5, 264, 520, "f32")),
+    ((2, 4096, 2048, "f32"), (70, 1028, 132, "f32")),
 ]
 
 
