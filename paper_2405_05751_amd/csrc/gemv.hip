@@ -7,7 +7,10 @@
 //     RPI = 64/LPR lane groups; each of the workgroup's 4*RPI groups owns a run of consecutive W
 //     rows, a lane owns 8 columns, so a wave-wide dwordx4 load covers RPI rows of 16*LPR
 //     contiguous bytes.  Loads are raw buffer loads: rows beyond the slab read as zero with no
-//     branch, and D batches of 8 rows per lane are in flight at any time;
+//     branch, and D batches of 8 rows per lane are in flight at any time.  Up to 4 rows of X the
+//     batches land in an LDS ring by direct loads (each lane reads back the 16 bytes it asked
+//     for: the ring is a queue, not a shared tile), which frees the registers a deep queue would
+//     take and lets two workgroups share a compute unit; above that they land in registers;
 //   * X-hat = X (.) g (fp32).  For M <= 4 a lane group loads the 8 X and g values of its batch
 //     straight into registers next to the W batch (no LDS, no barrier); for M = 8, 16 the slab's
 //     X-hat is staged once in LDS as [m][k].  Either way the same pass adds up the slab's share of
