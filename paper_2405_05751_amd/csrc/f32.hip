@@ -220,9 +220,12 @@ static F32Plan f32_plan(const Problem& p)
     const int Mb = std::min(p.M, 64);
     int S = p.k_split;
     if (S == 0) {
-        // fill the chip twice over while a slab keeps at least 4 runs per wave; the partials fit the library's workspace
+        // as many slabs as still give every workgroup a compute unit of its own (a sweep of 1 to 16 slabs over 14
+        // shapes, M 1 to 128: the best count was the largest with at most 256 workgroups, or within 8 % of it; a
+        // second round of workgroups cost 10 to 40 %), while a slab keeps at least 4 runs per wave and the
+        // partials fit the library's workspace
         const int64_t wgs = int64_t(pl.n_tiles) * pl.RB;
-        S = int(std::min<int64_t>(16, std::max<int64_t>(1, (512 + wgs - 1) / wgs)));
+        S = int(std::min<int64_t>(16, std::max<int64_t>(1, 256 / wgs)));
         S = std::min(S, std::max(1, runs / 4));
         while (S > 1 && int64_t(S) * pl.RB * Mb * p.N * 4 > (int64_t(48) << 20)) --S;
     }

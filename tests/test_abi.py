@@ -97,8 +97,8 @@ def test_workspace_bytes_queries(rl):
     rl.rl_set_variant("auto")
     assert rl.rl_workspace_bytes(0, 8, 8, torch.bfloat16) == 0
     assert rl.rl_workspace_bytes(1, 4097, 4099, torch.float32) == 0      # plain kernel: no workspace
-    # the fp32 kernel splits this shape over K: 8 slabs of M x N fp32 partials behind the 1280 KiB head
-    assert rl.rl_workspace_bytes(1, 4096, 4096, torch.float32) == 1280 * 1024 + 8 * 1 * 4096 * 4
+    # the fp32 kernel splits this shape over K: 4 slabs of M x N fp32 partials behind the 1280 KiB head
+    assert rl.rl_workspace_bytes(1, 4096, 4096, torch.float32) == 1280 * 1024 + 4 * 1 * 4096 * 4
     need = rl.rl_workspace_bytes(1, 4096, 4096, torch.bfloat16)
     assert 0 < need <= rl.rl_workspace_default_bytes()
 
