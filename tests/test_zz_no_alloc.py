@@ -137,3 +137,30 @@ def test_noalloc_rejects_what_does_not_fit(rl):
     Y_ref, Y2, _, _, Yh, Z = _both(rl, w)
     assert torch.equal(Y2.view(torch.int16), Y_ref.view(torch.int16))
     compare(Yh, Z, w.dtype, "noalloc after a rejected call")
+
+
+def test_noalloc_under_graph_capture_replays_bit_for_bit(rl):
+    """What the entry point is for: captured in a HIP graph (after one eager call has looked the array up),
+    replayed with eager work of the ordinary entry point in between; every replay gives the eager bits."""
+    import torch
+    dts = {"bf16": 1, "f32": 2}
+    for M, K, N, dt in ((1, 4096, 4096, "bf16"), (16, 4096, 1024, "bf16"), (2, 4096, 2048, "f32")):
+        w = workloads.make(M, K, N, dt, 1e-5, 9900 + M)
+        X, g, W = upload(w)
+        Y_ref = rl.rmsnorm_linear(X, g, W, w.eps)
+        Y = torch.zeros_like(Y_ref)
+        call = lambda: rl.lib().rmsnorm_linear_noalloc(X.data_ptr(), g.data_ptr(), W.data_ptr(), float(w.eps), Y.data_ptr(),
+                                                       M, K, N, dts[dt], torch.cuda.current_stream().cuda_stream)
+        assert call() == 0, rl.rl_last_error()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            assert call() == 0, rl.rl_last_error()
+        for n in range(3):
+            Y.zero_()
+            other = rl.rmsnorm_linear(X, g, W, w.eps)            # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(Y.view(torch.int16), Y_ref.view(torch.int16)), f"replay {n} of {M}x{K}x{N} {dt} differs"
+            assert torch.equal(other.view(torch.int16), Y_ref.view(torch.int16))
