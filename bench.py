@@ -494,6 +494,11 @@ def main():
                                  use_graph=not args.no_graph)
             r["roofline"] = roofline_of(other, r, wo, args.variant == "auto")
             others.append(r)
+        # the fp32 path (the decode projection's shape, and a matrix-bound one) on its own kernel
+        for other, st in (("1x4096x4096:f32", 200), ("2048x4096x4096:f32", 20)):
+            r, wo = run_workload(rl, torch, other, st, args.warmup, args.variant, use_graph=not args.no_graph, ceilings=False)
+            r["roofline"] = roofline_of(other, r, wo, False)
+            others.append(r)
         # the widened rows of the path, each with its own roofline (no CPU leg: the headline carries one)
         r, wo = run_workload(rl, torch, "gateup", 200, args.warmup, args.variant, use_graph=not args.no_graph,
                              gated=True, interleaved=True, ceilings=False)
