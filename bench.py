@@ -210,6 +210,14 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
         t_m, _, _ = min((_time_region(lambda: rl.rl_probe_mfma(sink, 2000, tdt), torch) for _ in range(3)), key=lambda t: t[0])
         ceiling = {"what": "register-only 32x32x16 matrix-core loop on pseudo-random operands, nothing else",
                    "mfma_loop_TFLOPs": fl / (t_m * 1e-3) / 1e12}
+        # the same call on all-zero operands: same kernels, same launch, no switching activity in the
+        # multipliers -- what the schedule delivers when the matrix cores' power draw does not lower the clock
+        Xz, Wz = torch.zeros_like(X0), torch.zeros_like(W0)
+        zero = make_runner(lambda i: fused_call(Xz, gs[0], Wz, w.eps, Ys[0]))
+        t_z, _, _ = min((_time_region(zero, torch) for _ in range(3)), key=lambda t: t[0])
+        ceiling["same_call_on_zero_operands_us"] = t_z / steps * 1e3
+        ceiling["same_call_on_zero_operands_TFLOPs"] = w.flops / (t_z / steps * 1e-3) / 1e12
+        del Xz, Wz
     res = {
         "workload": name + ("+gate" if gated else "") + ("(interleaved W)" if gated and interleaved else ""), "M": w.M, "K": w.K, "N": w.N, "dtype": w.dtype, "variant": used,
         "launch": {"variant": launch[0], "columns": launch[1], "slabs": launch[2], "workgroups": launch[3]},
