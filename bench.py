@@ -208,8 +208,11 @@ def run_workload(rl, torch, name, steps, warmup, variant, use_graph=True, check=
         fl = rl.rl_probe_mfma(sink, 2000, tdt)
         torch.cuda.synchronize()
         t_m, _, _ = min((_time_region(lambda: rl.rl_probe_mfma(sink, 2000, tdt), torch) for _ in range(3)), key=lambda t: t[0])
-        ceiling = {"what": "register-only 32x32x16 matrix-core loop on pseudo-random operands, nothing else",
-                   "mfma_loop_TFLOPs": fl / (t_m * 1e-3) / 1e12}
+        t_m0, _, _ = min((_time_region(lambda: rl.rl_probe_mfma(sink, 2000, tdt, zero_operands=True), torch) for _ in range(3)),
+                         key=lambda t: t[0])
+        ceiling = {"what": "register-only 32x32x16 matrix-core loop on pseudo-random operands, nothing else; and the same loop on "
+                           "zero operands (no switching activity: the clock the published peak assumes)",
+                   "mfma_loop_TFLOPs": fl / (t_m * 1e-3) / 1e12, "mfma_loop_zero_operands_TFLOPs": fl / (t_m0 * 1e-3) / 1e12}
         # the same call on all-zero operands: same kernels, same launch, no switching activity in the
         # multipliers -- what the schedule delivers when the matrix cores' power draw does not lower the clock
         Xz, Wz = torch.zeros_like(X0), torch.zeros_like(W0)

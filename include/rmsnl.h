@@ -386,11 +386,15 @@ rl_status rl_tile_order(int64_t M, int64_t N, int64_t position, int64_t* tile_ro
  * `bytes` bytes (multiple of 16) used to calibrate memory counters and to measure the
  * achievable streaming rate, and a register-only matrix-core loop of `iters` iterations
  * per wave that reports the achievable MFMA rate (writes one float per lane to `sink`,
- * which must hold rl_probe_mfma_sink_floats() floats).
+ * which must hold rl_probe_mfma_sink_floats() floats).  The loop's operands are pseudo-random values
+ * in (-2, 2); rl_probe_mfma_operands with zero_operands != 0 runs it on zeros: the matrix cores draw
+ * less power without switching activity and the clock stays up, so the two rates bracket what the
+ * multipliers allow on real data and what the published peak assumes.
  */
 rl_status rl_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
 rl_status rl_probe_read(const void* src, size_t bytes, void* sink, void* stream);
 rl_status rl_probe_mfma(void* sink, int iters, rl_dtype dt, void* stream);
+rl_status rl_probe_mfma_operands(void* sink, int iters, rl_dtype dt, int zero_operands, void* stream);
 /*
  * Streaming reads in the launch shapes of the small-M kernels, for a measured ceiling beside their
  * figures.  rl_probe_read_strips: the DEVICE matrix src [rows][row_bytes] (row_bytes a multiple of 256,

@@ -79,6 +79,7 @@ EXPORTS = {
     "rl_probe_copy": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "rl_probe_read": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]),
     "rl_probe_mfma": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]),
+    "rl_probe_mfma_operands": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]),
     "rl_probe_mfma_sink_floats": (ctypes.c_size_t, []),
     "rl_probe_mfma_flops": (ctypes.c_double, [ctypes.c_int]),
     "rl_last_error": (ctypes.c_char_p, []),
@@ -505,11 +506,13 @@ def rl_probe_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
     _check(lib().rl_probe_read(_dev(src, "src"), nbytes, _dev(sink, "sink"), _stream(stream)))
 
 
-def rl_probe_mfma(sink: torch.Tensor, iters: int, dtype: torch.dtype = torch.bfloat16, stream=None) -> float:
-    """Enqueue the matrix-core loop; returns the flops one launch performs."""
+def rl_probe_mfma(sink: torch.Tensor, iters: int, dtype: torch.dtype = torch.bfloat16, stream=None,
+                  zero_operands: bool = False) -> float:
+    """Enqueue the matrix-core loop (on pseudo-random operands, or on zeros); returns the flops one launch performs."""
     if sink.numel() < lib().rl_probe_mfma_sink_floats() or sink.dtype != torch.float32:
         raise ValueError("sink too small")
-    _check(lib().rl_probe_mfma(_dev(sink, "sink"), int(iters), _DTYPES[dtype], _stream(stream)))
+    _check(lib().rl_probe_mfma_operands(_dev(sink, "sink"), int(iters), _DTYPES[dtype], int(bool(zero_operands)),
+                                        _stream(stream)))
     return float(lib().rl_probe_mfma_flops(int(iters)))
 
 

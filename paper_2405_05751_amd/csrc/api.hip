@@ -951,12 +951,17 @@ rl_status rl_probe_read_flat(const void* src, size_t bytes, int workgroups, void
     return e == hipSuccess ? RL_OK : fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
 }
 
-rl_status rl_probe_mfma(void* sink, int iters, rl_dtype dt, void* stream)
+rl_status rl_probe_mfma_operands(void* sink, int iters, rl_dtype dt, int zero_operands, void* stream)
 {
     if (!sink || iters < 1 || (dt != RL_F16 && dt != RL_BF16))
         return fail(RL_ERR_INVALID_ARG, "probe mfma needs a sink, iters >= 1 and a 16-bit type");
-    hipError_t e = launch_probe_mfma(sink, iters, DType(dt), static_cast<hipStream_t>(stream));
+    hipError_t e = launch_probe_mfma(sink, iters, DType(dt), zero_operands != 0, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? RL_OK : fail(RL_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
+}
+
+rl_status rl_probe_mfma(void* sink, int iters, rl_dtype dt, void* stream)
+{
+    return rl_probe_mfma_operands(sink, iters, dt, 0, stream);
 }
 
 const char* rl_last_error(void) { return tl_error; }

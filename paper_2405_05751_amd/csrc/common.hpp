@@ -108,7 +108,7 @@ hipError_t launch_ff_pairs_ref(const void* X, const void* g, const void* W, void
 
 hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t s);
-hipError_t launch_probe_mfma(void* sink, int iters, DType dt, hipStream_t s);
+hipError_t launch_probe_mfma(void* sink, int iters, DType dt, int zero, hipStream_t s);
 hipError_t launch_probe_strips(const void* src, int rows, int row_bytes, int parts, void* sink,
                                unsigned long long* trace, int trace_groups, hipStream_t s);
 hipError_t launch_probe_flat(const void* src, size_t bytes, int workgroups, void* sink, hipStream_t s);

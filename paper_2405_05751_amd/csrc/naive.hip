@@ -508,7 +508,7 @@ template <> __device__ __forceinline__ float16_t mfma32<f16x8_t>(f16x8_t a, f16x
 { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
 
 template <typename V>
-__global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ sink, int iters)
+__global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ sink, int iters, int zero)
 {
     // operands: pseudo-random values in (-2, 2), different per lane, element and accumulator, so the
     // datapath toggles like it does on real activations (constant operands draw less power and clock higher)
@@ -519,8 +519,8 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ sin
         for (int e = 0; e < 8; ++e) {
             uint32_t h = (threadIdx.x * 8u + e) * 2654435761u + j * 0x9e3779b9u + blockIdx.x * 40503u;
             h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
-            af[e] = float(int(h & 0xffff) - 32768) * (1.0f / 16384.0f);
-            bf[e] = float(int(h >> 16) - 32768) * (1.0f / 16384.0f);
+            af[e] = zero ? 0.f : float(int(h & 0xffff) - 32768) * (1.0f / 16384.0f);
+            bf[e] = zero ? 0.f : float(int(h >> 16) - 32768) * (1.0f / 16384.0f);
         }
         a[j] = __builtin_convertvector(af, V);
         b[j] = __builtin_convertvector(bf, V);
@@ -537,10 +537,10 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ sin
     sink[size_t(blockIdx.x) * 256 + threadIdx.x] = r;
 }
 
-hipError_t launch_probe_mfma(void* sink, int iters, DType dt, hipStream_t s)
+hipError_t launch_probe_mfma(void* sink, int iters, DType dt, int zero, hipStream_t s)
 {
-    if (dt == F16) probe_mfma_kernel<f16x8_t><<<kProbeBlocks, 256, 0, s>>>((float*)sink, iters);
-    else           probe_mfma_kernel<bf16x8_t><<<kProbeBlocks, 256, 0, s>>>((float*)sink, iters);
+    if (dt == F16) probe_mfma_kernel<f16x8_t><<<kProbeBlocks, 256, 0, s>>>((float*)sink, iters, zero);
+    else           probe_mfma_kernel<bf16x8_t><<<kProbeBlocks, 256, 0, s>>>((float*)sink, iters, zero);
     return hipGetLastError();
 }
 
